@@ -1,0 +1,198 @@
+"""CPU oracle for the VeLoRA hot path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes loader around ``velora_oracle.cpp`` (plain C++17, double
+precision, written from the paper's Sec. 3.2/3.3 definitions and Algorithm 1).
+Only the tests, the smoke check and the benchmark's ``cpu_baseline`` leg may
+import this package; the product package never does.
+
+Arrays are numpy: float32 storage is ``np.float32``; bfloat16 storage is
+``np.uint16`` bit patterns.  ``M`` is the number of sub-tokens per token and
+``d = D // M`` the sub-token size (the paper writes M for the size).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "velora_oracle.cpp")
+_LIB = os.path.join(_HERE, "libvelora_oracle.so")
+
+DT_F32 = 0
+DT_BF16 = 1
+ERR_DEGENERATE = 6
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with the host compiler (no GPU code)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    L = ctypes.CDLL(_LIB)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    L.velora_oracle_round_bf16.argtypes = [ctypes.c_double]
+    L.velora_oracle_round_bf16.restype = ctypes.c_uint16
+    L.velora_oracle_widen_bf16.argtypes = [ctypes.c_uint16]
+    L.velora_oracle_widen_bf16.restype = ctypes.c_double
+    L.velora_oracle_init_v.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci]
+    L.velora_oracle_init_v.restype = ci
+    L.velora_oracle_compress.argtypes = [vp, ci, vp, i64, i64, i64, vp, vp, ci]
+    L.velora_oracle_compress.restype = None
+    L.velora_oracle_reconstruct.argtypes = [vp, ci, vp, i64, i64, i64, vp, ci]
+    L.velora_oracle_reconstruct.restype = None
+    L.velora_oracle_weight_grad_bruteforce.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, ci]
+    L.velora_oracle_weight_grad_bruteforce.restype = None
+    L.velora_oracle_weight_grad_bruteforce_rows.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, i64, vp, ci]
+    L.velora_oracle_weight_grad_bruteforce_rows.restype = None
+    L.velora_oracle_weight_grad_factored.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, ci]
+    L.velora_oracle_weight_grad_factored.restype = None
+    L.velora_oracle_linear.argtypes = [vp, vp, ci, i64, i64, i64, vp, ci]
+    L.velora_oracle_linear.restype = None
+    _lib = L
+    return L
+
+
+def default_threads() -> int:
+    try:
+        return max(1, len(os.sched_getaffinity(0)))
+    except AttributeError:  # pragma: no cover
+        return max(1, os.cpu_count() or 1)
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return DT_F32
+    if a.dtype == np.uint16:
+        return DT_BF16
+    raise TypeError(f"storage array must be float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _c(a: np.ndarray) -> np.ndarray:
+    if not a.flags["C_CONTIGUOUS"]:
+        raise ValueError("array must be C-contiguous")
+    return a
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _v32(v: np.ndarray, d: int) -> np.ndarray:
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    if v.shape != (d,):
+        raise ValueError(f"v must have shape ({d},), got {v.shape}")
+    return v
+
+
+def round_bf16(x: float) -> int:
+    return int(_load().velora_oracle_round_bf16(float(x)))
+
+
+def widen_bf16(b: int) -> float:
+    return float(_load().velora_oracle_widen_bf16(int(b)))
+
+
+def init_v(X: np.ndarray, M: int, threads: int = 0) -> Tuple[np.ndarray, np.ndarray, int]:
+    """-> (v float32[d], un-normalised mean float64[d], status 0 | 6)."""
+    X = _c(X)
+    N, D = X.shape
+    assert D % M == 0
+    d = D // M
+    mean = np.empty(d, dtype=np.float64)
+    v = np.empty(d, dtype=np.float32)
+    rc = _load().velora_oracle_init_v(_p(X), _dt(X), N, D, M, _p(mean), _p(v), threads or default_threads())
+    return v, mean, int(rc)
+
+
+def compress(X: np.ndarray, v: np.ndarray, M: int, threads: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """-> (S_exact float64[N, M], S_store in X's storage dtype [N, M])."""
+    X = _c(X)
+    N, D = X.shape
+    assert D % M == 0
+    v = _v32(v, D // M)
+    S_exact = np.empty((N, M), dtype=np.float64)
+    S_store = np.empty((N, M), dtype=X.dtype)
+    _load().velora_oracle_compress(_p(X), _dt(X), _p(v), N, D, M, _p(S_exact), _p(S_store),
+                                   threads or default_threads())
+    return S_exact, S_store
+
+
+def reconstruct(S: np.ndarray, v: np.ndarray, D: int, threads: int = 0) -> np.ndarray:
+    """-> Xhat float64[N, D]."""
+    S = _c(S)
+    N, M = S.shape
+    assert D % M == 0
+    v = _v32(v, D // M)
+    Xhat = np.empty((N, D), dtype=np.float64)
+    _load().velora_oracle_reconstruct(_p(S), _dt(S), _p(v), N, D, M, _p(Xhat), threads or default_threads())
+    return Xhat
+
+
+def weight_grad_bruteforce(G: np.ndarray, S: np.ndarray, v: np.ndarray, D: int, threads: int = 0) -> np.ndarray:
+    """dW float64[O, D] = G^T @ ungroup(reconstruct(S, v)), Xhat materialised."""
+    G, S = _c(G), _c(S)
+    N, O = G.shape
+    N2, M = S.shape
+    assert N == N2 and _dt(G) == _dt(S) and D % M == 0
+    v = _v32(v, D // M)
+    dW = np.empty((O, D), dtype=np.float64)
+    _load().velora_oracle_weight_grad_bruteforce(_p(G), _p(S), _p(v), N, O, D, M, _dt(G), _p(dW),
+                                                 threads or default_threads())
+    return dW
+
+
+def weight_grad_bruteforce_rows(G: np.ndarray, S: np.ndarray, v: np.ndarray, D: int,
+                                rows: Sequence[int], threads: int = 0) -> np.ndarray:
+    """Rows ``rows`` of the brute-force dW, float64[len(rows), D]."""
+    G, S = _c(G), _c(S)
+    N, O = G.shape
+    N2, M = S.shape
+    assert N == N2 and _dt(G) == _dt(S) and D % M == 0
+    v = _v32(v, D // M)
+    r = np.ascontiguousarray(rows, dtype=np.int64)
+    assert r.ndim == 1 and (r >= 0).all() and (r < O).all()
+    out = np.empty((r.shape[0], D), dtype=np.float64)
+    _load().velora_oracle_weight_grad_bruteforce_rows(_p(G), _p(S), _p(v), N, O, D, M, _dt(G), _p(r),
+                                                      r.shape[0], _p(out), threads or default_threads())
+    return out
+
+
+def weight_grad_factored(G: np.ndarray, S: np.ndarray, v: np.ndarray, D: int,
+                         threads: int = 0, want_dW: bool = True) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    """-> (T float64[O, M], dW float64[O, D] or None)."""
+    G, S = _c(G), _c(S)
+    N, O = G.shape
+    N2, M = S.shape
+    assert N == N2 and _dt(G) == _dt(S) and D % M == 0
+    v = _v32(v, D // M)
+    T = np.empty((O, M), dtype=np.float64)
+    dW = np.empty((O, D), dtype=np.float64) if want_dW else None
+    _load().velora_oracle_weight_grad_factored(_p(G), _p(S), _p(v), N, O, D, M, _dt(G), _p(T), _p(dW),
+                                               threads or default_threads())
+    return T, dW
+
+
+def linear(X: np.ndarray, W: np.ndarray, threads: int = 0) -> np.ndarray:
+    """Y float64[N, O] = X @ W^T with W stored [O, D]."""
+    X, W = _c(X), _c(W)
+    N, D = X.shape
+    O, D2 = W.shape
+    assert D == D2 and _dt(X) == _dt(W)
+    Y = np.empty((N, O), dtype=np.float64)
+    _load().velora_oracle_linear(_p(X), _p(W), _dt(X), N, D, O, _p(Y), threads or default_threads())
+    return Y

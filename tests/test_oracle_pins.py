@@ -1,0 +1,405 @@
+"""Pins for the CPU oracle: everything here runs without a GPU.
+
+The oracle (oracle/velora_oracle.cpp) is checked against things other than
+itself: a hand-worked example (tests/golden/worked_example_sec3_2.txt), closed
+forms, projector invariants that follow from |v| = 1 (paper Sec. 3.2), the
+gradient-similarity identity of the appendix ("Gradient Similarity"), the
+no-sub-token special case of Sec. 3.3 ("Connection to parameter efficient
+fine-tuning"), special cases that reduce to a gather or to a textbook matrix
+product, and pure-Python brute force on tiny inputs.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_example_sec3_2.txt")
+
+
+def _read_golden():
+    out, name = {}, None
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            try:
+                row = [float(t) for t in line.split()]
+                out[name].append(row)
+            except ValueError:
+                name = line
+                out[name] = []
+    return {k: np.array(v, dtype=np.float64) for k, v in out.items()}
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _rand(shape, seed, dtype=wl.F32, sigma=1.0):
+    return wl.random_tensor(shape[0], shape[1], dtype, seed, sigma=sigma)
+
+
+# ------------------------------------------------------------------ bf16 format
+class TestBf16Format:
+    def test_roundtrip_all_bit_patterns(self):
+        for b in range(0, 1 << 16, 1):
+            exp = (b >> 7) & 0xFF
+            if exp == 0xFF and (b & 0x7F):      # NaN payloads are not preserved
+                continue
+            assert oracle.round_bf16(oracle.widen_bf16(b)) == b
+
+    def test_ties_to_even_and_single_rounding(self):
+        one = 0x3F80
+        assert oracle.round_bf16(1.0 + 2.0 ** -8) == one             # tie -> even (down)
+        assert oracle.round_bf16(1.0 + 3 * 2.0 ** -8) == one + 2      # tie -> even (up)
+        assert oracle.round_bf16(1.0 + 2.0 ** -8 + 2.0 ** -30) == one + 1
+        # would be a tie after a first rounding to float32; one rounding from
+        # double must see that it lies above the tie
+        assert oracle.round_bf16(1.0 + 2.0 ** -8 + 2.0 ** -40) == one + 1
+        assert oracle.round_bf16(-(1.0 + 2.0 ** -8)) == 0x8000 | one
+
+    def test_range_ends(self):
+        assert oracle.round_bf16(0.0) == 0
+        assert oracle.round_bf16(-0.0) == 0x8000
+        assert oracle.round_bf16(1e40) == 0x7F80
+        assert oracle.round_bf16(-1e40) == 0xFF80
+        big = oracle.widen_bf16(0x7F7F)                               # largest finite
+        assert oracle.round_bf16(big) == 0x7F7F
+        assert oracle.round_bf16(big * (1 + 2.0 ** -8)) == 0x7F80     # more than half an ulp above it
+        assert oracle.round_bf16(big * (1 + 2.0 ** -10)) == 0x7F7F    # less than half an ulp above it
+        assert oracle.round_bf16(2.0 ** -133) == 1                    # smallest subnormal
+        assert oracle.round_bf16(2.0 ** -134) == 0                    # tie -> even (0)
+        assert oracle.round_bf16(2.0 ** -126) == 0x0080               # smallest normal
+
+    def test_agrees_with_independent_bit_trick(self):
+        a = np.random.default_rng(3).standard_normal(20000).astype(np.float32) * 37.0
+        want = wl.f32_to_bf16_bits(a)
+        got = np.array([oracle.round_bf16(float(x)) for x in a], dtype=np.uint16)
+        assert (got == want).all()
+
+
+# ------------------------------------------------------------------ worked example
+class TestWorkedExample:
+    def test_compress_reconstruct_weight_grad_init(self):
+        g = _read_golden()
+        v = _f32(g["v"][0])
+        X = _f32(g["X"])
+        G = _f32(g["G"])
+        S_exact, S_store = oracle.compress(X, v, M=2)
+        np.testing.assert_allclose(S_exact, g["S"], rtol=0, atol=2e-7)
+        np.testing.assert_allclose(S_store, g["S"], rtol=0, atol=5e-7)
+        Xhat = oracle.reconstruct(S_store, v, D=4)
+        np.testing.assert_allclose(Xhat, g["Xhat"], rtol=0, atol=1e-6)
+        dW = oracle.weight_grad_bruteforce(G, S_store, v, D=4)
+        np.testing.assert_allclose(dW, g["dW"], rtol=0, atol=3e-6)
+        T, dWf = oracle.weight_grad_factored(G, S_store, v, D=4)
+        np.testing.assert_allclose(dWf, g["dW"], rtol=0, atol=3e-6)
+        vi, mean, rc = oracle.init_v(X, M=2)
+        assert rc == 0
+        np.testing.assert_allclose(mean, g["mean"][0], rtol=0, atol=1e-15)
+        np.testing.assert_allclose(vi, g["v_init"][0], rtol=0, atol=6e-8)
+
+
+# ------------------------------------------------------------------ compress / reconstruct
+class TestCompressReconstruct:
+    @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+    def test_gather_is_bit_exact(self, dtype):
+        # v = e_j turns compress into a gather: pins group()'s indexing with no arithmetic.
+        N, D, d = 7, 48, 8
+        M = D // d
+        X = _rand((N, D), 11, dtype)
+        for j in (0, 3, 7):
+            v = np.zeros(d, dtype=np.float32)
+            v[j] = 1.0
+            S_exact, S_store = oracle.compress(X, v, M)
+            want = X.reshape(N, M, d)[:, :, j]
+            assert (S_store == want).all()
+            assert (S_exact == wl.to_f64(want, dtype)).all()
+
+    def test_exact_on_multiples_of_v(self):
+        # sub-token k = c_k * v with v = (1/4,...,1/4) in R^16 (unit length) and
+        # integer c_k: every quantity is exactly representable.
+        N, M, d = 5, 3, 16
+        v = np.full(d, 0.25, dtype=np.float32)
+        c = np.arange(-7, 8, dtype=np.float64).reshape(N, M)
+        X = _f32((c[:, :, None] * v[None, None, :].astype(np.float64)).reshape(N, M * d))
+        S_exact, S_store = oracle.compress(X, v, M)
+        assert (S_exact == c).all()
+        assert (S_store == c).all()
+        Xhat = oracle.reconstruct(S_store, v, D=M * d)
+        assert (Xhat == X.astype(np.float64)).all()
+
+    def test_sign_and_d_equals_one(self):
+        X = _rand((9, 10), 5)
+        for sgn in (1.0, -1.0):
+            S_exact, S_store = oracle.compress(X, np.array([sgn], dtype=np.float32), M=10)
+            assert (S_store == sgn * X).all()
+            Xhat = oracle.reconstruct(S_store, np.array([sgn], dtype=np.float32), D=10)
+            assert (Xhat == X.astype(np.float64)).all()
+
+    def test_against_python_loops(self):
+        N, D, d = 3, 6, 2
+        M = D // d
+        X = _rand((N, D), 21)
+        v = wl.random_unit_v(d, 4)
+        S_exact, _ = oracle.compress(X, v, M)
+        for n in range(N):
+            for g in range(M):
+                acc = 0.0
+                for j in range(d):
+                    acc += float(X[n, g * d + j]) * float(v[j])
+                assert S_exact[n, g] == pytest.approx(acc, rel=1e-15, abs=1e-300)
+
+    @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+    def test_matches_reshape_matvec(self, dtype):
+        N, D, d = 33, 96, 32
+        M = D // d
+        X = _rand((N, D), 8, dtype)
+        v = wl.random_unit_v(d, 2)
+        S_exact, S_store = oracle.compress(X, v, M)
+        want = (wl.to_f64(X, dtype).reshape(N * M, d) @ v.astype(np.float64)).reshape(N, M)
+        np.testing.assert_allclose(S_exact, want, rtol=1e-13, atol=1e-14)
+        # the stored value is the exact value rounded once to the storage dtype
+        if dtype == wl.F32:
+            assert (S_store == S_exact.astype(np.float32)).all()
+        else:
+            ulp = np.abs(want) * 2.0 ** -8 + 1e-30
+            assert (np.abs(wl.to_f64(S_store, dtype) - want) <= ulp).all()
+
+    def test_projector_invariants(self):
+        N, D, d = 17, 64, 16
+        M = D // d
+        X = _rand((N, D), 13)
+        v = wl.random_unit_v(d, 9)
+        vd = v.astype(np.float64)
+        vn2 = float(vd @ vd)                      # 1 up to float32 rounding of v
+        S, _ = oracle.compress(X, v, M)
+        z = X.astype(np.float64).reshape(N * M, d)
+        s = S.reshape(-1)
+        # contraction (Cauchy-Schwarz with |v| = 1)
+        assert (np.abs(s) <= np.linalg.norm(z, axis=1) * math.sqrt(vn2) * (1 + 1e-12)).all()
+        # reconstruct from exact S (float64 S given as f32 would round): use numpy outer
+        S32 = _f32(S)
+        Xhat = oracle.reconstruct(S32, v, D).reshape(N * M, d)
+        s32 = S32.astype(np.float64).reshape(-1)
+        # residual orthogonal to v, Pythagoras, |Xhat| <= |X|
+        res = z - Xhat
+        np.testing.assert_allclose(res @ vd, s - s32 * vn2, atol=1e-12)
+        assert np.linalg.norm(Xhat) <= np.linalg.norm(z) * (1 + 1e-6)
+        np.testing.assert_allclose((z * z).sum(1), s * s + ((z - s[:, None] * vd) ** 2).sum(1), rtol=1e-6)
+        # idempotence: compress(reconstruct(S)) = S * |v|^2
+        S2, _ = oracle.compress(_f32(Xhat.reshape(N, D)), v, M)
+        np.testing.assert_allclose(S2.reshape(-1), s32 * vn2, rtol=0, atol=3e-7)
+        # appendix "Gradient Similarity": sim(proj z_i, proj z_j) = (v.z_i)(v.z_j)
+        gram = Xhat @ Xhat.T
+        np.testing.assert_allclose(gram, np.outer(s32, s32) * vn2, rtol=1e-12, atol=1e-12)
+
+    def test_linearity(self):
+        N, D, d = 6, 32, 8
+        A = _rand((N, D), 1)
+        B = _rand((N, D), 2)
+        v = wl.random_unit_v(d, 3)
+        # integer combinations of float32 stay exactly representable only if we
+        # form the combination in float64 and compare against float64 sums
+        SA, _ = oracle.compress(A, v, D // d)
+        SB, _ = oracle.compress(B, v, D // d)
+        C = _f32(2.0 * A.astype(np.float64) - 0.5 * B.astype(np.float64))
+        SC, _ = oracle.compress(C, v, D // d)
+        np.testing.assert_allclose(SC, 2.0 * SA - 0.5 * SB, rtol=0, atol=2e-6)
+
+    def test_reconstruct_python_loops(self):
+        N, M, d = 2, 3, 4
+        S = _rand((N, M), 17)
+        v = wl.random_unit_v(d, 6)
+        Xhat = oracle.reconstruct(S, v, M * d)
+        for n in range(N):
+            for g in range(M):
+                for j in range(d):
+                    assert Xhat[n, g * d + j] == float(S[n, g]) * float(v[j])
+
+
+# ------------------------------------------------------------------ init_v
+class TestInitV:
+    def test_constant_subtokens(self):
+        d, M, N = 8, 4, 5
+        u = np.array([1, -2, 3, 0.5, 0, 4, -1, 2], dtype=np.float64)
+        X = _f32(np.tile(u, (N, M)))
+        v, mean, rc = oracle.init_v(X, M)
+        assert rc == 0
+        np.testing.assert_allclose(mean, u, rtol=0, atol=1e-15)
+        np.testing.assert_allclose(v, u / np.linalg.norm(u), rtol=0, atol=6e-8)
+        # natural sign is kept
+        v2, _, _ = oracle.init_v(-X, M)
+        np.testing.assert_allclose(v2, -u / np.linalg.norm(u), rtol=0, atol=6e-8)
+
+    def test_mean_runs_over_tokens_and_groups(self):
+        # sub-token (n, g) = (n + 1) * (g + 1) * u  ->  mean = mean_n(n+1) * mean_g(g+1) * u
+        d, M, N = 4, 3, 5
+        u = np.array([1.0, 2.0, -1.0, 0.5])
+        X = np.zeros((N, M * d))
+        for n in range(N):
+            for g in range(M):
+                X[n, g * d:(g + 1) * d] = (n + 1) * (g + 1) * u
+        v, mean, rc = oracle.init_v(_f32(X), M)
+        np.testing.assert_allclose(mean, 3.0 * 2.0 * u, rtol=1e-15)
+        np.testing.assert_allclose(np.linalg.norm(v.astype(np.float64)), 1.0, atol=1e-7)
+
+    @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+    def test_matches_column_mean_and_permutation_invariance(self, dtype):
+        N, D, d = 40, 96, 16
+        M = D // d
+        X = _rand((N, D), 31, dtype)
+        X64 = wl.to_f64(X, dtype)
+        v, mean, rc = oracle.init_v(X, M)
+        want = X64.reshape(N * M, d).mean(axis=0)
+        np.testing.assert_allclose(mean, want, rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(v, want / np.linalg.norm(want), atol=6e-8)
+        assert abs(np.linalg.norm(v.astype(np.float64)) - 1.0) < 2e-7
+        perm = np.random.default_rng(0).permutation(N)
+        v2, mean2, _ = oracle.init_v(np.ascontiguousarray(X[perm]), M)
+        np.testing.assert_allclose(mean2, mean, rtol=1e-12, atol=1e-16)
+        gperm = np.random.default_rng(1).permutation(M)
+        Xg = np.ascontiguousarray(X.reshape(N, M, d)[:, gperm, :].reshape(N, D))
+        _, mean3, _ = oracle.init_v(Xg, M)
+        np.testing.assert_allclose(mean3, mean, rtol=1e-12, atol=1e-16)
+
+    def test_degenerate(self):
+        d, M = 4, 2
+        v, mean, rc = oracle.init_v(np.zeros((3, M * d), dtype=np.float32), M)
+        assert rc == oracle.ERR_DEGENERATE
+        assert (v == np.float32(0.5)).all()
+        u = np.array([1.0, 2.0, 3.0, 4.0])
+        X = _f32(np.concatenate([u, -u])[None, :])        # the two sub-tokens cancel
+        v, mean, rc = oracle.init_v(X, M)
+        assert rc == oracle.ERR_DEGENERATE and (v == np.float32(0.5)).all()
+        Xn = np.ones((2, M * d), dtype=np.float32)
+        Xn[1, 3] = np.inf
+        v, _, rc = oracle.init_v(Xn, M)
+        assert rc == oracle.ERR_DEGENERATE and (v == np.float32(0.5)).all()
+
+
+# ------------------------------------------------------------------ weight gradient
+class TestWeightGrad:
+    @pytest.mark.parametrize("N,O,D,d,dtype", [
+        (5, 3, 8, 2, wl.F32), (9, 7, 12, 4, wl.F32), (16, 5, 6, 6, wl.BF16),
+        (11, 4, 10, 1, wl.BF16), (33, 6, 24, 8, wl.F32),
+    ])
+    def test_factored_equals_bruteforce(self, N, O, D, d, dtype):
+        M = D // d
+        G = _rand((N, O), 40 + N, dtype, sigma=0.02)
+        S = _rand((N, M), 50 + N, dtype)
+        v = wl.random_unit_v(d, N)
+        dWb = oracle.weight_grad_bruteforce(G, S, v, D)
+        T, dWf = oracle.weight_grad_factored(G, S, v, D)
+        np.testing.assert_allclose(dWf, dWb, rtol=1e-12, atol=1e-16)
+        rows = [O - 1, 0, O // 2]
+        dWr = oracle.weight_grad_bruteforce_rows(G, S, v, D, rows)
+        np.testing.assert_allclose(dWr, dWb[rows], rtol=1e-14, atol=1e-18)
+
+    def test_against_python_loops_nonsquare(self):
+        # N, O, D all different: a transposed operand or swapped index cannot pass
+        N, O, D, d = 4, 3, 6, 3
+        M = D // d
+        G = _rand((N, O), 3)
+        S = _rand((N, M), 4)
+        v = wl.random_unit_v(d, 5)
+        dW = oracle.weight_grad_bruteforce(G, S, v, D)
+        assert dW.shape == (O, D)
+        for o in range(O):
+            for c in range(D):
+                acc = 0.0
+                for n in range(N):
+                    xhat = float(S[n, c // d]) * float(v[c % d])
+                    acc += float(G[n, o]) * xhat
+                assert dW[o, c] == pytest.approx(acc, rel=1e-14, abs=1e-300)
+
+    def test_single_one_in_G_copies_a_reconstructed_token(self):
+        N, O, D, d = 6, 5, 8, 4
+        S = _rand((N, D // d), 9)
+        v = wl.random_unit_v(d, 1)
+        Xhat = oracle.reconstruct(S, v, D)
+        for (n, o) in [(0, 0), (5, 4), (2, 3)]:
+            G = np.zeros((N, O), dtype=np.float32)
+            G[n, o] = 1.0
+            for fn in (oracle.weight_grad_bruteforce,
+                       lambda *a: oracle.weight_grad_factored(*a)[1]):
+                dW = fn(G, S, v, D)
+                assert (dW[o] == Xhat[n]).all()
+                mask = np.ones(O, dtype=bool)
+                mask[o] = False
+                assert (dW[mask] == 0).all()
+
+    def test_no_subtoken_case_is_rank_one(self):
+        # Sec. 3.3 "Connection to parameter efficient fine-tuning": with d = D the
+        # gradient is (G^T X v) v^T.
+        N, O, D = 12, 5, 16
+        X = _rand((N, D), 77)
+        G = _rand((N, O), 78, sigma=0.02)
+        v = wl.random_unit_v(D, 7)
+        S_exact, S_store = oracle.compress(X, v, M=1)
+        dW = oracle.weight_grad_bruteforce(G, S_store, v, D)
+        want = np.outer(G.astype(np.float64).T @ S_store.astype(np.float64)[:, 0], v.astype(np.float64))
+        np.testing.assert_allclose(dW, want, rtol=1e-12, atol=1e-18)
+        assert np.linalg.matrix_rank(dW) == 1
+        # and S itself is X v
+        np.testing.assert_allclose(S_exact[:, 0], X.astype(np.float64) @ v.astype(np.float64), rtol=1e-13)
+
+    def test_d_equals_one_is_dense_product(self):
+        N, O, D = 10, 4, 7
+        X = _rand((N, D), 5)
+        G = _rand((N, O), 6)
+        one = np.ones(1, dtype=np.float32)
+        _, S = oracle.compress(X, one, M=D)
+        for dW in (oracle.weight_grad_bruteforce(G, S, one, D), oracle.weight_grad_factored(G, S, one, D)[1]):
+            np.testing.assert_allclose(dW, G.astype(np.float64).T @ X.astype(np.float64), rtol=1e-13, atol=1e-16)
+
+    def test_block_structure_and_linearity(self):
+        N, O, D, d = 14, 6, 24, 8
+        M = D // d
+        G1 = _rand((N, O), 1, sigma=0.1)
+        G2 = _rand((N, O), 2, sigma=0.1)
+        S = _rand((N, M), 3)
+        v = wl.random_unit_v(d, 8)
+        vd = v.astype(np.float64)
+        T, dW = oracle.weight_grad_factored(G1, S, v, D)
+        blocks = dW.reshape(O, M, d)
+        # every d-wide block of a row is T[o, g] * v, so rank(dW) <= M and
+        # projecting the rows back onto v returns T (times |v|^2)
+        np.testing.assert_allclose(blocks, T[:, :, None] * vd[None, None, :], rtol=1e-15)
+        np.testing.assert_allclose(blocks @ vd, T * float(vd @ vd), rtol=1e-12, atol=1e-18)
+        assert np.linalg.matrix_rank(dW) <= M
+        np.testing.assert_allclose(T, G1.astype(np.float64).T @ S.astype(np.float64), rtol=1e-12, atol=1e-18)
+        G3 = _f32(G1.astype(np.float64) + 2.0 * G2.astype(np.float64))
+        dW1 = oracle.weight_grad_bruteforce(G1, S, v, D)
+        dW2 = oracle.weight_grad_bruteforce(G2, S, v, D)
+        dW3 = oracle.weight_grad_bruteforce(G3, S, v, D)
+        np.testing.assert_allclose(dW3, dW1 + 2.0 * dW2, rtol=0, atol=1e-6)
+
+    def test_config1_tiny_bruteforce_vs_factored(self):
+        # BASELINE configuration 1: X[256,64] ~ N(0,1) seed 0, M = 4 (d = 16),
+        # G ~ N(0, 0.02), v = normalised mean of X's sub-tokens.
+        sh = wl.shape_by_name("cfg1_tiny")
+        X, G = wl.make_X(sh), wl.make_G(sh)
+        v, _, rc = oracle.init_v(X, sh.M)
+        assert rc == 0
+        _, S = oracle.compress(X, v, sh.M)
+        dWb = oracle.weight_grad_bruteforce(G, S, v, sh.D)
+        _, dWf = oracle.weight_grad_factored(G, S, v, sh.D)
+        np.testing.assert_allclose(dWf, dWb, rtol=1e-11, atol=1e-16)
+        # |Xhat| <= |X|
+        Xhat = oracle.reconstruct(S, v, sh.D)
+        assert np.linalg.norm(Xhat) <= np.linalg.norm(X.astype(np.float64))
+
+
+class TestLinear:
+    @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+    def test_matches_matmul(self, dtype):
+        X = _rand((9, 20), 1, dtype)
+        W = _rand((7, 20), 2, dtype)
+        Y = oracle.linear(X, W)
+        np.testing.assert_allclose(Y, wl.to_f64(X, dtype) @ wl.to_f64(W, dtype).T, rtol=1e-13, atol=1e-15)
