@@ -1,0 +1,139 @@
+/*
+ * libvelora -- C ABI of the MI355X (gfx950) implementation of the VeLoRA hot
+ * path: rank-1 sub-token compression of a linear layer's input activations and
+ * the weight gradient built on it (paper Sec. 3.2 "VeLoRA", Sec. 3.3 "Cheap
+ * initialisation strategies", Algorithm 1).
+ *
+ * Symbols
+ *   N  tokens (batch x sequence, flattened)      D  input features
+ *   O  output features                           M  sub-tokens per token
+ *   d = D / M  sub-token size (the paper writes "M" for this size; this
+ *              library follows the convention S[N, M], d = D/M)
+ *   X[N, D] activations, S[N, M] compressed activations, v[d] projection
+ *   vector, G[N, O] gradient of the loss w.r.t. the layer output,
+ *   dW[O, D] gradient w.r.t. the weight (layout of grad_output^T @ input).
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller, to a
+ *     row-major contiguous array.  The library neither allocates nor frees
+ *     device memory; calls that need scratch take a caller-provided workspace
+ *     of at least velora_workspace_bytes(...) bytes.
+ *   - v is always float32.  X, S and G share one storage dtype (float32 or
+ *     bfloat16); arithmetic is float32 accumulate, and values are rounded to
+ *     the storage dtype with round-to-nearest-even when stored.
+ *   - Calls are asynchronous: work is enqueued on `stream` (a hipStream_t, 0 =
+ *     the null stream) and the call returns.  velora_init_v is the exception:
+ *     it waits for its own work so that it can report a degenerate mean.
+ *   - Arguments are validated on the host before anything is launched; on any
+ *     error other than VELORA_ERR_HIP / VELORA_ERR_DEGENERATE nothing was
+ *     launched and the outputs are untouched.  No C++ exception crosses the
+ *     boundary.  The library keeps no state between calls; concurrent calls on
+ *     different streams with disjoint outputs/workspaces are safe.
+ *   - Pointers must be aligned to their element size (VELORA_ERR_ALIGN
+ *     otherwise).  16-byte aligned pointers with d a multiple of 8 (bf16) or 4
+ *     (f32) take the vectorised kernels; anything else takes slower generic
+ *     kernels with identical results up to summation order.
+ */
+#ifndef VELORA_H_
+#define VELORA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VELORA_OK = 0,
+    VELORA_ERR_NULL = 1,        /* a required pointer is NULL                           */
+    VELORA_ERR_SHAPE = 2,       /* N, D, O or M <= 0, or M does not divide D            */
+    VELORA_ERR_DTYPE = 3,       /* dtype value not in velora_dtype                      */
+    VELORA_ERR_ALIGN = 4,       /* pointer not aligned to its element size              */
+    VELORA_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than velora_workspace_bytes */
+    VELORA_ERR_DEGENERATE = 6,  /* init_v: mean of the sub-tokens is zero or not finite */
+    VELORA_ERR_HIP = 7          /* a HIP runtime call failed                            */
+} velora_status;
+
+typedef enum { VELORA_F32 = 0, VELORA_BF16 = 1 } velora_dtype;
+
+typedef enum {
+    VELORA_OP_INIT_V = 0,
+    VELORA_OP_COMPRESS = 1,
+    VELORA_OP_RECONSTRUCT = 2,
+    VELORA_OP_WEIGHT_GRAD = 3
+} velora_op;
+
+typedef void* velora_stream; /* hipStream_t */
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* velora_status_string(velora_status st);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int velora_version(void);
+
+/*
+ * Bytes of device workspace the given call needs for these sizes (0 if none).
+ * Pass the same N, D, O, M and input dtype as to the call itself; arguments an
+ * op does not use (e.g. O for VELORA_OP_INIT_V) are ignored.  Returns 0 for
+ * invalid shapes (the call itself will report the error).
+ */
+size_t velora_workspace_bytes(velora_op op, int64_t N, int64_t D, int64_t O, int64_t M,
+                              velora_dtype in_dt);
+
+/*
+ * Initialise the projection vector (Sec. 3.3: the average of the first batch's
+ * sub-tokens; Sec. 3.2: unit length):
+ *     m[j] = 1/(N*M) * sum_{n<N, g<M} X[n, g*d + j],      v = m / ||m||_2
+ * The average runs over all tokens AND all groups: one v per layer.
+ *   X   [N, D] device, dtype xdt (read only)
+ *   v   [d]    device, float32 (written)
+ *   ws  device workspace, >= velora_workspace_bytes(VELORA_OP_INIT_V, N, D, 0, M, xdt)
+ * Synchronises `stream` before returning.  If ||m|| is zero or any m[j] is not
+ * finite, writes v[j] = 1/sqrt(d) and returns VELORA_ERR_DEGENERATE.
+ */
+velora_status velora_init_v(const void* X, int64_t N, int64_t D, int64_t M, velora_dtype xdt,
+                            float* v, void* ws, size_t ws_bytes, velora_stream stream);
+
+/*
+ * group + compress (Sec. 3.2, Eq. 1):  S[n, g] = sum_{j<d} X[n, g*d + j] * v[j].
+ *   X [N, D] device, dtype xdt (read only);  v [d] device float32 (read only)
+ *   S [N, M] device, dtype xdt (written; float32 accumulate, RNE on store)
+ */
+velora_status velora_compress(const void* X, const float* v, int64_t N, int64_t D, int64_t M,
+                              velora_dtype xdt, void* S, velora_stream stream);
+
+/*
+ * reconstruct + ungroup (Sec. 3.2, second equation):  Xhat[n, g*d + j] = S[n, g] * v[j].
+ * The materialising form; velora_weight_grad never needs it.
+ *   S [N, M] device, dtype dt (read only);  v [d] device float32 (read only)
+ *   Xhat [N, D] device, dtype dt (written)
+ */
+velora_status velora_reconstruct(const void* S, const float* v, int64_t N, int64_t D, int64_t M,
+                                 velora_dtype dt, void* Xhat, velora_stream stream);
+
+/*
+ * Weight gradient from the compressed activations (Algorithm 1, backward:
+ * input_hat = ungroup(reconstruct(z, v)); grad_weight = grad_output^T @ input_hat):
+ *     dW[o, g*d + j] (+)= sum_{n<N} G[n, o] * S[n, g] * v[j]
+ * evaluated as T = G^T S followed by the expansion with v, which is the same
+ * sum re-associated; Xhat is never formed.
+ *   G  [N, O] device, dtype in_dt (read only)
+ *   S  [N, M] device, dtype in_dt (read only)
+ *   v  [d]    device float32 (read only)
+ *   dW [O, D] device, dtype dw_dt (float32 or bfloat16).  accumulate == 0:
+ *      overwritten; accumulate != 0: the result is added to the existing
+ *      contents (in float32, rounded once on store).
+ *   ws device workspace, >= velora_workspace_bytes(VELORA_OP_WEIGHT_GRAD, N, D, O, M, in_dt)
+ * Deterministic: the reduction over tokens is split in a fixed way that
+ * depends only on the sizes; no floating-point atomics.
+ */
+velora_status velora_weight_grad(const void* G, const void* S, const float* v,
+                                 int64_t N, int64_t O, int64_t D, int64_t M, velora_dtype in_dt,
+                                 void* dW, velora_dtype dw_dt, int accumulate,
+                                 void* ws, size_t ws_bytes, velora_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VELORA_H_ */

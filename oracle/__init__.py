@@ -68,10 +68,18 @@ def _load():
 
 
 def default_threads() -> int:
+    """Host threads the oracle uses: the cores this process may run on, capped
+    by OMP_NUM_THREADS when that is set (shared boxes export their CPU share
+    there) and by 16 otherwise."""
     try:
-        return max(1, len(os.sched_getaffinity(0)))
+        n = len(os.sched_getaffinity(0))
     except AttributeError:  # pragma: no cover
-        return max(1, os.cpu_count() or 1)
+        n = os.cpu_count() or 1
+    try:
+        cap = int(os.environ.get("OMP_NUM_THREADS", "16"))
+    except ValueError:
+        cap = 16
+    return max(1, min(n, cap))
 
 
 def _dt(a: np.ndarray) -> int:

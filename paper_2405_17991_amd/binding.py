@@ -1,0 +1,204 @@
+"""ctypes binding of libvelora (see include/velora.h for the contract).
+
+Argument marshalling only.  Tensors are torch tensors on the GPU (PyTorch is
+used for device memory and streams, nothing else); each wrapper checks dtype,
+device and contiguity, then passes raw device pointers and sizes to the C ABI
+on torch's current HIP stream.  ``M`` is the number of sub-tokens per token.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libvelora.so")
+
+F32 = 0
+BF16 = 1
+OP_INIT_V = 0
+OP_COMPRESS = 1
+OP_RECONSTRUCT = 2
+OP_WEIGHT_GRAD = 3
+
+STATUS = {
+    0: "VELORA_OK", 1: "VELORA_ERR_NULL", 2: "VELORA_ERR_SHAPE", 3: "VELORA_ERR_DTYPE",
+    4: "VELORA_ERR_ALIGN", 5: "VELORA_ERR_WORKSPACE", 6: "VELORA_ERR_DEGENERATE", 7: "VELORA_ERR_HIP",
+}
+
+EXPORTS = [
+    "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
+    "velora_compress", "velora_reconstruct", "velora_weight_grad",
+]
+
+
+class VeloraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {velora_status_string(status)}")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build the HIP library first "
+            "(python -m paper_2405_17991_amd.build, or __graft_entry__.build()). "
+            "There is no fallback path.")
+    L = ctypes.CDLL(_LIB_PATH)
+    i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.velora_status_string.argtypes = [ci]
+    L.velora_status_string.restype = ctypes.c_char_p
+    L.velora_version.argtypes = []
+    L.velora_version.restype = ci
+    L.velora_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci]
+    L.velora_workspace_bytes.restype = sz
+    L.velora_init_v.argtypes = [vp, i64, i64, i64, ci, vp, vp, sz, vp]
+    L.velora_init_v.restype = ci
+    L.velora_compress.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp]
+    L.velora_compress.restype = ci
+    L.velora_reconstruct.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp]
+    L.velora_reconstruct.restype = ci
+    L.velora_weight_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, ci, ci, vp, sz, vp]
+    L.velora_weight_grad.restype = ci
+    return L
+
+
+raw = _load()   # the C ABI itself, for callers that hold raw pointers
+
+
+def velora_status_string(status: int) -> str:
+    return raw.velora_status_string(int(status)).decode()
+
+
+def velora_version() -> int:
+    return int(raw.velora_version())
+
+
+def velora_workspace_bytes(op: int, N: int, D: int, O: int, M: int, dtype: int) -> int:
+    return int(raw.velora_workspace_bytes(op, N, D, O, M, dtype))
+
+
+# ---- torch plumbing ---------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _dt(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: expected float32 or bfloat16")
+
+
+def _check(t, name: str, ndim: int):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if t.dim() != ndim:
+        raise ValueError(f"{name} must have {ndim} dimensions, got {tuple(t.shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def _stream() -> int:
+    return int(_torch().cuda.current_stream().cuda_stream)
+
+
+def _ws(nbytes: int, like, ws):
+    torch = _torch()
+    if ws is None:
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=like.device)
+    return ws
+
+
+def _raise(st: int, where: str):
+    if st != 0:
+        raise VeloraError(st, where)
+
+
+def velora_init_v(X, M: int, v=None, ws=None, allow_degenerate: bool = False):
+    """v[d] = normalised mean of the N*M sub-tokens of X[N, D] (float32)."""
+    torch = _torch()
+    _check(X, "X", 2)
+    N, D = X.shape
+    if v is None:
+        v = torch.empty(D // M if M > 0 and D % M == 0 else 1, dtype=torch.float32, device=X.device)
+    _check(v, "v", 1)
+    need = velora_workspace_bytes(OP_INIT_V, N, D, 0, M, _dt(X))
+    ws = _ws(need, X, ws)
+    st = raw.velora_init_v(X.data_ptr(), N, D, M, _dt(X), v.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    if st == 6 and allow_degenerate:
+        return v
+    _raise(st, "velora_init_v")
+    return v
+
+
+def velora_compress(X, v, M: int, S=None):
+    """S[N, M] = <sub-token, v>, dtype of X."""
+    torch = _torch()
+    _check(X, "X", 2)
+    _check(v, "v", 1)
+    N, D = X.shape
+    if v.dtype != torch.float32:
+        raise TypeError("v must be float32")
+    if M > 0 and D % M == 0 and v.numel() != D // M:
+        raise ValueError(f"v must have D/M = {D // M} elements, got {v.numel()}")
+    if S is None:
+        S = torch.empty((N, max(M, 1)), dtype=X.dtype, device=X.device)
+    _check(S, "S", 2)
+    if S.dtype != X.dtype:
+        raise TypeError("S must have X's dtype")
+    st = raw.velora_compress(X.data_ptr(), v.data_ptr(), N, D, M, _dt(X), S.data_ptr(), _stream())
+    _raise(st, "velora_compress")
+    return S
+
+
+def velora_reconstruct(S, v, D: int, Xhat=None):
+    """Xhat[N, D] with Xhat[n, g*d + j] = S[n, g] * v[j], dtype of S."""
+    torch = _torch()
+    _check(S, "S", 2)
+    _check(v, "v", 1)
+    N, M = S.shape
+    if v.dtype != torch.float32:
+        raise TypeError("v must be float32")
+    if Xhat is None:
+        Xhat = torch.empty((N, D), dtype=S.dtype, device=S.device)
+    _check(Xhat, "Xhat", 2)
+    st = raw.velora_reconstruct(S.data_ptr(), v.data_ptr(), N, D, M, _dt(S), Xhat.data_ptr(), _stream())
+    _raise(st, "velora_reconstruct")
+    return Xhat
+
+
+def velora_weight_grad(G, S, v, D: int, dW=None, dw_dtype=None, accumulate: bool = False, ws=None):
+    """dW[O, D] (+)= G^T @ ungroup(reconstruct(S, v)) without forming Xhat."""
+    torch = _torch()
+    _check(G, "G", 2)
+    _check(S, "S", 2)
+    _check(v, "v", 1)
+    N, O = G.shape
+    N2, M = S.shape
+    if N2 != N:
+        raise ValueError("G and S must have the same number of tokens")
+    if G.dtype != S.dtype:
+        raise TypeError("G and S must share a dtype")
+    if v.dtype != torch.float32:
+        raise TypeError("v must be float32")
+    if dW is None:
+        if accumulate:
+            raise ValueError("accumulate=True needs an existing dW")
+        dW = torch.empty((O, D), dtype=dw_dtype or torch.float32, device=G.device)
+    _check(dW, "dW", 2)
+    if tuple(dW.shape) != (O, D):
+        raise ValueError(f"dW must be [{O}, {D}]")
+    need = velora_workspace_bytes(OP_WEIGHT_GRAD, N, D, O, M, _dt(G))
+    ws = _ws(need, G, ws)
+    st = raw.velora_weight_grad(G.data_ptr(), S.data_ptr(), v.data_ptr(), N, O, D, M, _dt(G), dW.data_ptr(),
+                                _dt(dW), 1 if accumulate else 0, ws.data_ptr(), ws.numel(), _stream())
+    _raise(st, "velora_weight_grad")
+    return dW

@@ -1,0 +1,166 @@
+// C-ABI entry points of libvelora: argument validation, launch planning and
+// error mapping.  Nothing here touches device memory contents; the arithmetic
+// lives in compress.hip, init_v.hip and wgrad.hip.
+#include "../../include/velora.h"
+
+#include <atomic>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+using velora::LaunchCfg;
+
+constexpr int kMaxDevices = 64;
+constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
+
+LaunchCfg current_cfg() {
+    static std::atomic<int> cached[kMaxDevices];   // zero-initialised: 0 = not queried
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
+        cus = cached[dev].load(std::memory_order_relaxed);
+        if (cus == 0) {
+            int n = 0;
+            if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+                cus = n;
+                cached[dev].store(n, std::memory_order_relaxed);
+            }
+        }
+    } else {
+        (void)hipGetLastError();   // clear the sticky "no device" error
+    }
+    if (cus <= 0) cus = kDefaultCus;
+    LaunchCfg c;
+    c.num_cus = cus;
+    c.max_blocks = cus * 8;        // 8 blocks x 4 waves = full wave occupancy per CU
+    return c;
+}
+
+int ptr_align(const void* p) {
+    const uintptr_t a = reinterpret_cast<uintptr_t>(p);
+    int al = 16;
+    while (al > 1 && (a % static_cast<uintptr_t>(al)) != 0) al >>= 1;
+    return al;
+}
+
+bool dtype_ok(velora_dtype dt) { return dt == VELORA_F32 || dt == VELORA_BF16; }
+int elem_bytes(velora_dtype dt) { return dt == VELORA_BF16 ? 2 : 4; }
+
+bool shape_ok(int64_t N, int64_t D, int64_t M) { return N > 0 && D > 0 && M > 0 && M <= D && D % M == 0; }
+
+// Sizes that would overflow 64-bit element counts or 32-bit sub-token sizes are
+// rejected as shapes.
+bool size_ok(int64_t rows, int64_t cols) {
+    return rows > 0 && cols > 0 && cols <= (INT64_C(1) << 40) / rows;
+}
+
+velora_status hip_status(hipError_t e) { return e == hipSuccess ? VELORA_OK : VELORA_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* velora_status_string(velora_status st) {
+    switch (st) {
+        case VELORA_OK: return "VELORA_OK";
+        case VELORA_ERR_NULL: return "VELORA_ERR_NULL: a required pointer is NULL";
+        case VELORA_ERR_SHAPE: return "VELORA_ERR_SHAPE: sizes must be positive and M must divide D";
+        case VELORA_ERR_DTYPE: return "VELORA_ERR_DTYPE: unknown dtype";
+        case VELORA_ERR_ALIGN: return "VELORA_ERR_ALIGN: pointer not aligned to its element size";
+        case VELORA_ERR_WORKSPACE: return "VELORA_ERR_WORKSPACE: workspace missing or too small";
+        case VELORA_ERR_DEGENERATE: return "VELORA_ERR_DEGENERATE: sub-token mean is zero or not finite";
+        case VELORA_ERR_HIP: return "VELORA_ERR_HIP: a HIP runtime call failed";
+    }
+    return "VELORA: unknown status";
+}
+
+int velora_version(void) { return 100; }
+
+size_t velora_workspace_bytes(velora_op op, int64_t N, int64_t D, int64_t O, int64_t M, velora_dtype in_dt) {
+    if (!dtype_ok(in_dt) || !shape_ok(N, D, M) || !size_ok(N, D)) return 0;
+    const LaunchCfg cfg = current_cfg();
+    switch (op) {
+        case VELORA_OP_INIT_V:
+            return velora::plan_init_v(N * M, D / M, in_dt == VELORA_BF16, cfg).ws_bytes;
+        case VELORA_OP_WEIGHT_GRAD:
+            if (O <= 0 || !size_ok(N, O) || !size_ok(O, D)) return 0;
+            return velora::plan_wgrad(N, O, D, M, in_dt == VELORA_BF16, cfg).ws_bytes;
+        case VELORA_OP_COMPRESS:
+        case VELORA_OP_RECONSTRUCT:
+            return 0;
+    }
+    return 0;
+}
+
+velora_status velora_init_v(const void* X, int64_t N, int64_t D, int64_t M, velora_dtype xdt, float* v, void* ws,
+                            size_t ws_bytes, velora_stream stream) {
+    if (!X || !v) return VELORA_ERR_NULL;
+    if (!dtype_ok(xdt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(N, D, M) || !size_ok(N, D) || D / M > INT32_MAX / 8) return VELORA_ERR_SHAPE;
+    if (ptr_align(X) < elem_bytes(xdt) || ptr_align(v) < 4) return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool bf = xdt == VELORA_BF16;
+    const velora::InitVPlan plan = velora::plan_init_v(N * M, D / M, bf, cfg);
+    if (!ws || ws_bytes < plan.ws_bytes) return VELORA_ERR_WORKSPACE;
+    if (ptr_align(ws) < 16) return VELORA_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = velora::launch_init_v(X, v, N * M, D / M, bf, ptr_align(X) >= 16, ws, plan, st);
+    if (e != hipSuccess) return VELORA_ERR_HIP;
+    int flag = -1;
+    e = hipMemcpyAsync(&flag, ws, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return VELORA_ERR_HIP;
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return VELORA_ERR_HIP;
+    if (flag == 0) return VELORA_OK;
+    return flag == VELORA_ERR_DEGENERATE ? VELORA_ERR_DEGENERATE : VELORA_ERR_HIP;
+}
+
+velora_status velora_compress(const void* X, const float* v, int64_t N, int64_t D, int64_t M, velora_dtype xdt,
+                              void* S, velora_stream stream) {
+    if (!X || !v || !S) return VELORA_ERR_NULL;
+    if (!dtype_ok(xdt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(N, D, M) || !size_ok(N, D) || D / M > INT32_MAX / 8) return VELORA_ERR_SHAPE;
+    const int eb = elem_bytes(xdt);
+    if (ptr_align(X) < eb || ptr_align(S) < eb || ptr_align(v) < 4) return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool vec_ok = ptr_align(X) >= 16;
+    return hip_status(velora::launch_compress(X, v, S, N * M, D / M, xdt == VELORA_BF16, vec_ok, cfg,
+                                              static_cast<hipStream_t>(stream)));
+}
+
+velora_status velora_reconstruct(const void* S, const float* v, int64_t N, int64_t D, int64_t M, velora_dtype dt,
+                                 void* Xhat, velora_stream stream) {
+    if (!S || !v || !Xhat) return VELORA_ERR_NULL;
+    if (!dtype_ok(dt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(N, D, M) || !size_ok(N, D) || D / M > INT32_MAX / 8) return VELORA_ERR_SHAPE;
+    const int eb = elem_bytes(dt);
+    if (ptr_align(S) < eb || ptr_align(Xhat) < eb || ptr_align(v) < 4) return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool vec_ok = ptr_align(Xhat) >= 16;
+    return hip_status(velora::launch_reconstruct(S, v, Xhat, N * M, D / M, dt == VELORA_BF16, vec_ok, cfg,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
+velora_status velora_weight_grad(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D,
+                                 int64_t M, velora_dtype in_dt, void* dW, velora_dtype dw_dt, int accumulate,
+                                 void* ws, size_t ws_bytes, velora_stream stream) {
+    if (!G || !S || !v || !dW) return VELORA_ERR_NULL;
+    if (!dtype_ok(in_dt) || !dtype_ok(dw_dt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(N, D, M) || O <= 0 || !size_ok(N, D) || !size_ok(N, O) || !size_ok(O, D) ||
+        D / M > INT32_MAX / 8 || O > INT32_MAX)
+        return VELORA_ERR_SHAPE;
+    const int eb = elem_bytes(in_dt);
+    if (ptr_align(G) < eb || ptr_align(S) < eb || ptr_align(v) < 4 || ptr_align(dW) < elem_bytes(dw_dt))
+        return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool bf = in_dt == VELORA_BF16;
+    const velora::WgradPlan plan = velora::plan_wgrad(N, O, D, M, bf, cfg);
+    if (!ws || ws_bytes < plan.ws_bytes) return VELORA_ERR_WORKSPACE;
+    if (ptr_align(ws) < 16) return VELORA_ERR_ALIGN;
+    return hip_status(velora::launch_wgrad(G, S, v, N, O, D, M, bf, ptr_align(G), ptr_align(S), ptr_align(v), dW,
+                                           dw_dt == VELORA_BF16, ptr_align(dW), accumulate != 0, ws, plan, cfg,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,243 @@
+// group + compress, and reconstruct + ungroup (paper Sec. 3.2).
+//
+// X[N, D] is row-major and d divides D, so "split every token into M = D/d
+// sub-tokens" is nothing but reading the flat array in runs of d elements:
+// sub-token k = n*M + g occupies elements [k*d, (k+1)*d).  compress is a flat
+// batched dot product S[k] = <X[k*d : (k+1)*d], v>, reconstruct its transpose
+// Xhat[k*d + j] = S[k] * v[j].  Both are pure HBM streams (about one flop per
+// byte), so the kernels are built around 16-byte coalesced accesses with many
+// loads in flight per wave; the arithmetic hides under the memory time.
+#include "common.h"
+#include "kernels.h"
+
+namespace velora {
+
+// ---------------------------------------------------------------------------
+// Vectorised compress.
+//   E   element traits (F32Elem: 4 per 16-byte vector, Bf16Elem: 8)
+//   P   lanes that share one sub-token (d / E::kPerVec, capped at 64)
+//   L   16-byte vectors each lane reads per sub-token (1 unless d > 64*kPerVec)
+//   U   sub-tokens per lane group and iteration = independent loads in flight
+// A wave iteration ("super-chunk") covers SEG*U consecutive sub-tokens, SEG =
+// 64/P lane groups; group `seg` owns sub-tokens base + seg*U + [0, U), so after
+// the cross-lane sums lane (seg, p) can store result u = p and the wave's
+// stores form one contiguous run of S.
+// ---------------------------------------------------------------------------
+template <typename E, int P, int L, int U>
+__global__ __launch_bounds__(256) void compress_vec_kernel(const uint4* __restrict__ X,
+                                                          const float* __restrict__ v,
+                                                          typename E::type* __restrict__ S,
+                                                          int64_t n_sub) {
+    constexpr int kV = E::kPerVec;
+    constexpr int SEG = kWave / P;
+    constexpr int kVecPerSub = P * L;               // 16-byte vectors per sub-token
+    const int lane = threadIdx.x & (kWave - 1);
+    const int p = lane % P;
+    const int seg = lane / P;
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * blockDim.x / kWave;
+    const int64_t n_chunks = ceil_div(n_sub, static_cast<int64_t>(SEG) * U);
+
+    // this lane's slice of v never changes
+    float vf[L][kV];
+#pragma unroll
+    for (int l = 0; l < L; ++l)
+#pragma unroll
+        for (int e = 0; e < kV; ++e) vf[l][e] = v[(l * P + p) * kV + e];
+
+    for (int64_t chunk = wave; chunk < n_chunks; chunk += n_waves) {
+        const int64_t k0 = chunk * (SEG * U) + static_cast<int64_t>(seg) * U;
+        uint4 q[U][L];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                q[u][l] = make_uint4(0u, 0u, 0u, 0u);
+                if (k0 + u < n_sub) q[u][l] = load_stream16(&X[(k0 + u) * kVecPerSub + l * P + p]);
+            }
+        float sum[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float acc = 0.f;
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                float f[kV];
+                E::unpack(q[u][l], f);
+#pragma unroll
+                for (int e = 0; e < kV; ++e) acc = fmaf(f[e], vf[l][e], acc);
+            }
+            sum[u] = group_sum<P>(acc);
+        }
+        // lane (seg, p) stores results u = p, p + P, ... of its group
+#pragma unroll
+        for (int u0 = 0; u0 < U; u0 += P) {
+            float val = sum[u0];
+#pragma unroll
+            for (int t = 1; t < P && u0 + t < U; ++t)
+                if (p == t) val = sum[u0 + t];
+            const int u = u0 + p;
+            if (u < U && k0 + u < n_sub) E::store(S, k0 + u, val);
+        }
+    }
+}
+
+// Generic compress: any d, element-aligned pointers.  P lanes (power of two,
+// chosen by the host) share a sub-token and stride over its elements.
+template <typename E>
+__global__ __launch_bounds__(256) void compress_generic_kernel(const typename E::type* __restrict__ X,
+                                                              const float* __restrict__ v,
+                                                              typename E::type* __restrict__ S,
+                                                              int64_t n_sub, int d, int P) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int p = lane % P;
+    const int seg = lane / P;
+    const int SEG = kWave / P;
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * blockDim.x / kWave;
+    const int64_t n_chunks = ceil_div(n_sub, SEG);
+    for (int64_t chunk = wave; chunk < n_chunks; chunk += n_waves) {
+        const int64_t k = chunk * SEG + seg;
+        float acc = 0.f;
+        if (k < n_sub)
+            for (int j = p; j < d; j += P) acc = fmaf(E::load(X, k * d + j), v[j], acc);
+        acc = group_sum_rt(acc, P);
+        if (p == 0 && k < n_sub) E::store(S, k, acc);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// reconstruct + ungroup: every lane writes one 16-byte vector of Xhat.
+// ---------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(256) void reconstruct_vec_kernel(const typename E::type* __restrict__ S,
+                                                             const float* __restrict__ v,
+                                                             uint4* __restrict__ Xhat,
+                                                             int64_t n_vec, int d) {
+    constexpr int kV = E::kPerVec;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
+        const int64_t e0 = i * kV;
+        const int64_t k = e0 / d;
+        const int j0 = static_cast<int>(e0 - k * d);
+        const float s = E::load(S, k);
+        float f[kV];
+#pragma unroll
+        for (int e = 0; e < kV; ++e) f[e] = s * v[j0 + e];
+        uint4 out;
+        if constexpr (kV == 4) {
+            out = make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+        } else {
+            out = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
+                             pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+        }
+        Xhat[i] = out;
+    }
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void reconstruct_generic_kernel(const typename E::type* __restrict__ S,
+                                                                 const float* __restrict__ v,
+                                                                 typename E::type* __restrict__ Xhat,
+                                                                 int64_t n_elem, int d) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n_elem; i += stride) {
+        const int64_t k = i / d;
+        E::store(Xhat, i, E::load(S, k) * v[i - k * d]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host-side dispatch
+// ---------------------------------------------------------------------------
+namespace {
+
+constexpr int kBlock = 256;
+
+int grid_for(int64_t n_wave_items, int waves_per_block, int max_blocks) {
+    int64_t b = ceil_div(n_wave_items, waves_per_block);
+    if (b < 1) b = 1;
+    if (b > max_blocks) b = max_blocks;
+    return static_cast<int>(b);
+}
+
+template <typename E, int P, int L, int U>
+hipError_t launch_compress_vec(const void* X, const float* v, void* S, int64_t n_sub, const LaunchCfg& cfg,
+                               hipStream_t st) {
+    constexpr int SEG = kWave / P;
+    const int64_t n_chunks = ceil_div(n_sub, static_cast<int64_t>(SEG) * U);
+    const int grid = grid_for(n_chunks, kBlock / kWave, cfg.max_blocks);
+    hipLaunchKernelGGL((compress_vec_kernel<E, P, L, U>), dim3(grid), dim3(kBlock), 0, st,
+                       static_cast<const uint4*>(X), v, static_cast<typename E::type*>(S), n_sub);
+    return hipGetLastError();
+}
+
+template <typename E>
+hipError_t dispatch_compress_vec(int vec_per_sub, const void* X, const float* v, void* S, int64_t n_sub,
+                                 const LaunchCfg& cfg, hipStream_t st, bool* handled) {
+    *handled = true;
+    switch (vec_per_sub) {
+        case 1:   return launch_compress_vec<E, 1, 1, 8>(X, v, S, n_sub, cfg, st);
+        case 2:   return launch_compress_vec<E, 2, 1, 8>(X, v, S, n_sub, cfg, st);
+        case 4:   return launch_compress_vec<E, 4, 1, 8>(X, v, S, n_sub, cfg, st);
+        case 8:   return launch_compress_vec<E, 8, 1, 8>(X, v, S, n_sub, cfg, st);
+        case 16:  return launch_compress_vec<E, 16, 1, 8>(X, v, S, n_sub, cfg, st);
+        case 32:  return launch_compress_vec<E, 32, 1, 8>(X, v, S, n_sub, cfg, st);
+        case 64:  return launch_compress_vec<E, 64, 1, 8>(X, v, S, n_sub, cfg, st);
+        case 128: return launch_compress_vec<E, 64, 2, 4>(X, v, S, n_sub, cfg, st);
+        case 256: return launch_compress_vec<E, 64, 4, 2>(X, v, S, n_sub, cfg, st);
+        default:  *handled = false; return hipSuccess;
+    }
+}
+
+template <typename E>
+hipError_t compress_any(const void* X, const float* v, void* S, int64_t n_sub, int64_t d, bool vec_ok,
+                        const LaunchCfg& cfg, hipStream_t st) {
+    if (vec_ok && d % E::kPerVec == 0) {
+        bool handled = false;
+        hipError_t e = dispatch_compress_vec<E>(static_cast<int>(d / E::kPerVec), X, v, S, n_sub, cfg, st, &handled);
+        if (handled) return e;
+    }
+    int P = 1;
+    while (P < kWave && P < d) P <<= 1;
+    const int64_t n_chunks = ceil_div(n_sub, kWave / P);
+    const int grid = grid_for(n_chunks, kBlock / kWave, cfg.max_blocks);
+    hipLaunchKernelGGL((compress_generic_kernel<E>), dim3(grid), dim3(kBlock), 0, st,
+                       static_cast<const typename E::type*>(X), v, static_cast<typename E::type*>(S), n_sub,
+                       static_cast<int>(d), P);
+    return hipGetLastError();
+}
+
+template <typename E>
+hipError_t reconstruct_any(const void* S, const float* v, void* Xhat, int64_t n_sub, int64_t d, bool vec_ok,
+                           const LaunchCfg& cfg, hipStream_t st) {
+    const int64_t n_elem = n_sub * d;
+    if (vec_ok && d % E::kPerVec == 0) {
+        const int64_t n_vec = n_elem / E::kPerVec;
+        const int grid = grid_for(ceil_div(n_vec, kBlock), 1, cfg.max_blocks * 4);
+        hipLaunchKernelGGL((reconstruct_vec_kernel<E>), dim3(grid), dim3(kBlock), 0, st,
+                           static_cast<const typename E::type*>(S), v, static_cast<uint4*>(Xhat), n_vec,
+                           static_cast<int>(d));
+    } else {
+        const int grid = grid_for(ceil_div(n_elem, kBlock), 1, cfg.max_blocks * 4);
+        hipLaunchKernelGGL((reconstruct_generic_kernel<E>), dim3(grid), dim3(kBlock), 0, st,
+                           static_cast<const typename E::type*>(S), v, static_cast<typename E::type*>(Xhat), n_elem,
+                           static_cast<int>(d));
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_compress(const void* X, const float* v, void* S, int64_t n_sub, int64_t d, bool is_bf16,
+                           bool vec_ok, const LaunchCfg& cfg, hipStream_t st) {
+    return is_bf16 ? compress_any<Bf16Elem>(X, v, S, n_sub, d, vec_ok, cfg, st)
+                   : compress_any<F32Elem>(X, v, S, n_sub, d, vec_ok, cfg, st);
+}
+
+hipError_t launch_reconstruct(const void* S, const float* v, void* Xhat, int64_t n_sub, int64_t d, bool is_bf16,
+                              bool vec_ok, const LaunchCfg& cfg, hipStream_t st) {
+    return is_bf16 ? reconstruct_any<Bf16Elem>(S, v, Xhat, n_sub, d, vec_ok, cfg, st)
+                   : reconstruct_any<F32Elem>(S, v, Xhat, n_sub, d, vec_ok, cfg, st);
+}
+
+}  // namespace velora

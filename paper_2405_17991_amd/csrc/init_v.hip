@@ -1,0 +1,236 @@
+// Initialisation of the projection vector (paper Sec. 3.3, "Cheap
+// initialisation strategies": the average of the first batch's sub-tokens;
+// Sec. 3.2: v has unit length):
+//     m[j] = 1/(N*M) * sum_k X[k*d + j],   v = m / ||m||_2
+// i.e. the column mean of the flat [N*M, d] view of X.  One streaming pass over
+// X (HBM-bound) produces per-block float32 partial column sums; they are
+// combined in float64 in a fixed order, so the result is deterministic and the
+// long sum never runs in a single float32 accumulator.
+#include "common.h"
+#include "kernels.h"
+
+namespace velora {
+
+// Same lane <-> element mapping as the vectorised compress kernel: lane
+// (seg, p) always sees columns (l*P + p)*kPerVec + [0, kPerVec) of a sub-token.
+template <typename E, int P, int L, int U>
+__global__ __launch_bounds__(256) void colsum_vec_kernel(const uint4* __restrict__ X, float* __restrict__ partial,
+                                                        int64_t n_sub, int d) {
+    constexpr int kV = E::kPerVec;
+    constexpr int SEG = kWave / P;
+    constexpr int kVecPerSub = P * L;
+    constexpr int kWavesPerBlock = 256 / kWave;
+    __shared__ float lds[kWavesPerBlock][L * kV][kWave + 1];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wib = threadIdx.x / kWave;
+    const int p = lane % P;
+    const int seg = lane / P;
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * blockDim.x / kWave;
+    const int64_t n_chunks = ceil_div(n_sub, static_cast<int64_t>(SEG) * U);
+
+    float acc[L][kV];
+#pragma unroll
+    for (int l = 0; l < L; ++l)
+#pragma unroll
+        for (int e = 0; e < kV; ++e) acc[l][e] = 0.f;
+
+    for (int64_t chunk = wave; chunk < n_chunks; chunk += n_waves) {
+        const int64_t k0 = chunk * (SEG * U) + seg;
+        uint4 q[U][L];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                q[u][l] = make_uint4(0u, 0u, 0u, 0u);
+                const int64_t k = k0 + static_cast<int64_t>(u) * SEG;
+                if (k < n_sub) q[u][l] = load_stream16(&X[k * kVecPerSub + l * P + p]);
+            }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                float f[kV];
+                E::unpack(q[u][l], f);
+#pragma unroll
+                for (int e = 0; e < kV; ++e) acc[l][e] += f[e];
+            }
+    }
+#pragma unroll
+    for (int l = 0; l < L; ++l)
+#pragma unroll
+        for (int e = 0; e < kV; ++e) lds[wib][l * kV + e][lane] = acc[l][e];
+    __syncthreads();
+    // column j lives in lanes seg*P + p of every wave, slot l*kV + e
+    for (int j = threadIdx.x; j < d; j += blockDim.x) {
+        const int l = j / (P * kV);
+        const int rem = j - l * (P * kV);
+        const int pp = rem / kV;
+        const int e = rem - pp * kV;
+        float s = 0.f;
+        for (int w = 0; w < kWavesPerBlock; ++w)
+            for (int sg = 0; sg < SEG; ++sg) s += lds[w][l * kV + e][sg * P + pp];
+        partial[static_cast<int64_t>(blockIdx.x) * d + j] = s;
+    }
+}
+
+// Generic column sums: any d, element-aligned pointer.  C threads across
+// columns (coalesced), R = 256/C sub-tokens in parallel.
+template <typename E>
+__global__ __launch_bounds__(256) void colsum_generic_kernel(const typename E::type* __restrict__ X,
+                                                            float* __restrict__ partial, int64_t n_sub, int d,
+                                                            int C, int64_t sub_per_block) {
+    __shared__ float lds[256];
+    const int R = 256 / C;
+    const int c = threadIdx.x % C;
+    const int r = threadIdx.x / C;
+    const int64_t k_begin = static_cast<int64_t>(blockIdx.x) * sub_per_block;
+    int64_t k_end = k_begin + sub_per_block;
+    if (k_end > n_sub) k_end = n_sub;
+    for (int j0 = 0; j0 < d; j0 += C) {
+        const int j = j0 + c;
+        float acc = 0.f;
+        if (j < d)
+            for (int64_t k = k_begin + r; k < k_end; k += R) acc += E::load(X, k * d + j);
+        lds[threadIdx.x] = acc;
+        __syncthreads();
+        if (r == 0 && j < d) {
+            float s = 0.f;
+            for (int rr = 0; rr < R; ++rr) s += lds[rr * C + c];
+            partial[static_cast<int64_t>(blockIdx.x) * d + j] = s;
+        }
+        __syncthreads();
+    }
+}
+
+// mean[j] = (sum over blocks of partial[b][j]) / n_sub, in float64, fixed order.
+__global__ __launch_bounds__(256) void colsum_combine_kernel(const float* __restrict__ partial,
+                                                            double* __restrict__ mean, int blocks, int d,
+                                                            double inv_count) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= d) return;
+    double s = 0.0;
+    for (int b = 0; b < blocks; ++b) s += static_cast<double>(partial[static_cast<int64_t>(b) * d + j]);
+    mean[j] = s * inv_count;
+}
+
+// v = mean / ||mean||; flag = 0, or 6 (and v = 1/sqrt(d)) when the mean is zero
+// or not finite.  One block.
+__global__ __launch_bounds__(256) void normalise_v_kernel(const double* __restrict__ mean, float* __restrict__ v,
+                                                         int* __restrict__ flag, int d) {
+    __shared__ double red[256];
+    __shared__ int bad[256];
+    double ss = 0.0;
+    int nonfinite = 0;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) {
+        const double m = mean[j];
+        ss += m * m;
+        if (!isfinite(m)) nonfinite = 1;
+    }
+    red[threadIdx.x] = ss;
+    bad[threadIdx.x] = nonfinite;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) {
+            red[threadIdx.x] += red[threadIdx.x + s];
+            bad[threadIdx.x] |= bad[threadIdx.x + s];
+        }
+        __syncthreads();
+    }
+    const double norm = sqrt(red[0]);
+    const bool degenerate = bad[0] || !(norm > 0.0) || !isfinite(norm);
+    for (int j = threadIdx.x; j < d; j += blockDim.x)
+        v[j] = degenerate ? static_cast<float>(1.0 / sqrt(static_cast<double>(d))) : static_cast<float>(mean[j] / norm);
+    if (threadIdx.x == 0) *flag = degenerate ? 6 : 0;
+}
+
+namespace {
+
+constexpr size_t kFlagBytes = 256;
+
+template <typename E, int P, int L, int U>
+hipError_t launch_colsum_vec(const void* X, float* partial, int64_t n_sub, int d, int blocks, hipStream_t st) {
+    hipLaunchKernelGGL((colsum_vec_kernel<E, P, L, U>), dim3(blocks), dim3(256), 0, st,
+                       static_cast<const uint4*>(X), partial, n_sub, d);
+    return hipGetLastError();
+}
+
+template <typename E>
+hipError_t dispatch_colsum_vec(int vec_per_sub, const void* X, float* partial, int64_t n_sub, int d, int blocks,
+                               hipStream_t st, bool* handled) {
+    *handled = true;
+    switch (vec_per_sub) {
+        case 1:   return launch_colsum_vec<E, 1, 1, 8>(X, partial, n_sub, d, blocks, st);
+        case 2:   return launch_colsum_vec<E, 2, 1, 8>(X, partial, n_sub, d, blocks, st);
+        case 4:   return launch_colsum_vec<E, 4, 1, 8>(X, partial, n_sub, d, blocks, st);
+        case 8:   return launch_colsum_vec<E, 8, 1, 8>(X, partial, n_sub, d, blocks, st);
+        case 16:  return launch_colsum_vec<E, 16, 1, 8>(X, partial, n_sub, d, blocks, st);
+        case 32:  return launch_colsum_vec<E, 32, 1, 8>(X, partial, n_sub, d, blocks, st);
+        case 64:  return launch_colsum_vec<E, 64, 1, 8>(X, partial, n_sub, d, blocks, st);
+        case 128: return launch_colsum_vec<E, 64, 2, 4>(X, partial, n_sub, d, blocks, st);
+        case 256: return launch_colsum_vec<E, 64, 4, 2>(X, partial, n_sub, d, blocks, st);
+        default:  *handled = false; return hipSuccess;
+    }
+}
+
+bool vec_shape_ok(int64_t d, int per_vec) {
+    if (d % per_vec) return false;
+    const int64_t vps = d / per_vec;
+    return vps <= 256 && (vps & (vps - 1)) == 0;
+}
+
+template <typename E>
+hipError_t colsum_any(const void* X, float* partial, int64_t n_sub, int64_t d, bool vec_ok, int blocks,
+                      hipStream_t st) {
+    if (vec_ok && vec_shape_ok(d, E::kPerVec)) {
+        bool handled = false;
+        hipError_t e = dispatch_colsum_vec<E>(static_cast<int>(d / E::kPerVec), X, partial, n_sub,
+                                              static_cast<int>(d), blocks, st, &handled);
+        if (handled) return e;
+    }
+    int C = 1;
+    while (C < 256 && C < d) C <<= 1;
+    const int64_t sub_per_block = ceil_div(n_sub, blocks);
+    hipLaunchKernelGGL((colsum_generic_kernel<E>), dim3(blocks), dim3(256), 0, st,
+                       static_cast<const typename E::type*>(X), partial, n_sub, static_cast<int>(d), C,
+                       sub_per_block);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+InitVPlan plan_init_v(int64_t n_sub, int64_t d, bool is_bf16, const LaunchCfg& cfg) {
+    InitVPlan p;
+    // enough blocks to stream at full rate, few enough that the float64
+    // combine pass over [blocks][d] stays negligible
+    int64_t blocks = static_cast<int64_t>(cfg.num_cus) * 4;
+    const int64_t per_vec = is_bf16 ? 8 : 4;
+    const int64_t work_items = ceil_div(n_sub * d, 64 * per_vec * 8);   // wave iterations available
+    if (blocks > ceil_div(work_items, 4)) blocks = ceil_div(work_items, 4);
+    if (blocks < 1) blocks = 1;
+    p.blocks = static_cast<int>(blocks);
+    p.partial_off = kFlagBytes + ceil_div(static_cast<int64_t>(d) * 8, 256) * 256;   // flag | mean[d] f64 | partial
+    p.ws_bytes = p.partial_off + static_cast<size_t>(blocks) * static_cast<size_t>(d) * sizeof(float);
+    return p;
+}
+
+hipError_t launch_init_v(const void* X, float* v, int64_t n_sub, int64_t d, bool is_bf16, bool vec_ok,
+                         void* ws, const InitVPlan& plan, hipStream_t st) {
+    char* base = static_cast<char*>(ws);
+    int* flag = reinterpret_cast<int*>(base);
+    double* mean = reinterpret_cast<double*>(base + kFlagBytes);
+    float* partial = reinterpret_cast<float*>(base + plan.partial_off);
+    hipError_t e = is_bf16 ? colsum_any<Bf16Elem>(X, partial, n_sub, d, vec_ok, plan.blocks, st)
+                           : colsum_any<F32Elem>(X, partial, n_sub, d, vec_ok, plan.blocks, st);
+    if (e != hipSuccess) return e;
+    const int di = static_cast<int>(d);
+    hipLaunchKernelGGL(colsum_combine_kernel, dim3(static_cast<unsigned>(ceil_div(d, 256))), dim3(256), 0, st,
+                       partial, mean, plan.blocks, di, 1.0 / static_cast<double>(n_sub));
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(normalise_v_kernel, dim3(1), dim3(256), 0, st, mean, v, flag, di);
+    return hipGetLastError();
+}
+
+}  // namespace velora

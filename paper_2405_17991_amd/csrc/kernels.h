@@ -1,0 +1,47 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernels.
+// Every function only enqueues work on `st` and returns hipGetLastError().
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace velora {
+
+struct LaunchCfg {
+    int num_cus;     // compute units of the current device
+    int max_blocks;  // cap for grid-stride streaming kernels (256-thread blocks)
+};
+
+// ---- compress.hip ----
+hipError_t launch_compress(const void* X, const float* v, void* S, int64_t n_sub, int64_t d, bool is_bf16,
+                           bool vec_ok, const LaunchCfg& cfg, hipStream_t st);
+hipError_t launch_reconstruct(const void* S, const float* v, void* Xhat, int64_t n_sub, int64_t d, bool is_bf16,
+                              bool vec_ok, const LaunchCfg& cfg, hipStream_t st);
+
+// ---- init_v.hip ----
+// Workspace layout: [int32 flag | pad to 256 B | float partial[blocks][d]].
+struct InitVPlan {
+    int blocks;        // partial-sum blocks of the first kernel
+    size_t ws_bytes;   // total workspace
+    size_t partial_off;
+};
+InitVPlan plan_init_v(int64_t n_sub, int64_t d, bool is_bf16, const LaunchCfg& cfg);
+hipError_t launch_init_v(const void* X, float* v, int64_t n_sub, int64_t d, bool is_bf16, bool vec_ok,
+                         void* ws, const InitVPlan& plan, hipStream_t st);
+
+// ---- wgrad.hip ----
+// Workspace layout: float partial[splits][O][Mp], Mp = M rounded up to 4.
+struct WgradPlan {
+    int splits;        // number of token ranges (split-K)
+    int64_t rows_per_split;
+    int64_t Mp;
+    size_t ws_bytes;
+};
+WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, const LaunchCfg& cfg);
+// g_align / s_align / dw_align / v_align: largest power of two (<= 16) dividing the pointer.
+hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D, int64_t M,
+                        bool is_bf16, int g_align, int s_align, int v_align, void* dW, bool dw_bf16, int dw_align,
+                        bool accumulate, void* ws, const WgradPlan& plan, const LaunchCfg& cfg, hipStream_t st);
+
+}  // namespace velora

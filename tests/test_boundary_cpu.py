@@ -1,0 +1,124 @@
+"""The C-ABI boundary without a GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "velora.h")
+
+
+@pytest.fixture(scope="module")
+def vl():
+    import __graft_entry__ as ge
+    ge.ensure_built()
+    import paper_2405_17991_amd as vl
+    return vl
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(velora_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(vl):
+    names = _declared_symbols()
+    assert {"velora_init_v", "velora_compress", "velora_reconstruct", "velora_weight_grad",
+            "velora_workspace_bytes", "velora_status_string", "velora_version"} <= set(names)
+    lib = ctypes.CDLL(vl.lib_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/velora.h but not exported"
+    from paper_2405_17991_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_status_strings(vl):
+    assert vl.velora_version() >= 100
+    for code, name in vl.STATUS.items():
+        assert vl.velora_status_string(code).startswith(name)
+    assert "unknown" in vl.velora_status_string(99)
+
+
+P = 0x7F0000001000      # a 4096-aligned, never dereferenced "device pointer"
+
+
+def test_compress_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    c = raw.velora_compress
+    assert c(None, P, 4, 8, 2, vl.BF16, P, None) == 1
+    assert c(P, None, 4, 8, 2, vl.BF16, P, None) == 1
+    assert c(P, P, 4, 8, 2, vl.BF16, None, None) == 1
+    assert c(P, P, 4, 8, 2, 7, P, None) == 3
+    assert c(P, P, 0, 8, 2, vl.BF16, P, None) == 2
+    assert c(P, P, 4, 8, 3, vl.BF16, P, None) == 2          # M does not divide D
+    assert c(P, P, 4, 8, 0, vl.BF16, P, None) == 2
+    assert c(P, P, 4, 8, 16, vl.BF16, P, None) == 2         # M > D
+    assert c(P, P, -1, 8, 2, vl.F32, P, None) == 2
+    assert c(P + 1, P, 4, 8, 2, vl.BF16, P, None) == 4      # odd address for a 2-byte type
+    assert c(P + 2, P, 4, 8, 2, vl.F32, P, None) == 4
+    assert c(P, P + 2, 4, 8, 2, vl.BF16, P, None) == 4      # v is float32
+    # the one cell of configuration 5 whose sub-token size does not divide D
+    assert c(P, P, 16384, 13824, 13, vl.BF16, P, None) == 2
+
+
+def test_weight_grad_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    w = raw.velora_weight_grad
+    N, O, D, M = 64, 32, 16, 4
+    need = vl.velora_workspace_bytes(vl.OP_WEIGHT_GRAD, N, D, O, M, vl.BF16)
+    assert need > 0
+    ok = (P, P, P, N, O, D, M, vl.BF16, P, vl.F32, 0, P, need, None)
+
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return w(*a)
+
+    assert call(a0=None) == 1 and call(a1=None) == 1 and call(a2=None) == 1 and call(a8=None) == 1
+    assert call(a7=5) == 3 and call(a9=5) == 3
+    assert call(a3=0) == 2 and call(a4=0) == 2 and call(a6=3) == 2 and call(a5=-16) == 2
+    assert call(a0=P + 1) == 4 and call(a8=P + 2) == 4
+    assert call(a11=None) == 5
+    assert call(a12=need - 1) == 5
+
+
+def test_init_v_and_reconstruct_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    need = vl.velora_workspace_bytes(vl.OP_INIT_V, 64, 16, 0, 4, vl.F32)
+    assert need > 0
+    i = raw.velora_init_v
+    assert i(None, 64, 16, 4, vl.F32, P, P, need, None) == 1
+    assert i(P, 64, 16, 4, vl.F32, None, P, need, None) == 1
+    assert i(P, 64, 16, 5, vl.F32, P, P, need, None) == 2
+    assert i(P, 64, 16, 4, 9, P, P, need, None) == 3
+    assert i(P, 64, 16, 4, vl.F32, P, None, need, None) == 5
+    assert i(P, 64, 16, 4, vl.F32, P, P, need - 1, None) == 5
+    assert i(P + 2, 64, 16, 4, vl.F32, P, P, need, None) == 4
+    r = raw.velora_reconstruct
+    assert r(None, P, 4, 8, 2, vl.BF16, P, None) == 1
+    assert r(P, P, 4, 8, 3, vl.BF16, P, None) == 2
+    assert r(P, P, 4, 8, 2, 4, P, None) == 3
+    assert r(P, P, 4, 8, 2, vl.BF16, P + 1, None) == 4
+
+
+def test_workspace_query(vl):
+    q = vl.velora_workspace_bytes
+    assert q(vl.OP_COMPRESS, 128, 64, 0, 4, vl.BF16) == 0
+    assert q(vl.OP_RECONSTRUCT, 128, 64, 0, 4, vl.BF16) == 0
+    assert q(vl.OP_WEIGHT_GRAD, 128, 64, 0, 4, vl.BF16) == 0      # O missing
+    assert q(vl.OP_WEIGHT_GRAD, 128, 64, 32, 5, vl.BF16) == 0     # M does not divide D
+    a = q(vl.OP_WEIGHT_GRAD, 16384, 4096, 4096, 16, vl.BF16)
+    assert a > 0 and a % 4 == 0
+    # partial-sum traffic stays a small fraction of what the kernels must move anyway
+    assert 2 * a <= 0.25 * (16384 * 4096 * 2 + 4096 * 4096 * 4)
+
+
+def test_no_fallback_when_library_missing(vl, monkeypatch):
+    from paper_2405_17991_amd import binding
+    monkeypatch.setattr(binding, "_LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
+    with pytest.raises(ImportError):
+        binding._load()

@@ -1,0 +1,278 @@
+"""GPU parity: libvelora (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Sizes here are ones the oracle finishes in
+seconds but that still span several tiles, ragged tails and every kernel
+variant (vectorised / generic, each MFMA tiling, the float32 path)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_helpers import (TOL_BF16, TOL_BF16_STORE, TOL_F32, TOL_F32_FROM_BF16, assert_bf16_store_matches,
+                         rel_fro, rel_max, to_dev, to_host_bits, to_host_f64)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vl():
+    import __graft_entry__ as ge
+    ge.ensure_built()
+    import paper_2405_17991_amd as vl
+    return vl
+
+
+def _torch():
+    import torch
+    return torch
+
+
+# ------------------------------------------------------------------ compress
+COMPRESS_CASES = [
+    # (N, D, d, dtype)  -- d spans every lane grouping of the vectorised kernel
+    (256, 64, 16, wl.F32),          # configuration 1
+    (37, 64, 4, wl.F32), (129, 96, 8, wl.F32), (300, 128, 32, wl.F32), (77, 192, 64, wl.F32),
+    (65, 256, 128, wl.F32), (33, 512, 256, wl.F32), (19, 1024, 512, wl.F32), (9, 2048, 1024, wl.F32),
+    (301, 64, 8, wl.BF16), (257, 64, 16, wl.BF16), (130, 96, 32, wl.BF16), (4 * 197, 768, 64, wl.BF16),
+    (515, 768, 128, wl.BF16), (203, 1024, 256, wl.BF16), (67, 1536, 512, wl.BF16), (41, 2048, 1024, wl.BF16),
+    (23, 4096, 2048, wl.BF16),
+    # generic kernel: d not a power of two times the vector width, d = 1, d = D
+    (50, 60, 12, wl.BF16), (50, 63, 7, wl.F32), (31, 33, 1, wl.BF16), (17, 100, 100, wl.F32),
+    (11, 3000, 3000, wl.BF16), (1, 8, 8, wl.BF16), (1, 1, 1, wl.F32),
+]
+
+
+@pytest.mark.parametrize("N,D,d,dtype", COMPRESS_CASES)
+def test_compress_matches_oracle(vl, N, D, d, dtype):
+    M = D // d
+    X = wl.random_tensor(N, D, dtype, seed=N + D + d)
+    v = wl.random_unit_v(d, seed=d)
+    S = vl.velora_compress(to_dev(X, dtype), to_dev(v, wl.F32), M)
+    _torch().cuda.synchronize()
+    S_exact, S_store = oracle.compress(X, v, M)
+    got = to_host_f64(S)
+    if dtype == wl.F32:
+        assert rel_fro(got, S_exact) <= TOL_F32
+        assert rel_max(got, S_exact) <= TOL_F32
+    else:
+        assert rel_fro(got, S_exact) <= TOL_BF16
+        assert rel_fro(got, S_exact) <= TOL_BF16_STORE
+        assert_bf16_store_matches(to_host_bits(S), S_exact, S_store, "compress")
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("d", [8, 64, 256, 12])
+def test_compress_gather_is_bit_exact(vl, dtype, d):
+    # v = e_j: compress degenerates to a gather, so the indexing (group) is
+    # checked with no rounding at all.
+    N, M = 131, 5
+    D = M * d
+    X = wl.random_tensor(N, D, dtype, seed=99)
+    for j in (0, d // 2, d - 1):
+        v = np.zeros(d, dtype=np.float32)
+        v[j] = 1.0
+        S = vl.velora_compress(to_dev(X, dtype), to_dev(v, wl.F32), M)
+        want = X.reshape(N, M, d)[:, :, j]
+        assert (to_host_bits(S) == want).all()
+
+
+def test_compress_unaligned_views_take_generic_path(vl):
+    torch = _torch()
+    N, D, d = 64, 256, 64
+    X = wl.random_tensor(N + 1, D, wl.BF16, seed=5)
+    v = wl.random_unit_v(d, seed=1)
+    Xd = to_dev(X, wl.BF16).reshape(-1)
+    Xv = Xd[1:1 + N * D].view(N, D)                 # 2-byte aligned only
+    assert Xv.data_ptr() % 16 != 0 and Xv.is_contiguous()
+    S = vl.velora_compress(Xv, to_dev(v, wl.F32), D // d)
+    Xh = np.ascontiguousarray(X.reshape(-1)[1:1 + N * D].reshape(N, D))
+    S_exact, S_store = oracle.compress(Xh, v, D // d)
+    assert_bf16_store_matches(to_host_bits(S), S_exact, S_store, "compress (unaligned)")
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ reconstruct
+@pytest.mark.parametrize("N,D,d,dtype", [
+    (256, 64, 16, wl.F32), (33, 96, 32, wl.BF16), (100, 768, 64, wl.BF16), (7, 60, 12, wl.BF16),
+    (9, 63, 7, wl.F32), (5, 33, 1, wl.F32), (3, 2048, 1024, wl.BF16),
+])
+def test_reconstruct_matches_oracle(vl, N, D, d, dtype):
+    M = D // d
+    S = wl.random_tensor(N, M, dtype, seed=3 + N)
+    v = wl.random_unit_v(d, seed=2 + d)
+    Xhat = vl.velora_reconstruct(to_dev(S, dtype), to_dev(v, wl.F32), D)
+    want = oracle.reconstruct(S, v, D)
+    got = to_host_f64(Xhat)
+    if dtype == wl.F32:
+        # one float32 multiply per element
+        assert np.abs(got - want).max() <= 2.0 ** -23 * np.abs(want).max()
+    else:
+        assert rel_fro(got, want) <= TOL_BF16_STORE
+        assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-30).all()
+
+
+def test_projection_is_idempotent_on_gpu(vl):
+    # compress(reconstruct(S)) = S |v|^2, through the HIP path alone
+    N, D, d = 200, 256, 32
+    S0 = wl.random_tensor(N, D // d, wl.F32, seed=8)
+    v = wl.random_unit_v(d, seed=8)
+    vd, Sd = to_dev(v, wl.F32), to_dev(S0, wl.F32)
+    S1 = vl.velora_compress(vl.velora_reconstruct(Sd, vd, D), vd, D // d)
+    np.testing.assert_allclose(to_host_f64(S1), S0.astype(np.float64), rtol=0, atol=2e-6 * np.abs(S0).max())
+
+
+# ------------------------------------------------------------------ init_v
+@pytest.mark.parametrize("N,D,d,dtype", [
+    (256, 64, 16, wl.F32), (4 * 197, 768, 64, wl.BF16), (1000, 768, 128, wl.BF16), (555, 1024, 256, wl.BF16),
+    (300, 2048, 1024, wl.BF16), (64, 4096, 2048, wl.BF16), (513, 96, 8, wl.F32), (100, 60, 12, wl.BF16),
+    (77, 63, 7, wl.F32), (40, 33, 1, wl.F32), (3, 3000, 3000, wl.BF16),
+])
+def test_init_v_matches_oracle(vl, N, D, d, dtype):
+    M = D // d
+    # a non-zero mean so that v is well conditioned (a zero-mean batch makes v a
+    # normalised noise vector: still defined, tested at full size below)
+    X32 = wl.random_tensor(N, D, wl.F32, seed=N + d).astype(np.float32)
+    shift = np.tile(np.linspace(-1.0, 2.0, d, dtype=np.float32), M)
+    X = wl.to_storage(X32 + shift[None, :], dtype)
+    v = vl.velora_init_v(to_dev(X, dtype), M)
+    v_ref, _, rc = oracle.init_v(X, M)
+    assert rc == 0
+    got = v.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(got - v_ref.astype(np.float64)) <= 1e-5
+    assert abs(np.linalg.norm(got) - 1.0) <= 1e-6
+
+
+def test_init_v_degenerate(vl):
+    torch = _torch()
+    X = torch.zeros((64, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(vl.VeloraError) as ei:
+        vl.velora_init_v(X, 4)
+    assert ei.value.status == 6
+    v = vl.velora_init_v(X, 4, allow_degenerate=True)
+    assert (v.cpu().numpy() == np.float32(1.0 / np.sqrt(32.0))).all()
+    Xn = torch.ones((64, 128), dtype=torch.float32, device="cuda")
+    Xn[3, 5] = float("inf")
+    v = vl.velora_init_v(Xn, 4, allow_degenerate=True)
+    assert (v.cpu().numpy() == np.float32(1.0 / np.sqrt(32.0))).all()
+
+
+# ------------------------------------------------------------------ weight_grad
+WGRAD_CASES = [
+    # (N, O, D, d, dtype)
+    (256, 64, 64, 16, wl.F32),                 # configuration 1
+    (100, 50, 24, 3, wl.F32), (333, 70, 40, 40, wl.F32), (64, 9, 12, 1, wl.F32),
+    # bf16 MFMA tilings: M = D/d picks (S columns per lane, sets); O picks the G tile
+    (1000, 256, 768, 64, wl.BF16),             # M = 12
+    (777, 384, 768, 128, wl.BF16),             # M = 6, ragged token tail
+    (515, 136, 2048, 128, wl.BF16),            # M = 16, partial O tile (136 = 128 + 8)
+    (600, 128, 5120, 256, wl.BF16),            # M = 20
+    (450, 72, 1376, 32, wl.BF16),              # M = 43 (odd: 2-byte S loads)
+    (500, 96, 1728, 32, wl.BF16),              # M = 54
+    (400, 64, 864, 32, wl.BF16),               # M = 27
+    (520, 120, 5120, 64, wl.BF16),             # M = 80
+    (300, 64, 1728, 8, wl.BF16),               # M = 216
+    (260, 44, 640, 8, wl.BF16),                # M = 80, O % 8 != 0 -> 8-byte G loads
+    (200, 36, 2400, 8, wl.BF16),               # M = 300 -> two group chunks
+    (150, 30, 64, 16, wl.BF16),                # O % 4 != 0 -> generic kernel
+    (130, 32, 40, 1, wl.BF16),                 # d = 1: dW = G^T S
+    (90, 48, 512, 512, wl.BF16),               # M = 1: rank-one gradient
+    (1, 16, 64, 16, wl.BF16), (31, 8, 16, 8, wl.BF16),
+]
+
+
+@pytest.mark.parametrize("N,O,D,d,dtype", WGRAD_CASES)
+def test_weight_grad_matches_bruteforce_oracle(vl, N, O, D, d, dtype):
+    M = D // d
+    G = wl.random_tensor(N, O, dtype, seed=N + O, stream=7, sigma=0.02)
+    S = wl.random_tensor(N, M, dtype, seed=N + M, stream=8)
+    v = wl.random_unit_v(d, seed=d + 1)
+    dW = vl.velora_weight_grad(to_dev(G, dtype), to_dev(S, dtype), to_dev(v, wl.F32), D)
+    want = oracle.weight_grad_bruteforce(G, S, v, D)
+    got = to_host_f64(dW)
+    assert got.shape == (O, D)
+    if dtype == wl.F32:
+        assert rel_fro(got, want) <= TOL_F32
+        assert rel_max(got, want) <= TOL_F32
+    else:
+        assert rel_fro(got, want) <= TOL_BF16
+        assert rel_fro(got, want) <= TOL_F32_FROM_BF16
+        assert rel_max(got, want) <= TOL_F32_FROM_BF16
+
+
+@pytest.mark.parametrize("N,O,D,d", [(515, 136, 2048, 128), (300, 64, 1728, 8), (150, 30, 64, 16)])
+def test_weight_grad_bf16_output_and_accumulate(vl, N, O, D, d):
+    torch = _torch()
+    M = D // d
+    G = wl.random_tensor(N, O, wl.BF16, seed=1, stream=7, sigma=0.02)
+    S = wl.random_tensor(N, M, wl.BF16, seed=2, stream=8)
+    v = wl.random_unit_v(d, seed=3)
+    Gd, Sd, vd = to_dev(G, wl.BF16), to_dev(S, wl.BF16), to_dev(v, wl.F32)
+    want = oracle.weight_grad_bruteforce(G, S, v, D)
+    # bf16 output: one extra rounding
+    dWb = vl.velora_weight_grad(Gd, Sd, vd, D, dw_dtype=torch.bfloat16)
+    assert dWb.dtype == torch.bfloat16
+    assert rel_fro(to_host_f64(dWb), want) <= TOL_BF16_STORE
+    # accumulate into an existing float32 gradient
+    base = wl.random_tensor(O, D, wl.F32, seed=4, sigma=0.5)
+    dW = to_dev(base, wl.F32)
+    vl.velora_weight_grad(Gd, Sd, vd, D, dW=dW, accumulate=True)
+    assert rel_fro(to_host_f64(dW), base.astype(np.float64) + want) <= TOL_F32_FROM_BF16
+    # accumulate into bf16
+    baseb = wl.random_tensor(O, D, wl.BF16, seed=5, sigma=0.5)
+    dWa = to_dev(baseb, wl.BF16)
+    vl.velora_weight_grad(Gd, Sd, vd, D, dW=dWa, accumulate=True)
+    assert rel_fro(to_host_f64(dWa), wl.to_f64(baseb, wl.BF16) + want) <= TOL_BF16_STORE
+
+
+def test_weight_grad_single_one_copies_reconstructed_token(vl):
+    # G = e_n e_o^T: row o of dW is the reconstructed token n, everything else 0.
+    N, O, D, d = 160, 128, 256, 32
+    M = D // d
+    S = wl.random_tensor(N, M, wl.BF16, seed=12)
+    v = wl.random_unit_v(d, seed=12)
+    Xhat = oracle.reconstruct(S, v, D)
+    for (n, o) in [(0, 0), (159, 127), (77, 5), (31, 64), (32, 63)]:
+        G = np.zeros((N, O), dtype=np.uint16)
+        G[n, o] = 0x3F80                                    # 1.0 in bf16
+        dW = to_host_f64(vl.velora_weight_grad(to_dev(G, wl.BF16), to_dev(S, wl.BF16), to_dev(v, wl.F32), D))
+        np.testing.assert_allclose(dW[o], Xhat[n], rtol=2e-7, atol=0)
+        mask = np.ones(O, dtype=bool)
+        mask[o] = False
+        assert (dW[mask] == 0).all()
+
+
+def test_weight_grad_is_deterministic(vl):
+    N, O, D, d = 2048, 256, 1024, 64
+    G = wl.random_tensor(N, O, wl.BF16, seed=21, sigma=0.02)
+    S = wl.random_tensor(N, D // d, wl.BF16, seed=22)
+    v = wl.random_unit_v(d, seed=23)
+    Gd, Sd, vd = to_dev(G, wl.BF16), to_dev(S, wl.BF16), to_dev(v, wl.F32)
+    a = vl.velora_weight_grad(Gd, Sd, vd, D).cpu().numpy()
+    for _ in range(3):
+        b = vl.velora_weight_grad(Gd, Sd, vd, D).cpu().numpy()
+        assert (a.view(np.uint32) == b.view(np.uint32)).all()
+
+
+def test_end_to_end_config1(vl):
+    # BASELINE configuration 1 through the whole path: init_v -> compress -> weight_grad
+    sh = wl.shape_by_name("cfg1_tiny")
+    X, G = wl.make_X(sh), wl.make_G(sh)
+    Xd, Gd = to_dev(X, sh.dtype), to_dev(G, sh.dtype)
+    v = vl.velora_init_v(Xd, sh.M)
+    S = vl.velora_compress(Xd, v, sh.M)
+    dW = vl.velora_weight_grad(Gd, S, v, sh.D)
+    v_ref, _, _ = oracle.init_v(X, sh.M)
+    S_exact, S_store = oracle.compress(X, v_ref, sh.M)
+    want = oracle.weight_grad_bruteforce(G, S_store, v_ref, sh.D)
+    assert np.linalg.norm(v.cpu().numpy().astype(np.float64) - v_ref) <= 1e-5
+    assert rel_fro(to_host_f64(S), S_exact) <= TOL_F32
+    assert rel_fro(to_host_f64(dW), want) <= TOL_F32
+    assert rel_max(to_host_f64(dW), want) <= TOL_F32
+
+
+def test_shape_error_reaches_python(vl):
+    torch = _torch()
+    X = torch.zeros((4, 13824), dtype=torch.bfloat16, device="cuda")
+    v = torch.zeros(1024, dtype=torch.float32, device="cuda")
+    with pytest.raises(vl.VeloraError) as ei:
+        vl.velora_compress(X, v, 13)                        # 13824 / 1024 is not an integer
+    assert ei.value.status == 2

@@ -17,7 +17,9 @@ bf16 tensors are returned as uint16 bit patterns (numpy has no bf16).
 """
 from __future__ import annotations
 
-from dataclasses import dataclass, field
+import concurrent.futures
+import os
+from dataclasses import dataclass
 from typing import List, Optional
 
 import numpy as np
@@ -156,11 +158,39 @@ def reduced(shape: Shape, N: int) -> Shape:
 # --------------------------------------------------------------------------
 # generators
 # --------------------------------------------------------------------------
-def _rng(seed: int, stream: int) -> np.random.Generator:
-    return np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64(stream)]))
+def _rng(seed: int, stream: int, block: int = 0) -> np.random.Generator:
+    """Counter-based generator keyed by (seed, stream) with the row-block index
+    in the counter's top word, so every block of rows is an independent,
+    reproducible stream whatever the number of worker threads."""
+    return np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64(stream)],
+                                                counter=[0, 0, 0, np.uint64(block)]))
 
 
-_ROWS_PER_CHUNK = 2048
+_ROWS_PER_BLOCK = 256
+
+
+def _workers() -> int:
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:  # pragma: no cover
+        n = os.cpu_count() or 1
+    return max(1, min(n, 16))
+
+
+def _fill_rows(out: np.ndarray, fn) -> None:
+    """out[r0:r1] = fn(block_index, n_rows) for consecutive blocks of rows."""
+    N = out.shape[0]
+    blocks = [(b, r0, min(N, r0 + _ROWS_PER_BLOCK)) for b, r0 in enumerate(range(0, N, _ROWS_PER_BLOCK))]
+
+    def run(item):
+        b, r0, r1 = item
+        out[r0:r1] = fn(b, r1 - r0)
+
+    if len(blocks) == 1:
+        run(blocks[0])
+        return
+    with concurrent.futures.ThreadPoolExecutor(max_workers=_workers()) as ex:
+        list(ex.map(run, blocks))
 
 
 def make_X(shape: Shape) -> np.ndarray:
@@ -173,7 +203,6 @@ def make_X(shape: Shape) -> np.ndarray:
     outlier_chan  N(0,1) with round(0.01*D) fixed channels multiplied by 20
     """
     N, D = shape.N, shape.D
-    rng = _rng(shape.seed, 1)
     aux = _rng(shape.seed, 2)
     scale: Optional[np.ndarray] = None
     if shape.x_dist == "chan_scale":
@@ -183,29 +212,34 @@ def make_X(shape: Shape) -> np.ndarray:
         idx = aux.choice(D, size=k, replace=False)
         scale = np.ones(D, dtype=np.float32)
         scale[idx] = 20.0
-    out = np.empty((N, D), dtype=np.float32 if shape.dtype == F32 else np.uint16)
-    for r0 in range(0, N, _ROWS_PER_CHUNK):
-        r1 = min(N, r0 + _ROWS_PER_CHUNK)
-        blk = rng.standard_normal((r1 - r0, D), dtype=np.float32)
+
+    def block(b: int, rows: int) -> np.ndarray:
+        rng = _rng(shape.seed, 1, b)
+        blk = rng.standard_normal((rows, D), dtype=np.float32)
         if shape.x_dist == "student_t4":
             # t_4 = Z / sqrt(chi2_4 / 4); chi2_4 = 2 * Gamma(shape=2)
-            chi = rng.standard_gamma(2.0, size=(r1 - r0, D), dtype=np.float32) * np.float32(2.0)
+            chi = rng.standard_gamma(2.0, size=(rows, D), dtype=np.float32) * np.float32(2.0)
             blk = blk / np.sqrt(chi / np.float32(4.0)) / np.float32(np.sqrt(2.0))
         if scale is not None:
             blk = blk * scale[None, :]
-        out[r0:r1] = to_storage(blk, shape.dtype)
+        return to_storage(blk, shape.dtype)
+
+    out = np.empty((N, D), dtype=np.float32 if shape.dtype == F32 else np.uint16)
+    _fill_rows(out, block)
     return out
 
 
 def make_G(shape: Shape) -> np.ndarray:
     """Output gradient G[N, O] ~ N(0, g_sigma) in storage dtype."""
     N, O = shape.N, shape.O
-    rng = _rng(shape.seed, 3)
+
+    def block(b: int, rows: int) -> np.ndarray:
+        rng = _rng(shape.seed, 3, b)
+        blk = rng.standard_normal((rows, O), dtype=np.float32) * np.float32(shape.g_sigma)
+        return to_storage(blk, shape.dtype)
+
     out = np.empty((N, O), dtype=np.float32 if shape.dtype == F32 else np.uint16)
-    for r0 in range(0, N, _ROWS_PER_CHUNK):
-        r1 = min(N, r0 + _ROWS_PER_CHUNK)
-        blk = rng.standard_normal((r1 - r0, O), dtype=np.float32) * np.float32(shape.g_sigma)
-        out[r0:r1] = to_storage(blk, shape.dtype)
+    _fill_rows(out, block)
     return out
 
 
