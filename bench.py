@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Benchmark of the VeLoRA hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input
+for one linear layer: compress(X, v) -> S, then weight_grad(G, S, v) -> dW
+(init_v is a one-off and is not part of the steady-state step).  Inputs are
+resident in HBM before the timed region starts; the step rotates through a ring
+of distinct buffer sets larger than the 256 MB last-level cache so that no
+re-read is served from cache.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+prints ONE JSON line.  `value` is the whole step's algorithmic bytes per second;
+`roofline` prices the dominant kernel (compress) against the HBM peak from HIP
+event timings taken inside the timed region; `weight_grad` does the same for
+the gradient kernels; `shapes` lists every layer shape of the five
+configurations; `cpu_baseline` is the CPU oracle timed on this machine's host
+cores on a stated sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA peak
+RING_BYTES = 1 << 30            # rotate through at least this much distinct memory
+DEFAULT_WORKLOAD = "cfg4_down"  # LLaMA-7B-like MLP down projection (D=11008 -> O=4096, d=256)
+METRIC = "compress GB/s (% HBM peak); weight-grad TFLOP/s (% MFMA peak), 1 MI355X"
+
+
+def _parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--dw-dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape sweep")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--shape-steps", type=int, default=20)
+    return ap.parse_args()
+
+
+class Ring:
+    """R distinct (X, G, S, dW) buffer sets for one layer shape."""
+
+    def __init__(self, vl, torch, sh, X0, G0, v, dw_dtype):
+        import workloads as wl
+        dw_b = 2 if dw_dtype == torch.bfloat16 else 4
+        set_bytes = (sh.N * sh.D + sh.N * sh.O + sh.N * sh.M) * sh.elem_bytes + sh.O * sh.D * dw_b
+        self.R = max(2, -(-RING_BYTES // set_bytes))
+        self.sh, self.v, self.vl = sh, v, vl
+        self.X = [X0] + [X0.clone() for _ in range(self.R - 1)]
+        self.G = [G0] + [G0.clone() for _ in range(self.R - 1)]
+        self.S = [torch.empty((sh.N, sh.M), dtype=X0.dtype, device=X0.device) for _ in range(self.R)]
+        self.dW = [torch.empty((sh.O, sh.D), dtype=dw_dtype, device=X0.device) for _ in range(self.R)]
+        in_dt = vl.BF16 if sh.dtype == wl.BF16 else vl.F32
+        need = vl.velora_workspace_bytes(vl.OP_WEIGHT_GRAD, sh.N, sh.D, sh.O, sh.M, in_dt)
+        self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X0.device)
+        self.ws_bytes = need
+
+    def compress(self, i):
+        r = i % self.R
+        self.vl.velora_compress(self.X[r], self.v, self.sh.M, S=self.S[r])
+
+    def wgrad(self, i):
+        r = i % self.R
+        self.vl.velora_weight_grad(self.G[r], self.S[r], self.v, self.sh.D, dW=self.dW[r], ws=self.ws)
+
+    def step(self, i):
+        self.compress(i)
+        self.wgrad(i)
+
+
+def _time_steps(torch, ring, steps, warmup, with_events):
+    """-> (seconds for `steps` steps, mean compress us, mean wgrad us)."""
+    for i in range(warmup):
+        ring.step(i)
+    ev = None
+    if with_events:
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        if ev:
+            ev[i][0].record()
+            ring.compress(warmup + i)
+            ev[i][1].record()
+            ring.wgrad(warmup + i)
+            ev[i][2].record()
+        else:
+            ring.step(warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    if not ev:
+        return dt, None, None
+    c = sum(e[0].elapsed_time(e[1]) for e in ev) / steps * 1e3
+    w = sum(e[1].elapsed_time(e[2]) for e in ev) / steps * 1e3
+    return dt, c, w
+
+
+def _device_inputs(torch, sh, dev):
+    """Synthetic layer inputs drawn on the device (sweep only: the kernels have
+    no data-dependent control flow, so timing needs the shape and dtype, and
+    roughly the distribution; parity is established by the tests on the
+    host-generated inputs)."""
+    import workloads as wl
+    g = torch.Generator(device=dev)
+    g.manual_seed(sh.seed)
+    dt = torch.float32 if sh.dtype == wl.F32 else torch.bfloat16
+    X = torch.randn((sh.N, sh.D), generator=g, device=dev, dtype=torch.float32)
+    if sh.x_dist == "chan_scale":
+        X *= torch.empty(sh.D, device=dev).uniform_(0.5, 2.0, generator=g)
+    elif sh.x_dist == "student_t4":
+        chi = torch.randn((4, sh.N, sh.D), generator=g, device=dev).square_().sum(0)
+        X = X / torch.sqrt(chi / 4.0) / (2.0 ** 0.5)
+        del chi
+    elif sh.x_dist == "outlier_chan":
+        idx = torch.randperm(sh.D, generator=g, device=dev)[: int(round(0.01 * sh.D))]
+        X[:, idx] *= 20.0
+    G = torch.randn((sh.N, sh.O), generator=g, device=dev, dtype=torch.float32) * sh.g_sigma
+    return X.to(dt), G.to(dt)
+
+
+def _shape_record(sh, c_us, w_us, dw_b, ws_bytes):
+    cb, wb = sh.compress_bytes(), sh.wgrad_bytes(dw_b)
+    rec = {
+        "shape": sh.name, "cfg": sh.cfg, "N": sh.N, "D": sh.D, "O": sh.O, "d": sh.d, "M": sh.M,
+        "compress_us": round(c_us, 2), "compress_GBps": round(cb / c_us * 1e-3, 1),
+        "compress_frac_hbm": round(cb / c_us * 1e-3 / HBM_PEAK_GBPS, 4),
+        "wgrad_us": round(w_us, 2), "wgrad_GBps": round(wb / w_us * 1e-3, 1),
+        "wgrad_frac_hbm": round(wb / w_us * 1e-3 / HBM_PEAK_GBPS, 4),
+        "wgrad_TFLOPs_factored": round(sh.wgrad_flops_factored() / w_us * 1e-6, 2),
+        "wgrad_TFLOPs_dense_equiv": round(sh.wgrad_flops_dense() / w_us * 1e-6, 1),
+        "wgrad_ws_MB": round(ws_bytes / 1e6, 2),
+    }
+    return rec
+
+
+def _cpu_baseline(sh, Xh, Gh, v_ref):
+    """The oracle as it stands, on this machine's host cores, on a bounded sample:
+    compress over all tokens, the factored weight gradient over a prefix of the
+    output features sized to a few GFLOP, scaled linearly in O."""
+    import numpy as np
+    import oracle
+    threads = oracle.default_threads()
+    t0 = time.perf_counter()
+    _, S_store = oracle.compress(Xh, v_ref, sh.M, threads=threads)
+    t_c = time.perf_counter() - t0
+    budget_flops = 6e9
+    o_s = int(min(sh.O, max(16, budget_flops // (2 * sh.N * sh.M))))
+    Gs = np.ascontiguousarray(Gh[:, :o_s])
+    t0 = time.perf_counter()
+    oracle.weight_grad_factored(Gs, S_store, v_ref, sh.D, threads=threads)
+    t_w = (time.perf_counter() - t0) * (sh.O / o_s)
+    bytes_step = sh.compress_bytes() + sh.wgrad_bytes(4)
+    return {
+        "value": round(bytes_step / (t_c + t_w) * 1e-9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": (f"oracle.compress on all {sh.N} tokens ({t_c:.2f} s) + oracle.weight_grad_factored on the first "
+                   f"{o_s} of {sh.O} output features, time scaled by {sh.O / o_s:.2f} ({t_w:.2f} s); "
+                   "plain C++ -O2 double precision, std::thread over the listed cores"),
+        "compress_GBps": round(sh.compress_bytes() / t_c * 1e-9, 3),
+        "wgrad_GBps": round(sh.wgrad_bytes(4) / t_w * 1e-9, 3),
+    }
+
+
+def _traffic(workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    if os.path.exists(path):
+        try:
+            with open(path) as f:
+                return json.load(f)
+        except Exception:
+            return None
+    return None
+
+
+def main():
+    args = _parse()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (one GPU per box, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import __graft_entry__ as ge
+    ge.ensure_built()
+    import paper_2405_17991_amd as vl
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    dw_dtype = torch.float32 if args.dw_dtype == "f32" else torch.bfloat16
+    dw_b = 4 if args.dw_dtype == "f32" else 2
+
+    # ---------------- headline workload: host-generated inputs (same as the parity tests)
+    sh = wl.shape_by_name(args.workload)
+    Xh, Gh = wl.make_X(sh), wl.make_G(sh)
+    tdt = torch.float32 if sh.dtype == wl.F32 else torch.bfloat16
+    X0 = torch.from_numpy(Xh).view(tdt).to(dev) if sh.dtype == wl.BF16 else torch.from_numpy(Xh).to(dev)
+    G0 = torch.from_numpy(Gh).view(tdt).to(dev) if sh.dtype == wl.BF16 else torch.from_numpy(Gh).to(dev)
+    v = vl.velora_init_v(X0, sh.M)           # first batch = this batch (one-off, untimed)
+    ring = Ring(vl, torch, sh, X0, G0, v, dw_dtype)
+
+    dt, _, _ = _time_steps(torch, ring, args.steps, args.warmup, with_events=False)
+    _, c_us, w_us = _time_steps(torch, ring, args.steps, 2, with_events=True)
+    ms_per_step = dt / args.steps * 1e3
+    step_bytes = sh.compress_bytes() + sh.wgrad_bytes(dw_b)
+    value = step_bytes / (dt / args.steps) * 1e-9
+
+    cb, wb = sh.compress_bytes(), sh.wgrad_bytes(dw_b)
+    c_gbps, w_gbps = cb / c_us * 1e-3, wb / w_us * 1e-3
+    traffic = _traffic(args.workload)
+    out = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if sh.dtype == wl.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": sh.name, "N": sh.N, "D": sh.D, "O": sh.O, "d": sh.d, "M": sh.M,
+                   "x_dist": sh.x_dist, "dW_dtype": args.dw_dtype, "ring_sets": ring.R,
+                   "step": "compress + weight_grad (2 kernels)"},
+        "roofline": {"kernel": "compress", "bound": "hbm", "achieved": round(c_gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(c_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": (traffic or {}).get("compress"), "avg_us": round(c_us, 2),
+                     "algorithmic_bytes": cb},
+        "weight_grad": {"kernels": "wgrad_partial + wgrad_expand", "bound": "hbm", "achieved": round(w_gbps, 1),
+                        "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(w_gbps / HBM_PEAK_GBPS, 4),
+                        "traffic": (traffic or {}).get("weight_grad"), "avg_us": round(w_us, 2),
+                        "algorithmic_bytes": wb,
+                        "TFLOPs_factored": round(sh.wgrad_flops_factored() / w_us * 1e-6, 2),
+                        "TFLOPs_dense_equiv": round(sh.wgrad_flops_dense() / w_us * 1e-6, 1),
+                        "frac_mfma_dense_equiv": round(sh.wgrad_flops_dense() / w_us * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                        "workspace_MB": round(ring.ws_bytes / 1e6, 2)},
+    }
+    v_host = v.cpu().numpy()
+    del ring, X0, G0
+    torch.cuda.empty_cache()
+
+    # ---------------- every layer shape of the five configurations
+    if not args.no_shapes:
+        recs = []
+        for s in wl.valid_shapes():
+            Xs, Gs = _device_inputs(torch, s, dev)
+            vs = vl.velora_init_v(Xs, s.M, allow_degenerate=True)
+            r = Ring(vl, torch, s, Xs, Gs, vs, dw_dtype)
+            _, cu, wu = _time_steps(torch, r, args.shape_steps, 3, with_events=True)
+            recs.append(_shape_record(s, cu, wu, dw_b, r.ws_bytes))
+            del r, Xs, Gs
+            torch.cuda.empty_cache()
+        out["shapes"] = recs
+
+    # ---------------- CPU oracle on the same workload
+    if not args.no_cpu_baseline:
+        import oracle
+        v_ref, _, _ = oracle.init_v(Xh, sh.M)
+        out["cpu_baseline"] = _cpu_baseline(sh, Xh, Gh, v_ref)
+        out["cpu_baseline"]["init_v_l2_diff_gpu_vs_oracle"] = float(
+            np.linalg.norm(v_host.astype(np.float64) - v_ref.astype(np.float64)))
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
