@@ -80,30 +80,44 @@ class Ring:
         self.wgrad(i)
 
 
+EVENT_BATCH = 10   # launches between two HIP events
+
+
 def _time_steps(torch, ring, steps, warmup, with_events):
-    """-> (seconds for `steps` steps, mean compress us, mean wgrad us)."""
+    """-> (seconds for `steps` steps, mean compress us, mean wgrad us).
+
+    Without events: `steps` steps back to back, wall clock around a
+    synchronise on both sides (this is what `value` is computed from).
+    With events: the same launches, grouped so that HIP events on the launch
+    stream bracket EVENT_BATCH launches of one entry point at a time; an event
+    pair around a single 20-100 us kernel would add its own few us of
+    dispatch latency to every sample."""
     for i in range(warmup):
         ring.step(i)
-    ev = None
-    if with_events:
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        if ev:
-            ev[i][0].record()
-            ring.compress(warmup + i)
-            ev[i][1].record()
-            ring.wgrad(warmup + i)
-            ev[i][2].record()
-        else:
+    if not with_events:
+        t0 = time.perf_counter()
+        for i in range(steps):
             ring.step(warmup + i)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, None, None
+    n_batches = max(1, steps // EVENT_BATCH)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_batches)]
+    t0 = time.perf_counter()
+    for b in range(n_batches):
+        i0 = warmup + b * EVENT_BATCH
+        ev[b][0].record()
+        for i in range(EVENT_BATCH):
+            ring.compress(i0 + i)
+        ev[b][1].record()
+        for i in range(EVENT_BATCH):
+            ring.wgrad(i0 + i)
+        ev[b][2].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    if not ev:
-        return dt, None, None
-    c = sum(e[0].elapsed_time(e[1]) for e in ev) / steps * 1e3
-    w = sum(e[1].elapsed_time(e[2]) for e in ev) / steps * 1e3
+    n = n_batches * EVENT_BATCH
+    c = sum(e[0].elapsed_time(e[1]) for e in ev) / n * 1e3
+    w = sum(e[1].elapsed_time(e[2]) for e in ev) / n * 1e3
     return dt, c, w
 
 

@@ -105,14 +105,24 @@ __global__ __launch_bounds__(256) void colsum_generic_kernel(const typename E::t
 }
 
 // mean[j] = (sum over blocks of partial[b][j]) / n_sub, in float64, fixed order.
+// 32 columns x 8 slices of the block axis per 256-thread block.
 __global__ __launch_bounds__(256) void colsum_combine_kernel(const float* __restrict__ partial,
                                                             double* __restrict__ mean, int blocks, int d,
                                                             double inv_count) {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= d) return;
+    __shared__ double red[8][32];
+    const int c = threadIdx.x & 31;
+    const int r = threadIdx.x >> 5;
+    const int j = blockIdx.x * 32 + c;
     double s = 0.0;
-    for (int b = 0; b < blocks; ++b) s += static_cast<double>(partial[static_cast<int64_t>(b) * d + j]);
-    mean[j] = s * inv_count;
+    if (j < d)
+        for (int b = r; b < blocks; b += 8) s += static_cast<double>(partial[static_cast<int64_t>(b) * d + j]);
+    red[r][c] = s;
+    __syncthreads();
+    if (r == 0 && j < d) {
+        double t = 0.0;
+        for (int rr = 0; rr < 8; ++rr) t += red[rr][c];
+        mean[j] = t * inv_count;
+    }
 }
 
 // v = mean / ||mean||; flag = 0, or 6 (and v = 1/sqrt(d)) when the mean is zero
@@ -225,7 +235,7 @@ hipError_t launch_init_v(const void* X, float* v, int64_t n_sub, int64_t d, bool
                            : colsum_any<F32Elem>(X, partial, n_sub, d, vec_ok, plan.blocks, st);
     if (e != hipSuccess) return e;
     const int di = static_cast<int>(d);
-    hipLaunchKernelGGL(colsum_combine_kernel, dim3(static_cast<unsigned>(ceil_div(d, 256))), dim3(256), 0, st,
+    hipLaunchKernelGGL(colsum_combine_kernel, dim3(static_cast<unsigned>(ceil_div(d, 32))), dim3(256), 0, st,
                        partial, mean, plan.blocks, di, 1.0 / static_cast<double>(n_sub));
     e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -31,11 +31,16 @@ hipError_t launch_init_v(const void* X, float* v, int64_t n_sub, int64_t d, bool
                          void* ws, const InitVPlan& plan, hipStream_t st);
 
 // ---- wgrad.hip ----
-// Workspace layout: float partial[splits][O][Mp], Mp = M rounded up to 4.
+// Workspace layout: float partial[splits][O][Mp] (Mp = M rounded up to 4),
+// then, for bf16 inputs, S re-laid out as MFMA fragments
+// (ceil(N/32) steps x tiles_packed tiles x 1 KiB).
 struct WgradPlan {
     int splits;        // number of token ranges (split-K)
     int64_t rows_per_split;
     int64_t Mp;
+    int64_t tiles_packed;
+    size_t partial_bytes;
+    size_t packed_bytes;
     size_t ws_bytes;
 };
 WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, const LaunchCfg& cfg);

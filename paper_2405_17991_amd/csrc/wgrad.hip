@@ -30,45 +30,80 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // K-consecutive bf16 in four VGPRs) and receives D[4*(l/16) + 0..3][l%16].
 // Here K runs over tokens n, A rows over sub-token groups g, B columns over
 // output features o.  Both operands are stored with n as the SLOW axis
-// (G[n][o], S[n][g]), so the eight K-consecutive values a lane needs are eight
-// different rows.  Instead of staging through LDS, a lane loads eight rows x
-// C columns (C*2 bytes per row, coalesced across the 16 lanes that share a
-// K-group) and transposes the 8 x C block of 16-bit values inside its own
-// registers with v_perm_b32; that yields C ready fragments for C different
-// columns.  The column a lane/fragment pair stands for is strided
-// (o = o0 + jj*CW + c), which is harmless: MFMA rows/columns need not be
-// adjacent in memory, the epilogue undoes the mapping.
+// (G[n][o], S[n][g]), so the eight K-consecutive values a lane needs sit in
+// eight different rows.
+//
+// G (the big operand, read exactly once from HBM): a lane loads eight rows x
+// CW columns (CW*2 bytes per row, coalesced across the 16 lanes that share a
+// K-group) and transposes the 8 x CW block of 16-bit values inside its own
+// registers with v_perm_b32, which yields CW ready B fragments for CW
+// different columns.  The column a lane/fragment pair stands for is strided
+// (o = o0 + jj*CW + c); MFMA columns need not be adjacent in memory and the
+// epilogue undoes the mapping.  No LDS is involved, so the loads of several
+// future steps can be kept in flight in a register ring (NST stages), which is
+// what a bandwidth-bound kernel needs.
+//
+// S (small, re-read by every column tile): a tiny pre-pass re-lays it out as
+// ready-made A fragments (pack kernel below), so the main loop fetches one
+// 16-byte fragment per lane and 16-group tile with no transposition at all.
 //
 //   CW   G columns per lane (8 -> 16-byte loads, 4 -> 8-byte)
-//   CWS  S columns per lane (8, 4, 2 or 1)
-//   NS   S load sets; the block covers 16*CWS*NS groups g
+//   GT   16-group tiles per block (the block covers 16*GT groups g)
+//   NST  ring depth: 32-token steps in flight per wave
 // Block = 4 waves; the waves take alternate 32-token steps of the block's token
 // range and are summed through LDS at the end in a fixed order.
-// grid = (o tiles of 16*CW, splits, g chunks of 16*CWS*NS)
+// grid = (o tiles of 16*CW, splits, g chunks of 16*GT)
 // ---------------------------------------------------------------------------
+constexpr int kStep = 32;        // tokens per MFMA K-step
+constexpr int kWavesPerBlock = 4;
+
+// Packed S: for every 32-token step and 16-group tile, the 64 lanes' A
+// fragments back to back (1 KiB): entry [(step*tiles + tile)*64 + lane] holds
+// S[step*32 + 8*(lane/16) + 0..7][tile*16 + lane%16], zero outside S.
+__global__ __launch_bounds__(256) void wgrad_pack_s_kernel(const uint16_t* __restrict__ S, uint4* __restrict__ packed,
+                                                          int64_t N, int64_t M, int64_t tiles, int64_t total) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int lane = static_cast<int>(i & 63);
+    const int64_t st = i >> 6;
+    const int64_t step = st / tiles;
+    const int64_t tile = st - step * tiles;
+    const int64_t g = tile * 16 + (lane & 15);
+    const int64_t n0 = step * kStep + (lane >> 4) * 8;
+    uint32_t h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int64_t n = n0 + e;
+        h[e] = (g < M && n < N) ? static_cast<uint32_t>(S[n * M + g]) : 0u;
+    }
+    packed[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
+// cache-policy operand of the buffer loads that stream G: bit 1 = non-temporal
+// (the data is read exactly once)
+constexpr int kStreamAux = 2;
+
 template <int NDW>
 struct RawRow {
     uint32_t w[NDW];
 };
 
-// Load C consecutive bf16 (C*2 bytes) from a wave-uniform base plus a 32-bit
-// per-lane byte offset, so the address can be formed as SGPR pair + VGPR.
-template <int C>
-__device__ __forceinline__ RawRow<(C >= 2 ? C / 2 : 1)> load_cols(const char* base, uint32_t voff, bool ok) {
-    RawRow<(C >= 2 ? C / 2 : 1)> r;
-    const char* p = base + voff;
-    if constexpr (C == 8) {
-        uint4 q = make_uint4(0u, 0u, 0u, 0u);
-        if (ok) q = *reinterpret_cast<const uint4*>(p);
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// CW consecutive bf16 through a buffer descriptor (wave-uniform base in SGPRs,
+// 32-bit per-lane byte offset).  A raw buffer load whose offset is not below
+// the descriptor's size returns zero without touching memory; the kernel uses
+// that for every edge (rows past the token range, columns past O, steps past
+// the end) instead of branching.
+template <int CW>
+__device__ __forceinline__ RawRow<CW / 2> load_g(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff) {
+    RawRow<CW / 2> r;
+    if constexpr (CW == 8) {
+        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, kStreamAux);
         r.w[0] = q.x; r.w[1] = q.y; r.w[2] = q.z; r.w[3] = q.w;
-    } else if constexpr (C == 4) {
-        uint2 q = make_uint2(0u, 0u);
-        if (ok) q = *reinterpret_cast<const uint2*>(p);
-        r.w[0] = q.x; r.w[1] = q.y;
-    } else if constexpr (C == 2) {
-        r.w[0] = ok ? *reinterpret_cast<const uint32_t*>(p) : 0u;
     } else {
-        r.w[0] = ok ? static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(p)) : 0u;
+        const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, 0, kStreamAux);
+        r.w[0] = q.x; r.w[1] = q.y;
     }
     return r;
 }
@@ -88,71 +123,20 @@ __device__ __forceinline__ bf16x8 column_fragment(const RawRow<NDW> (&rows)[8], 
     return __builtin_bit_cast(bf16x8, q);
 }
 
-template <int CW, int CWS, int NS>
-struct WgradRaw {
+template <int CW, int GT>
+struct WgradStage {
     RawRow<CW / 2> g[8];
-    RawRow<(CWS >= 2 ? CWS / 2 : 1)> s[NS][8];
+    uint4 s[GT];
 };
 
-template <int CW, int CWS, int NS>
-struct WgradFrags {
-    bf16x8 g[CW];
-    bf16x8 s[NS * CWS];
-};
-
-// One 32-token step of this wave.  gptr/sptr are wave-uniform and point at the
-// step's first token (row) and the block's first column; gvoff/svoff hold the
-// lane's (8*q rows, column) byte offset.  EDGE adds the bounds predicates
-// needed for a ragged last step or a partial column tile; out-of-range
-// elements read as zero and are never dereferenced.
-template <int CW, int CWS, int NS, bool EDGE>
-__device__ __forceinline__ void wgrad_load(WgradRaw<CW, CWS, NS>& t, const char* gptr, const char* sptr,
-                                           uint32_t gvoff, uint32_t svoff, uint32_t g_row_bytes,
-                                           uint32_t s_row_bytes, int rows_left, int q, bool col_ok,
-                                           const bool (&g_ok)[NS]) {
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const bool ok = !EDGE || (col_ok && (q * 8 + r) < rows_left);
-        t.g[r] = load_cols<CW>(gptr + static_cast<uint64_t>(r) * g_row_bytes, gvoff, ok);
-    }
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const bool ok = g_ok[s] && (!EDGE || (q * 8 + r) < rows_left);
-            t.s[s][r] = load_cols<CWS>(sptr + static_cast<uint64_t>(r) * s_row_bytes, svoff + s * 16 * CWS * 2, ok);
-        }
-}
-
-template <int CW, int CWS, int NS>
-__device__ __forceinline__ void wgrad_transpose(const WgradRaw<CW, CWS, NS>& t, WgradFrags<CW, CWS, NS>& f) {
-#pragma unroll
-    for (int c = 0; c < CW; ++c) f.g[c] = column_fragment(t.g, c);
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-        for (int cs = 0; cs < CWS; ++cs) f.s[s * CWS + cs] = column_fragment(t.s[s], cs);
-}
-
-template <int CW, int CWS, int NS>
-__device__ __forceinline__ void wgrad_mma(const WgradFrags<CW, CWS, NS>& f, f32x4 (&acc)[NS * CWS][CW]) {
-#pragma unroll
-    for (int a = 0; a < NS * CWS; ++a)
-#pragma unroll
-        for (int c = 0; c < CW; ++c)
-            acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.s[a], f.g[c], acc[a][c], 0, 0, 0);
-}
-
-template <int CW, int CWS, int NS>
+template <int CW, int GT, int NST>
 __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t* __restrict__ G,
-                                                                const uint16_t* __restrict__ S,
+                                                                const uint4* __restrict__ Spk,
                                                                 float* __restrict__ partial, int64_t N, int64_t O,
-                                                                int64_t M, int64_t Mp, int64_t rows_per_split) {
+                                                                int64_t M, int64_t Mp, int64_t rows_per_split,
+                                                                int64_t tiles_packed) {
     constexpr int OT = 16 * CW;          // output features per block
-    constexpr int CAPS = 16 * CWS;       // groups per S set
-    constexpr int kWaves = 4;
-    constexpr int kStep = 32;            // tokens per MFMA K-step
-    __shared__ float lds[OT][CAPS + 1];
+    __shared__ float lds[kWavesPerBlock][OT][17];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -160,82 +144,105 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
     const int jj = lane & 15;
     const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
     const int split = blockIdx.y;
-    const int64_t gbase = static_cast<int64_t>(blockIdx.z) * CAPS * NS;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * GT;
     const int64_t kb = static_cast<int64_t>(split) * rows_per_split;
     int64_t ke = kb + rows_per_split;
     if (ke > N) ke = N;
-    const int n_steps = static_cast<int>(ceil_div(ke - kb, kStep));
-    const int n_full = static_cast<int>((ke - kb) / kStep);    // steps with all 32 tokens in range
-    const bool col_edge = o0 + OT > O;                         // block-uniform
-
-    const uint32_t g_row_bytes = static_cast<uint32_t>(O) * 2u;
-    const uint32_t s_row_bytes = static_cast<uint32_t>(M) * 2u;
-    const uint32_t gvoff = static_cast<uint32_t>(q * 8) * g_row_bytes + static_cast<uint32_t>(jj * CW * 2);
-    const uint32_t svoff = static_cast<uint32_t>(q * 8) * s_row_bytes + static_cast<uint32_t>(jj * CWS * 2);
+    const int rows = static_cast<int>(ke - kb);
+    const int n_steps = (rows + kStep - 1) / kStep;
     const bool col_ok = o0 + jj * CW < O;
-    bool g_ok[NS];
-#pragma unroll
-    for (int s = 0; s < NS; ++s) g_ok[s] = gbase + s * CAPS + jj * CWS < M;
 
+    const uint32_t row_bytes = static_cast<uint32_t>(O) * 2u;
+    // Byte offsets of this lane's eight rows inside a step, constant for the
+    // whole kernel.  Lanes whose columns lie past O get an offset no descriptor
+    // can cover, so they read zeros.
+    uint32_t voff[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+        voff[r] = col_ok ? static_cast<uint32_t>(q * 8 + r) * row_bytes + static_cast<uint32_t>(jj * CW * 2)
+                         : 0xFFFFFFFFu;
     const char* gblock = reinterpret_cast<const char*>(G) + (kb * O + o0) * 2;
-    const char* sblock = reinterpret_cast<const char*>(S) + (kb * M + gbase) * 2;
-    const uint64_t g_step_bytes = static_cast<uint64_t>(kStep) * g_row_bytes;
-    const uint64_t s_step_bytes = static_cast<uint64_t>(kStep) * s_row_bytes;
+    const uint32_t gblock_bytes = static_cast<uint32_t>(rows) * row_bytes - static_cast<uint32_t>(o0 * 2);
+    const uint32_t step_bytes = static_cast<uint32_t>(kStep) * row_bytes;
+    // packed S of this block: steps kb/32 .., tiles tile0 .. ; one descriptor
+    const uint32_t s_step_bytes = static_cast<uint32_t>(tiles_packed) * 1024u;
+    const char* sblock = reinterpret_cast<const char*>(Spk) + ((kb / kStep) * tiles_packed + tile0) * 1024;
+    const uint32_t sblock_bytes = static_cast<uint32_t>(n_steps) * s_step_bytes - static_cast<uint32_t>(tile0) * 1024u;
+    __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(sblock), 0,
+                                                                     static_cast<int>(sblock_bytes), 0x00020000);
+    const uint32_t s_voff = static_cast<uint32_t>(lane) * 16u;
 
-    f32x4 acc[NS * CWS][CW];
+    f32x4 acc[GT][CW];
 #pragma unroll
-    for (int a = 0; a < NS * CWS; ++a)
+    for (int a = 0; a < GT; ++a)
 #pragma unroll
         for (int c = 0; c < CW; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    WgradRaw<CW, CWS, NS> raw;
-    WgradFrags<CW, CWS, NS> fr;
-    auto load_step = [&](int t) {
-        const char* gp = gblock + t * g_step_bytes;
-        const char* sp = sblock + t * s_step_bytes;
-        if (col_edge || t >= n_full) {
-            const int rows_left = static_cast<int>(ke - kb) - t * kStep;
-            wgrad_load<CW, CWS, NS, true>(raw, gp, sp, gvoff, svoff, g_row_bytes, s_row_bytes, rows_left, q, col_ok, g_ok);
-        } else {
-            wgrad_load<CW, CWS, NS, false>(raw, gp, sp, gvoff, svoff, g_row_bytes, s_row_bytes, kStep, q, col_ok, g_ok);
+    WgradStage<CW, GT> st[NST];
+    auto load_g_step = [&](WgradStage<CW, GT>& sg, int t) {
+        // descriptor for this step: starts at the step's first token and ends
+        // with the block's token range (empty for steps past the range)
+        const uint32_t off = static_cast<uint32_t>(t) * step_bytes;
+        const uint32_t left = t < n_steps ? gblock_bytes - off : 0u;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(gblock + (t < n_steps ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) sg.g[r] = load_g<CW>(rsrc, voff[r]);
+    };
+    auto load_s_step = [&](WgradStage<CW, GT>& sg, int t) {
+        const uint32_t off = s_voff + static_cast<uint32_t>(t) * s_step_bytes;
+#pragma unroll
+        for (int a = 0; a < GT; ++a) {
+            const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(s_rsrc, off + a * 1024u, 0, 0);
+            sg.s[a] = make_uint4(x.x, x.y, x.z, x.w);
         }
     };
-    // The raw registers are free again as soon as the fragments are built, so
-    // the next step's loads are in flight while this step's MFMAs run.
-    int t = w;
-    if (t < n_steps) load_step(t);
-    while (t < n_steps) {
-        wgrad_transpose(raw, fr);
-        const int tn = t + kWaves;
-        if (tn < n_steps) load_step(tn);
-        wgrad_mma(fr, acc);
-        t = tn;
+
+    // Register ring: NST steps of this wave are in flight at any time.  G's raw
+    // registers are free once its fragments are built, S's once the MFMAs have
+    // been issued, so each is re-loaded at that point.  Steps past the end of
+    // the range load zeros, which keeps the loop free of branches.
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+        load_g_step(st[s], w + s * kWavesPerBlock);
+        load_s_step(st[s], w + s * kWavesPerBlock);
+    }
+    for (int base = w; base < n_steps; base += NST * kWavesPerBlock) {
+#pragma unroll
+        for (int s = 0; s < NST; ++s) {
+            const int tn = base + (s + NST) * kWavesPerBlock;
+            bf16x8 gf[CW];
+#pragma unroll
+            for (int c = 0; c < CW; ++c) gf[c] = column_fragment(st[s].g, c);
+            load_g_step(st[s], tn);
+#pragma unroll
+            for (int a = 0; a < GT; ++a) {
+                const bf16x8 sf = __builtin_bit_cast(bf16x8, st[s].s[a]);
+#pragma unroll
+                for (int c = 0; c < CW; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
+            }
+            // keep the scheduler from hoisting the S reload above the MFMAs
+            // that still read the old fragments (it would double their registers)
+            __builtin_amdgcn_sched_barrier(0);
+            load_s_step(st[s], tn);
+        }
     }
 
-    // Sum the four waves in a fixed order through LDS, one S set at a time, and
-    // write the block's partial tile with lanes running along g.
+    // Sum the four waves in a fixed order through LDS, one 16-group tile at a
+    // time, and write the block's partial tile with lanes running along g.
     float* out = partial + static_cast<int64_t>(split) * O * Mp;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        for (int wv = 0; wv < kWaves; ++wv) {
-            if (w == wv) {
+    for (int a = 0; a < GT; ++a) {
 #pragma unroll
-                for (int cs = 0; cs < CWS; ++cs)
+        for (int c = 0; c < CW; ++c)
 #pragma unroll
-                    for (int c = 0; c < CW; ++c)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float* cell = &lds[jj * CW + c][(q * 4 + r) * CWS + cs];
-                            const float val = acc[s * CWS + cs][c][r];
-                            *cell = (wv == 0) ? val : (*cell + val);
-                        }
-            }
-            __syncthreads();
-        }
-        for (int idx = threadIdx.x; idx < OT * CAPS; idx += blockDim.x) {
-            const int ol = idx / CAPS, gl = idx % CAPS;
-            const int64_t o = o0 + ol, g = gbase + s * CAPS + gl;
-            if (o < O && g < M) out[o * Mp + g] = lds[ol][gl];
+            for (int r = 0; r < 4; ++r) lds[w][jj * CW + c][q * 4 + r] = acc[a][c][r];
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < OT * 16; idx += blockDim.x) {
+            const int ol = idx >> 4, gl = idx & 15;
+            const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
+            if (o < O && g < M) out[o * Mp + g] = ((lds[0][ol][gl] + lds[1][ol][gl]) + lds[2][ol][gl]) + lds[3][ol][gl];
         }
         __syncthreads();
     }
@@ -320,14 +327,16 @@ __global__ __launch_bounds__(256) void wgrad_expand_kernel(const float* __restri
                         const uint2 old = *p;
                         r0 += bf16_lo(old.x); r1 += bf16_hi(old.x); r2 += bf16_lo(old.y); r3 += bf16_hi(old.y);
                     }
-                    *p = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+                    const u32x2 packed_out = {pack_bf16x2(r0, r1), pack_bf16x2(r2, r3)};
+                    __builtin_nontemporal_store(packed_out, reinterpret_cast<u32x2*>(p));
                 } else {
                     float4* p = reinterpret_cast<float4*>(static_cast<float*>(dW) + e);
                     if (accumulate) {
                         const float4 old = *p;
                         r0 += old.x; r1 += old.y; r2 += old.z; r3 += old.w;
                     }
-                    *p = make_float4(r0, r1, r2, r3);
+                    const f32x4 out4 = {r0, r1, r2, r3};
+                    __builtin_nontemporal_store(out4, reinterpret_cast<f32x4*>(p));
                 }
             }
         } else {
@@ -357,60 +366,59 @@ __global__ __launch_bounds__(256) void wgrad_expand_kernel(const float* __restri
 namespace {
 
 struct MfmaChoice {
-    int cw, cws, ns;   // cw == 0: no MFMA configuration fits
+    int cw, gt, chunks;   // cw == 0: the MFMA path cannot take this call
 };
 
-int max_sets(int cws) { return cws == 8 ? 2 : 4; }
-
-MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, int s_align) {
-    MfmaChoice best{0, 0, 0};
-    // per-lane byte offsets inside a 32-token step are 32-bit
-    if (O > (INT64_C(1) << 24) || M > (INT64_C(1) << 24)) return best;
-    int64_t best_chunks = 0, best_gt = 0;
-    for (int cws = 8; cws >= 1; cws >>= 1) {
-        if (M % cws != 0 || s_align < 2 * cws) continue;
-        const int64_t cap_set = 16 * cws;
-        int64_t ns = ceil_div(M, cap_set);
-        if (ns > max_sets(cws)) ns = max_sets(cws);
-        const int64_t chunks = ceil_div(M, cap_set * ns);
-        const int64_t gt = ns * cws;
-        if (best.cws == 0 || chunks < best_chunks || (chunks == best_chunks && gt < best_gt)) {
-            best.cws = cws; best.ns = static_cast<int>(ns);
-            best_chunks = chunks; best_gt = gt;
-        }
+// 16-group tiles per block: the smallest supported count that covers M, else
+// chunks of 16 tiles.  Depends on M only, so the workspace query can use it.
+void tiles_for(int64_t M, int* gt, int64_t* chunks) {
+    static const int kSupported[] = {1, 2, 3, 4, 6, 8, 12, 16};
+    const int64_t need = ceil_div(M, 16);
+    if (need <= 16) {
+        for (int g : kSupported)
+            if (g >= need) { *gt = g; *chunks = 1; return; }
     }
-    if (best.cws == 0) return best;
-    const int64_t gt = static_cast<int64_t>(best.ns) * best.cws;
-    int cw = gt <= 4 ? 8 : 4;
-    while (cw >= 4 && (O % cw != 0 || g_align < 2 * cw)) cw >>= 1;
-    if (cw < 4) return MfmaChoice{0, 0, 0};
-    best.cw = cw;
-    return best;
+    *gt = 16;
+    *chunks = ceil_div(need, 16);
 }
 
-template <int CW, int CWS, int NS>
-hipError_t launch_mfma(const void* G, const void* S, float* partial, int64_t N, int64_t O, int64_t M,
-                       const WgradPlan& plan, hipStream_t st) {
+MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan) {
+    MfmaChoice ch{0, 0, 0};
+    int gt; int64_t chunks;
+    tiles_for(M, &gt, &chunks);
+    // byte offsets inside a block's token range are 32-bit
+    if (static_cast<double>(plan.rows_per_split) * static_cast<double>(O) * 2.0 >= 2147483648.0) return ch;
+    if (static_cast<double>(plan.rows_per_split / kStep + 1) * static_cast<double>(plan.tiles_packed) * 1024.0 >=
+        2147483648.0)
+        return ch;
+    if (chunks > 65535) return ch;
+    int cw = gt <= 4 ? 8 : 4;
+    while (cw >= 4 && (O % cw != 0 || g_align < 2 * cw)) cw >>= 1;
+    if (cw < 4) return ch;
+    ch.cw = cw; ch.gt = gt; ch.chunks = static_cast<int>(chunks);
+    return ch;
+}
+
+template <int CW, int GT, int NST>
+hipError_t launch_mfma(const void* G, const uint4* packed, float* partial, int64_t N, int64_t O, int64_t M,
+                       const WgradPlan& plan, int chunks, hipStream_t st) {
     dim3 grid(static_cast<unsigned>(ceil_div(O, 16 * CW)), static_cast<unsigned>(plan.splits),
-              static_cast<unsigned>(ceil_div(M, 16 * CWS * NS)));
-    hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, CWS, NS>), grid, dim3(256), 0, st,
-                       static_cast<const uint16_t*>(G), static_cast<const uint16_t*>(S), partial, N, O, M, plan.Mp,
-                       plan.rows_per_split);
+              static_cast<unsigned>(chunks));
+    hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST>), grid, dim3(256), 0, st,
+                       static_cast<const uint16_t*>(G), packed, partial, N, O, M, plan.Mp, plan.rows_per_split,
+                       plan.tiles_packed);
     return hipGetLastError();
 }
 
-#define VELORA_MFMA_CASE(CW, CWS, NS) \
-    if (ch.cw == CW && ch.cws == CWS && ch.ns == NS) return launch_mfma<CW, CWS, NS>(G, S, partial, N, O, M, plan, st);
+#define VELORA_MFMA_CASE(CW, GT, NST) \
+    if (ch.cw == CW && ch.gt == GT) return launch_mfma<CW, GT, NST>(G, packed, partial, N, O, M, plan, ch.chunks, st);
 
-hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* S, float* partial, int64_t N, int64_t O,
-                         int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
+hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const uint4* packed, float* partial, int64_t N,
+                         int64_t O, int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
     *handled = true;
-    VELORA_MFMA_CASE(8, 1, 1) VELORA_MFMA_CASE(8, 1, 2) VELORA_MFMA_CASE(8, 1, 3) VELORA_MFMA_CASE(8, 1, 4)
-    VELORA_MFMA_CASE(8, 2, 1) VELORA_MFMA_CASE(8, 2, 2) VELORA_MFMA_CASE(8, 4, 1)
-    VELORA_MFMA_CASE(4, 1, 1) VELORA_MFMA_CASE(4, 1, 2) VELORA_MFMA_CASE(4, 1, 3) VELORA_MFMA_CASE(4, 1, 4)
-    VELORA_MFMA_CASE(4, 2, 1) VELORA_MFMA_CASE(4, 2, 2) VELORA_MFMA_CASE(4, 2, 3) VELORA_MFMA_CASE(4, 2, 4)
-    VELORA_MFMA_CASE(4, 4, 1) VELORA_MFMA_CASE(4, 4, 2) VELORA_MFMA_CASE(4, 4, 3) VELORA_MFMA_CASE(4, 4, 4)
-    VELORA_MFMA_CASE(4, 8, 1) VELORA_MFMA_CASE(4, 8, 2)
+    VELORA_MFMA_CASE(8, 1, 3) VELORA_MFMA_CASE(8, 2, 3) VELORA_MFMA_CASE(8, 3, 4) VELORA_MFMA_CASE(8, 4, 4)
+    VELORA_MFMA_CASE(4, 1, 4) VELORA_MFMA_CASE(4, 2, 4) VELORA_MFMA_CASE(4, 3, 4) VELORA_MFMA_CASE(4, 4, 4)
+    VELORA_MFMA_CASE(4, 6, 3) VELORA_MFMA_CASE(4, 8, 4) VELORA_MFMA_CASE(4, 12, 3) VELORA_MFMA_CASE(4, 16, 2)
     *handled = false;
     return hipSuccess;
 }
@@ -453,9 +461,15 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     WgradPlan p;
     p.Mp = ceil_div(M, 4) * 4;
     const int64_t in_b = is_bf16 ? 2 : 4;
-    // Enough blocks to occupy every CU twice ...
-    const int64_t o_tiles = ceil_div(O, 128);
-    int64_t splits = ceil_div(static_cast<int64_t>(cfg.num_cus) * 2, o_tiles);
+    int gt = 1;
+    int64_t chunks = 1;
+    if (is_bf16) tiles_for(M, &gt, &chunks);
+    // One resident round of blocks: the partial kernel keeps two blocks per CU
+    // for a single group tile and one otherwise (register budget), and a second
+    // round of blocks would pay the pipeline start-up twice.
+    const int64_t blocks_per_cu = gt <= 1 ? 2 : 1;
+    const int64_t o_tiles = ceil_div(O, gt <= 4 ? 128 : 64) * chunks;
+    int64_t splits = (static_cast<int64_t>(cfg.num_cus) * blocks_per_cu) / o_tiles;
     // ... but keep the partial write + re-read under ~10 % of the bytes the
     // two kernels must move anyway, and give each block at least 256 tokens.
     const double must_move = static_cast<double>(N) * O * in_b + static_cast<double>(O) * D * 4.0;
@@ -470,7 +484,15 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     int64_t rows = ceil_div(ceil_div(N, splits), 128) * 128;
     p.rows_per_split = rows;
     p.splits = static_cast<int>(ceil_div(N, rows));
-    p.ws_bytes = static_cast<size_t>(p.splits) * static_cast<size_t>(O) * static_cast<size_t>(p.Mp) * sizeof(float);
+    p.partial_bytes = static_cast<size_t>(p.splits) * static_cast<size_t>(O) * static_cast<size_t>(p.Mp) * sizeof(float);
+    p.partial_bytes = (p.partial_bytes + 255) / 256 * 256;
+    p.tiles_packed = 0;
+    p.packed_bytes = 0;
+    if (is_bf16) {
+        p.tiles_packed = gt * chunks;
+        p.packed_bytes = static_cast<size_t>(ceil_div(N, kStep)) * static_cast<size_t>(p.tiles_packed) * 1024;
+    }
+    p.ws_bytes = p.partial_bytes + p.packed_bytes;
     return p;
 }
 
@@ -481,10 +503,20 @@ hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N,
     float* partial = static_cast<float*>(ws);
     hipError_t e = hipSuccess;
     bool done = false;
+    const int phases = env_int("VELORA_WGRAD_PHASES", 7);   // tuning aid: 1 pack, 2 partial, 4 expand
+    (void)s_align;
     if (is_bf16 && env_int("VELORA_WGRAD_FORCE_SIMPLE", 0) == 0) {
-        const MfmaChoice ch = choose_mfma(O, M, g_align, s_align);
+        const MfmaChoice ch = choose_mfma(O, M, g_align, plan);
         if (ch.cw != 0) {
-            e = dispatch_mfma(ch, G, S, partial, N, O, M, plan, st, &done);
+            uint4* packed = reinterpret_cast<uint4*>(static_cast<char*>(ws) + plan.partial_bytes);
+            const int64_t total = ceil_div(N, kStep) * plan.tiles_packed * 64;
+            if (phases & 1)
+                hipLaunchKernelGGL(wgrad_pack_s_kernel, dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0,
+                                   st, static_cast<const uint16_t*>(S), packed, N, M, plan.tiles_packed, total);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            if (phases & 2) e = dispatch_mfma(ch, G, packed, partial, N, O, M, plan, st, &done);
+            else done = true;
             if (e != hipSuccess) return e;
         }
     }
@@ -493,6 +525,7 @@ hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N,
                     : launch_simple<F32Elem>(G, S, partial, N, O, M, plan, st);
         if (e != hipSuccess) return e;
     }
+    if (!(phases & 4)) return hipSuccess;
     const int64_t d = D / M;
     const bool vec = (d % 4 == 0) && v_align >= 16 && dw_align >= (dw_bf16 ? 8 : 16);
     if (dw_bf16) {
