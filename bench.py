@@ -46,6 +46,9 @@ def _parse():
     ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--shape-steps", type=int, default=20)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 256 MiB device-to-device copies (a kernel of known traffic, "
+                         "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -219,6 +222,14 @@ def main():
     dev = torch.device("cuda:0")
     dw_dtype = torch.float32 if args.dw_dtype == "f32" else torch.bfloat16
     dw_b = 4 if args.dw_dtype == "f32" else 2
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 26, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------- headline workload: host-generated inputs (same as the parity tests)
     sh = wl.shape_by_name(args.workload)

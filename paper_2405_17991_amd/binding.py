@@ -78,14 +78,29 @@ def velora_version() -> int:
     return int(raw.velora_version())
 
 
+_ws_cache = {}
+
+
 def velora_workspace_bytes(op: int, N: int, D: int, O: int, M: int, dtype: int) -> int:
-    return int(raw.velora_workspace_bytes(op, N, D, O, M, dtype))
+    key = (op, N, D, O, M, dtype)
+    need = _ws_cache.get(key)
+    if need is None:
+        need = int(raw.velora_workspace_bytes(op, N, D, O, M, dtype))
+        if len(_ws_cache) < 4096:
+            _ws_cache[key] = need
+    return need
 
 
 # ---- torch plumbing ---------------------------------------------------------
+_torch_mod = None
+
+
 def _torch():
-    import torch
-    return torch
+    global _torch_mod
+    if _torch_mod is None:
+        import torch
+        _torch_mod = torch
+    return _torch_mod
 
 
 def _dt(t) -> int:

@@ -123,15 +123,17 @@ __device__ __forceinline__ bf16x8 column_fragment(const RawRow<NDW> (&rows)[8], 
     return __builtin_bit_cast(bf16x8, q);
 }
 
-template <int CW, int GT>
+// One 32-token step in flight.  S is either a ready fragment per tile (packed
+// path) or eight 16-bit values per tile still to be paired up (direct path).
+template <int CW, int GT, bool DIRECT>
 struct WgradStage {
     RawRow<CW / 2> g[8];
-    uint4 s[GT];
+    uint32_t s[GT][DIRECT ? 8 : 4];
 };
 
-template <int CW, int GT, int NST>
+template <int CW, int GT, int NST, bool DIRECT>
 __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t* __restrict__ G,
-                                                                const uint4* __restrict__ Spk,
+                                                                const void* __restrict__ Sany,
                                                                 float* __restrict__ partial, int64_t N, int64_t O,
                                                                 int64_t M, int64_t Mp, int64_t rows_per_split,
                                                                 int64_t tiles_packed) {
@@ -164,13 +166,29 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
     const char* gblock = reinterpret_cast<const char*>(G) + (kb * O + o0) * 2;
     const uint32_t gblock_bytes = static_cast<uint32_t>(rows) * row_bytes - static_cast<uint32_t>(o0 * 2);
     const uint32_t step_bytes = static_cast<uint32_t>(kStep) * row_bytes;
-    // packed S of this block: steps kb/32 .., tiles tile0 .. ; one descriptor
-    const uint32_t s_step_bytes = static_cast<uint32_t>(tiles_packed) * 1024u;
-    const char* sblock = reinterpret_cast<const char*>(Spk) + ((kb / kStep) * tiles_packed + tile0) * 1024;
-    const uint32_t sblock_bytes = static_cast<uint32_t>(n_steps) * s_step_bytes - static_cast<uint32_t>(tile0) * 1024u;
-    __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(sblock), 0,
-                                                                     static_cast<int>(sblock_bytes), 0x00020000);
-    const uint32_t s_voff = static_cast<uint32_t>(lane) * 16u;
+    // S of this block.  Packed path: steps kb/32 .., tiles tile0 .. of the
+    // fragment array, one descriptor for the whole range.  Direct path (few
+    // group tiles): the rows kb .. ke of S[N, M] itself; lane (jj, q) gathers
+    // S[8q + e][16*tile + jj], e < 8, as eight 2-byte loads per tile.
+    const uint32_t s_step_bytes = DIRECT ? static_cast<uint32_t>(kStep) * static_cast<uint32_t>(M) * 2u
+                                         : static_cast<uint32_t>(tiles_packed) * 1024u;
+    const char* sblock = DIRECT ? reinterpret_cast<const char*>(Sany) + kb * M * 2
+                                : reinterpret_cast<const char*>(Sany) + ((kb / kStep) * tiles_packed + tile0) * 1024;
+    const uint32_t sblock_bytes = DIRECT ? static_cast<uint32_t>(rows) * static_cast<uint32_t>(M) * 2u
+                                         : static_cast<uint32_t>(n_steps) * s_step_bytes - static_cast<uint32_t>(tile0) * 1024u;
+    uint32_t s_voff[DIRECT ? GT : 1][DIRECT ? 8 : 1];
+    if constexpr (DIRECT) {
+#pragma unroll
+        for (int a = 0; a < GT; ++a) {
+            const int64_t g = (tile0 + a) * 16 + jj;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                s_voff[a][e] = g < M ? (static_cast<uint32_t>(q * 8 + e) * static_cast<uint32_t>(M) + static_cast<uint32_t>(g)) * 2u
+                                     : 0xFFFFFFFFu;
+        }
+    } else {
+        s_voff[0][0] = static_cast<uint32_t>(lane) * 16u;
+    }
 
     f32x4 acc[GT][CW];
 #pragma unroll
@@ -178,8 +196,8 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
 #pragma unroll
         for (int c = 0; c < CW; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    WgradStage<CW, GT> st[NST];
-    auto load_g_step = [&](WgradStage<CW, GT>& sg, int t) {
+    WgradStage<CW, GT, DIRECT> st[NST];
+    auto load_g_step = [&](WgradStage<CW, GT, DIRECT>& sg, int t) {
         // descriptor for this step: starts at the step's first token and ends
         // with the block's token range (empty for steps past the range)
         const uint32_t off = static_cast<uint32_t>(t) * step_bytes;
@@ -189,13 +207,36 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
 #pragma unroll
         for (int r = 0; r < 8; ++r) sg.g[r] = load_g<CW>(rsrc, voff[r]);
     };
-    auto load_s_step = [&](WgradStage<CW, GT>& sg, int t) {
-        const uint32_t off = s_voff + static_cast<uint32_t>(t) * s_step_bytes;
+    auto load_s_step = [&](WgradStage<CW, GT, DIRECT>& sg, int t) {
+        const uint32_t off = static_cast<uint32_t>(t) * s_step_bytes;
+        const uint32_t left = (t < n_steps && off < sblock_bytes) ? sblock_bytes - off : 0u;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(sblock + (left ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
+        if constexpr (DIRECT) {
 #pragma unroll
-        for (int a = 0; a < GT; ++a) {
-            const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(s_rsrc, off + a * 1024u, 0, 0);
-            sg.s[a] = make_uint4(x.x, x.y, x.z, x.w);
+            for (int a = 0; a < GT; ++a)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    sg.s[a][e] = static_cast<uint32_t>(__builtin_amdgcn_raw_buffer_load_b16(rsrc, s_voff[a][e], 0, 0));
+        } else {
+#pragma unroll
+            for (int a = 0; a < GT; ++a) {
+                const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, s_voff[0][0] + a * 1024u, 0, 0);
+                sg.s[a][0] = x.x; sg.s[a][1] = x.y; sg.s[a][2] = x.z; sg.s[a][3] = x.w;
+            }
         }
+    };
+    auto s_fragment = [&](const WgradStage<CW, GT, DIRECT>& sg, int a) -> bf16x8 {
+        uint4 f;
+        if constexpr (DIRECT) {
+            f = make_uint4(__builtin_amdgcn_perm(sg.s[a][1], sg.s[a][0], 0x05040100u),
+                           __builtin_amdgcn_perm(sg.s[a][3], sg.s[a][2], 0x05040100u),
+                           __builtin_amdgcn_perm(sg.s[a][5], sg.s[a][4], 0x05040100u),
+                           __builtin_amdgcn_perm(sg.s[a][7], sg.s[a][6], 0x05040100u));
+        } else {
+            f = make_uint4(sg.s[a][0], sg.s[a][1], sg.s[a][2], sg.s[a][3]);
+        }
+        return __builtin_bit_cast(bf16x8, f);
     };
 
     // Register ring: NST steps of this wave are in flight at any time.  G's raw
@@ -217,7 +258,7 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
             load_g_step(st[s], tn);
 #pragma unroll
             for (int a = 0; a < GT; ++a) {
-                const bf16x8 sf = __builtin_bit_cast(bf16x8, st[s].s[a]);
+                const bf16x8 sf = s_fragment(st[s], a);
 #pragma unroll
                 for (int c = 0; c < CW; ++c)
                     acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
@@ -269,13 +310,24 @@ __global__ __launch_bounds__(256) void wgrad_partial_simple_kernel(const typenam
     if (ke > N) ke = N;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     if (o < O) {
-        for (int64_t n = kb; n < ke; ++n) {
-            const float gv = E::load(G, n * O + o);
+        // eight tokens per trip so that the loads of a trip are independent
+        for (int64_t n0 = kb; n0 < ke; n0 += 8) {
+            float gv[8], sv[8][4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int64_t g = g0 + 4 * i;
-                if (g < M) acc[i] = fmaf(gv, E::load(S, n * M + g), acc[i]);
+            for (int u = 0; u < 8; ++u) {
+                const int64_t n = n0 + u;
+                const bool ok = n < ke;
+                gv[u] = ok ? E::load(G, n * O + o) : 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t g = g0 + 4 * i;
+                    sv[u][i] = (ok && g < M) ? E::load(S, n * M + g) : 0.f;
+                }
             }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] = fmaf(gv[u], sv[u][i], acc[i]);
         }
         float* out = partial + (static_cast<int64_t>(split) * O + o) * Mp;
 #pragma unroll
@@ -365,6 +417,12 @@ __global__ __launch_bounds__(256) void wgrad_expand_kernel(const float* __restri
 // ---------------------------------------------------------------------------
 namespace {
 
+int env_int(const char* name, int fallback) {
+    const char* s = std::getenv(name);
+    if (!s || !*s) return fallback;
+    return std::atoi(s);
+}
+
 struct MfmaChoice {
     int cw, gt, chunks;   // cw == 0: the MFMA path cannot take this call
 };
@@ -392,6 +450,7 @@ MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan)
         2147483648.0)
         return ch;
     if (chunks > 65535) return ch;
+    if (static_cast<double>(plan.rows_per_split) * static_cast<double>(M) * 2.0 >= 2147483648.0) return ch;
     int cw = gt <= 4 ? 8 : 4;
     while (cw >= 4 && (O % cw != 0 || g_align < 2 * cw)) cw >>= 1;
     if (cw < 4) return ch;
@@ -399,26 +458,34 @@ MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan)
     return ch;
 }
 
-template <int CW, int GT, int NST>
-hipError_t launch_mfma(const void* G, const uint4* packed, float* partial, int64_t N, int64_t O, int64_t M,
+// S operand: the [N, M] array itself (direct gather, at most two group tiles)
+// or the packed fragment array.
+bool direct_s(int gt) { return gt <= 2; }
+
+template <int CW, int GT, int NST, bool DIRECT>
+hipError_t launch_mfma(const void* G, const void* s_operand, float* partial, int64_t N, int64_t O, int64_t M,
                        const WgradPlan& plan, int chunks, hipStream_t st) {
     dim3 grid(static_cast<unsigned>(ceil_div(O, 16 * CW)), static_cast<unsigned>(plan.splits),
               static_cast<unsigned>(chunks));
-    hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST>), grid, dim3(256), 0, st,
-                       static_cast<const uint16_t*>(G), packed, partial, N, O, M, plan.Mp, plan.rows_per_split,
+    hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST, DIRECT>), grid, dim3(256), 0, st,
+                       static_cast<const uint16_t*>(G), s_operand, partial, N, O, M, plan.Mp, plan.rows_per_split,
                        plan.tiles_packed);
     return hipGetLastError();
 }
 
-#define VELORA_MFMA_CASE(CW, GT, NST) \
-    if (ch.cw == CW && ch.gt == GT) return launch_mfma<CW, GT, NST>(G, packed, partial, N, O, M, plan, ch.chunks, st);
+#define VELORA_MFMA_CASE(CW, GT, NST, DIRECT) \
+    if (ch.cw == CW && ch.gt == GT)           \
+        return launch_mfma<CW, GT, NST, DIRECT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
 
-hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const uint4* packed, float* partial, int64_t N,
+hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_operand, float* partial, int64_t N,
                          int64_t O, int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
     *handled = true;
-    VELORA_MFMA_CASE(8, 1, 3) VELORA_MFMA_CASE(8, 2, 3) VELORA_MFMA_CASE(8, 3, 4) VELORA_MFMA_CASE(8, 4, 4)
-    VELORA_MFMA_CASE(4, 1, 4) VELORA_MFMA_CASE(4, 2, 4) VELORA_MFMA_CASE(4, 3, 4) VELORA_MFMA_CASE(4, 4, 4)
-    VELORA_MFMA_CASE(4, 6, 3) VELORA_MFMA_CASE(4, 8, 4) VELORA_MFMA_CASE(4, 12, 3) VELORA_MFMA_CASE(4, 16, 2)
+    VELORA_MFMA_CASE(8, 1, 3, true) VELORA_MFMA_CASE(8, 2, 3, true)
+    VELORA_MFMA_CASE(8, 3, 4, false) VELORA_MFMA_CASE(8, 4, 4, false)
+    VELORA_MFMA_CASE(4, 1, 4, true) VELORA_MFMA_CASE(4, 2, 4, true)
+    VELORA_MFMA_CASE(4, 3, 4, false) VELORA_MFMA_CASE(4, 4, 4, false)
+    VELORA_MFMA_CASE(4, 6, 3, false) VELORA_MFMA_CASE(4, 8, 4, false)
+    VELORA_MFMA_CASE(4, 12, 3, false) VELORA_MFMA_CASE(4, 16, 2, false)
     *handled = false;
     return hipSuccess;
 }
@@ -449,11 +516,6 @@ hipError_t launch_expand(const float* partial, const float* v, void* dW, int64_t
     return hipGetLastError();
 }
 
-int env_int(const char* name, int fallback) {
-    const char* s = std::getenv(name);
-    if (!s || !*s) return fallback;
-    return std::atoi(s);
-}
 
 }  // namespace
 
@@ -476,19 +538,21 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     const double per_split = static_cast<double>(O) * p.Mp * 8.0;
     const int64_t traffic_cap = static_cast<int64_t>(0.10 * must_move / per_split);
     if (splits > traffic_cap) splits = traffic_cap;
-    if (splits > ceil_div(N, 256)) splits = ceil_div(N, 256);
+    const int64_t min_rows = is_bf16 ? 256 : 32;   // the plain-FMA kernel is latency-bound per token
+    if (splits > ceil_div(N, min_rows)) splits = ceil_div(N, min_rows);
     const int forced = env_int("VELORA_WGRAD_SPLITS", 0);   // tuning aid; 0 = automatic
     if (forced > 0) splits = forced;
     if (splits < 1) splits = 1;
     if (splits > 65535) splits = 65535;
-    int64_t rows = ceil_div(ceil_div(N, splits), 128) * 128;
+    const int64_t row_quantum = is_bf16 ? 128 : 32;
+    int64_t rows = ceil_div(ceil_div(N, splits), row_quantum) * row_quantum;
     p.rows_per_split = rows;
     p.splits = static_cast<int>(ceil_div(N, rows));
     p.partial_bytes = static_cast<size_t>(p.splits) * static_cast<size_t>(O) * static_cast<size_t>(p.Mp) * sizeof(float);
     p.partial_bytes = (p.partial_bytes + 255) / 256 * 256;
     p.tiles_packed = 0;
     p.packed_bytes = 0;
-    if (is_bf16) {
+    if (is_bf16 && !direct_s(gt)) {
         p.tiles_packed = gt * chunks;
         p.packed_bytes = static_cast<size_t>(ceil_div(N, kStep)) * static_cast<size_t>(p.tiles_packed) * 1024;
     }
@@ -508,14 +572,18 @@ hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N,
     if (is_bf16 && env_int("VELORA_WGRAD_FORCE_SIMPLE", 0) == 0) {
         const MfmaChoice ch = choose_mfma(O, M, g_align, plan);
         if (ch.cw != 0) {
-            uint4* packed = reinterpret_cast<uint4*>(static_cast<char*>(ws) + plan.partial_bytes);
-            const int64_t total = ceil_div(N, kStep) * plan.tiles_packed * 64;
-            if (phases & 1)
-                hipLaunchKernelGGL(wgrad_pack_s_kernel, dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0,
-                                   st, static_cast<const uint16_t*>(S), packed, N, M, plan.tiles_packed, total);
-            e = hipGetLastError();
-            if (e != hipSuccess) return e;
-            if (phases & 2) e = dispatch_mfma(ch, G, packed, partial, N, O, M, plan, st, &done);
+            const void* s_operand = S;
+            if (!direct_s(ch.gt)) {
+                uint4* packed = reinterpret_cast<uint4*>(static_cast<char*>(ws) + plan.partial_bytes);
+                const int64_t total = ceil_div(N, kStep) * plan.tiles_packed * 64;
+                if (phases & 1)
+                    hipLaunchKernelGGL(wgrad_pack_s_kernel, dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256),
+                                       0, st, static_cast<const uint16_t*>(S), packed, N, M, plan.tiles_packed, total);
+                e = hipGetLastError();
+                if (e != hipSuccess) return e;
+                s_operand = packed;
+            }
+            if (phases & 2) e = dispatch_mfma(ch, G, s_operand, partial, N, O, M, plan, st, &done);
             else done = true;
             if (e != hipSuccess) return e;
         }
