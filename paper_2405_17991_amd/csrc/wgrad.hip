@@ -340,71 +340,102 @@ __global__ __launch_bounds__(256) void wgrad_partial_simple_kernel(const typenam
 
 // ---------------------------------------------------------------------------
 // Kernel 2: T[o, :] = sum over splits (fixed order), dW[o, g*d + j] (+)= T[o,g]*v[j].
-// One block per output row; T is staged in LDS in chunks of kTChunk groups.
+// A block owns one output row (or a few short ones).  The row's partials are
+// loaded by all of its threads at once (one memory latency, not one per split),
+// summed in split order through LDS, then the row is streamed out.
 // VEC: four consecutive columns per lane (needs d % 4 == 0 and an aligned dW).
 // ---------------------------------------------------------------------------
+// The block shape is chosen by the host so that a thread issues about four
+// 16-byte stores: long rows get up to 1024 threads (few rows being written at
+// any moment helps HBM write efficiency), short rows are grouped.
 constexpr int kTChunk = 2048;
+constexpr int kExpandThreads = 1024;
 
 template <bool OUT_BF16, bool VEC>
-__global__ __launch_bounds__(256) void wgrad_expand_kernel(const float* __restrict__ partial,
-                                                          const float* __restrict__ v, void* __restrict__ dW,
-                                                          int splits, int64_t O, int64_t D, int64_t M, int64_t Mp,
-                                                          int d, int d_shift, int accumulate) {
-    __shared__ float T[kTChunk];
-    const int64_t o = blockIdx.x;
-    const float* prow = partial + o * Mp;
+__global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const float* __restrict__ partial,
+                                                                     const float* __restrict__ v,
+                                                                     void* __restrict__ dW, int splits, int64_t O,
+                                                                     int64_t D, int64_t M, int64_t Mp, int d,
+                                                                     int d_shift, int accumulate, int rows_per_block) {
+    __shared__ float P[kTChunk];     // partials of the block's rows: [row][split][group]
+    __shared__ float T[kTChunk / 2];  // their sums: [row][group]
     const int64_t split_stride = O * Mp;
-    for (int64_t gc0 = 0; gc0 < M; gc0 += kTChunk) {
-        const int gcn = static_cast<int>((M - gc0) < kTChunk ? (M - gc0) : kTChunk);
-        for (int gl = threadIdx.x; gl < gcn; gl += blockDim.x) {
-            float s = 0.f;
-            for (int sp = 0; sp < splits; ++sp) s += prow[sp * split_stride + gc0 + gl];
-            T[gl] = s;
+    // thread -> (row slot r, position p inside the row's share of threads)
+    const int tpr = static_cast<int>(blockDim.x) / rows_per_block;   // threads per row
+    const int r = threadIdx.x / tpr;
+    const int p = threadIdx.x - r * tpr;
+    const int64_t o = static_cast<int64_t>(blockIdx.x) * rows_per_block + r;
+    const bool row_ok = r < rows_per_block && o < O;
+    // groups are staged in LDS in chunks of mchunk per row, sized so that all
+    // splits of a chunk fit; the loads of a chunk are spread over the row's
+    // threads (one latency, not one per split) and then summed in split order
+    int mchunk = kTChunk / (rows_per_block * splits);
+    if (mchunk > kTChunk / 2 / rows_per_block) mchunk = kTChunk / 2 / rows_per_block;
+    for (int64_t gc0 = 0; gc0 < M; gc0 += mchunk) {
+        const int gcn = static_cast<int>((M - gc0) < mchunk ? (M - gc0) : mchunk);
+        float* Pr = P + r * splits * mchunk;
+        if (row_ok) {
+            const float* prow = partial + o * Mp + gc0;
+            for (int idx = p; idx < gcn * splits; idx += tpr) {
+                const int sp = idx / gcn, gl = idx - sp * gcn;
+                Pr[sp * mchunk + gl] = prow[sp * split_stride + gl];
+            }
         }
         __syncthreads();
-        const int64_t c_begin = gc0 * d;
-        const int64_t c_count = static_cast<int64_t>(gcn) * d;
-        if constexpr (VEC) {
-            for (int64_t i = threadIdx.x; i < c_count / 4; i += blockDim.x) {
-                const int64_t cl = i * 4;
-                const int gl = d_shift >= 0 ? static_cast<int>(cl >> d_shift) : static_cast<int>(cl / d);
-                const int j = static_cast<int>(cl - static_cast<int64_t>(gl) * d);
-                const float tg = T[gl];
-                const float4 vv = *reinterpret_cast<const float4*>(v + j);
-                float r0 = tg * vv.x, r1 = tg * vv.y, r2 = tg * vv.z, r3 = tg * vv.w;
-                const int64_t e = o * D + c_begin + cl;
-                if constexpr (OUT_BF16) {
-                    uint2* p = reinterpret_cast<uint2*>(static_cast<uint16_t*>(dW) + e);
-                    if (accumulate) {
-                        const uint2 old = *p;
-                        r0 += bf16_lo(old.x); r1 += bf16_hi(old.x); r2 += bf16_lo(old.y); r3 += bf16_hi(old.y);
-                    }
-                    const u32x2 packed_out = {pack_bf16x2(r0, r1), pack_bf16x2(r2, r3)};
-                    __builtin_nontemporal_store(packed_out, reinterpret_cast<u32x2*>(p));
-                } else {
-                    float4* p = reinterpret_cast<float4*>(static_cast<float*>(dW) + e);
-                    if (accumulate) {
-                        const float4 old = *p;
-                        r0 += old.x; r1 += old.y; r2 += old.z; r3 += old.w;
-                    }
-                    const f32x4 out4 = {r0, r1, r2, r3};
-                    __builtin_nontemporal_store(out4, reinterpret_cast<f32x4*>(p));
-                }
+        if (row_ok) {
+            for (int gl = p; gl < gcn; gl += tpr) {
+                float s = 0.f;
+                for (int sp = 0; sp < splits; ++sp) s += Pr[sp * mchunk + gl];
+                T[r * mchunk + gl] = s;
             }
-        } else {
-            for (int64_t cl = threadIdx.x; cl < c_count; cl += blockDim.x) {
-                const int gl = static_cast<int>(cl / d);
-                const int j = static_cast<int>(cl - static_cast<int64_t>(gl) * d);
-                float r = T[gl] * v[j];
-                const int64_t e = o * D + c_begin + cl;
-                if constexpr (OUT_BF16) {
-                    uint16_t* p = static_cast<uint16_t*>(dW) + e;
-                    if (accumulate) r += bf16_to_f32(*p);
-                    *p = f32_to_bf16(r);
-                } else {
-                    float* p = static_cast<float*>(dW) + e;
-                    if (accumulate) r += *p;
-                    *p = r;
+        }
+        __syncthreads();
+        if (row_ok) {
+            const float* Tr = T + r * mchunk;
+            const int64_t c_begin = gc0 * d;
+            const int64_t c_count = static_cast<int64_t>(gcn) * d;
+            if constexpr (VEC) {
+                for (int64_t i = p; i < c_count / 4; i += tpr) {
+                    const int64_t cl = i * 4;
+                    const int gl = d_shift >= 0 ? static_cast<int>(cl >> d_shift) : static_cast<int>(cl / d);
+                    const int j = static_cast<int>(cl - static_cast<int64_t>(gl) * d);
+                    const float tg = Tr[gl];
+                    const float4 vv = *reinterpret_cast<const float4*>(v + j);
+                    float r0 = tg * vv.x, r1 = tg * vv.y, r2 = tg * vv.z, r3 = tg * vv.w;
+                    const int64_t e = o * D + c_begin + cl;
+                    if constexpr (OUT_BF16) {
+                        uint2* q = reinterpret_cast<uint2*>(static_cast<uint16_t*>(dW) + e);
+                        if (accumulate) {
+                            const uint2 old = *q;
+                            r0 += bf16_lo(old.x); r1 += bf16_hi(old.x); r2 += bf16_lo(old.y); r3 += bf16_hi(old.y);
+                        }
+                        const u32x2 packed_out = {pack_bf16x2(r0, r1), pack_bf16x2(r2, r3)};
+                        __builtin_nontemporal_store(packed_out, reinterpret_cast<u32x2*>(q));
+                    } else {
+                        float4* q = reinterpret_cast<float4*>(static_cast<float*>(dW) + e);
+                        if (accumulate) {
+                            const float4 old = *q;
+                            r0 += old.x; r1 += old.y; r2 += old.z; r3 += old.w;
+                        }
+                        const f32x4 out4 = {r0, r1, r2, r3};
+                        __builtin_nontemporal_store(out4, reinterpret_cast<f32x4*>(q));
+                    }
+                }
+            } else {
+                for (int64_t cl = p; cl < c_count; cl += tpr) {
+                    const int gl = static_cast<int>(cl / d);
+                    const int j = static_cast<int>(cl - static_cast<int64_t>(gl) * d);
+                    float x = Tr[gl] * v[j];
+                    const int64_t e = o * D + c_begin + cl;
+                    if constexpr (OUT_BF16) {
+                        uint16_t* q = static_cast<uint16_t*>(dW) + e;
+                        if (accumulate) x += bf16_to_f32(*q);
+                        *q = f32_to_bf16(x);
+                    } else {
+                        float* q = static_cast<float*>(dW) + e;
+                        if (accumulate) x += *q;
+                        *q = x;
+                    }
                 }
             }
         }
@@ -511,8 +542,26 @@ hipError_t launch_expand(const float* partial, const float* v, void* dW, int64_t
         d_shift = 0;
         while ((1 << d_shift) < d) ++d_shift;
     }
-    hipLaunchKernelGGL((wgrad_expand_kernel<OUT_BF16, VEC>), dim3(static_cast<unsigned>(O)), dim3(256), 0, st, partial,
-                       v, dW, plan.splits, O, D, M, plan.Mp, d, d_shift, accumulate ? 1 : 0);
+    // Block shape: about `spt` 16-byte stores (or 4x as many scalars) per thread,
+    // 256..1024 threads; short rows are grouped (power of two, <= 16 rows).
+    // (measured: 4 stores per thread is at or near the best block shape for
+    // every layer shape of the five configurations)
+    const int64_t per_row = ceil_div(D, 4);
+    const int spt = 4;
+    int64_t threads = ceil_div(ceil_div(per_row, spt), 64) * 64;
+    if (threads > kExpandThreads) threads = kExpandThreads;
+    int rows_per_block = 1;
+    if (threads < 256) {
+        while (rows_per_block < 16 && threads * rows_per_block * 2 <= 256 && rows_per_block * 2 * plan.splits <= kTChunk)
+            rows_per_block *= 2;
+        threads = threads * rows_per_block;
+        threads = ceil_div(threads, 64) * 64;
+        // a row's share of the block must be the same for every row
+        while (threads % rows_per_block) threads += 64;
+    }
+    hipLaunchKernelGGL((wgrad_expand_kernel<OUT_BF16, VEC>), dim3(static_cast<unsigned>(ceil_div(O, rows_per_block))),
+                       dim3(static_cast<unsigned>(threads)), 0, st, partial, v, dW, plan.splits, O, D, M, plan.Mp, d,
+                       d_shift, accumulate ? 1 : 0, rows_per_block);
     return hipGetLastError();
 }
 
@@ -543,7 +592,7 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     const int forced = env_int("VELORA_WGRAD_SPLITS", 0);   // tuning aid; 0 = automatic
     if (forced > 0) splits = forced;
     if (splits < 1) splits = 1;
-    if (splits > 65535) splits = 65535;
+    if (splits > 1024) splits = 1024;   // also bounds the expand kernel's LDS staging (kTChunk / splits >= 2)
     const int64_t row_quantum = is_bf16 ? 128 : 32;
     int64_t rows = ceil_div(ceil_div(N, splits), row_quantum) * row_quantum;
     p.rows_per_split = rows;
