@@ -95,14 +95,14 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // the descriptor's size returns zero without touching memory; the kernel uses
 // that for every edge (rows past the token range, columns past O, steps past
 // the end) instead of branching.
-template <int CW>
+template <int CW, int AUX>
 __device__ __forceinline__ RawRow<CW / 2> load_g(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff) {
     RawRow<CW / 2> r;
     if constexpr (CW == 8) {
-        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, kStreamAux);
+        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, AUX);
         r.w[0] = q.x; r.w[1] = q.y; r.w[2] = q.z; r.w[3] = q.w;
     } else {
-        const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, 0, kStreamAux);
+        const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, 0, AUX);
         r.w[0] = q.x; r.w[1] = q.y;
     }
     return r;
@@ -131,7 +131,14 @@ struct WgradStage {
     uint32_t s[GT][DIRECT ? 8 : 4];
 };
 
-template <int CW, int GT, int NST, bool DIRECT>
+// GSPLIT (many group tiles): instead of alternating token steps, the four waves
+// all walk every step of the block's range and split the group tiles between
+// them (GT tiles each, 4*GT per block).  Each wave then keeps only GT*CW
+// accumulator tiles and re-reads S once per 128 output features instead of once
+// per 64; the price is that all four waves load the same G tile, which the
+// CU's vector cache serves after the first (so these loads are not marked
+// non-temporal).
+template <int CW, int GT, int NST, bool DIRECT, bool GSPLIT>
 __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t* __restrict__ G,
                                                                 const void* __restrict__ Sany,
                                                                 float* __restrict__ partial, int64_t N, int64_t O,
@@ -146,7 +153,10 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
     const int jj = lane & 15;
     const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
     const int split = blockIdx.y;
-    const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * GT;
+    constexpr int kTilesPerBlock = GSPLIT ? GT * kWavesPerBlock : GT;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * kTilesPerBlock + (GSPLIT ? w * GT : 0);
+    const int step_first = GSPLIT ? 0 : w;                       // this wave's first step ...
+    constexpr int kStepStride = GSPLIT ? 1 : kWavesPerBlock;     // ... and the distance to its next
     const int64_t kb = static_cast<int64_t>(split) * rows_per_split;
     int64_t ke = kb + rows_per_split;
     if (ke > N) ke = N;
@@ -205,7 +215,7 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char*>(gblock + (t < n_steps ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) sg.g[r] = load_g<CW>(rsrc, voff[r]);
+        for (int r = 0; r < 8; ++r) sg.g[r] = load_g<CW, GSPLIT ? 0 : kStreamAux>(rsrc, voff[r]);
     };
     auto load_s_step = [&](WgradStage<CW, GT, DIRECT>& sg, int t) {
         const uint32_t off = static_cast<uint32_t>(t) * s_step_bytes;
@@ -245,13 +255,13 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
     // the range load zeros, which keeps the loop free of branches.
 #pragma unroll
     for (int s = 0; s < NST; ++s) {
-        load_g_step(st[s], w + s * kWavesPerBlock);
-        load_s_step(st[s], w + s * kWavesPerBlock);
+        load_g_step(st[s], step_first + s * kStepStride);
+        load_s_step(st[s], step_first + s * kStepStride);
     }
-    for (int base = w; base < n_steps; base += NST * kWavesPerBlock) {
+    for (int base = step_first; base < n_steps; base += NST * kStepStride) {
 #pragma unroll
         for (int s = 0; s < NST; ++s) {
-            const int tn = base + (s + NST) * kWavesPerBlock;
+            const int tn = base + (s + NST) * kStepStride;
             bf16x8 gf[CW];
 #pragma unroll
             for (int c = 0; c < CW; ++c) gf[c] = column_fragment(st[s].g, c);
@@ -270,8 +280,9 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
         }
     }
 
-    // Sum the four waves in a fixed order through LDS, one 16-group tile at a
-    // time, and write the block's partial tile with lanes running along g.
+    // Epilogue through LDS, one 16-group tile at a time, so that the partial
+    // tile is written with lanes running along g.  Alternating-step waves are
+    // summed in a fixed order; group-splitting waves each own their tiles.
     float* out = partial + static_cast<int64_t>(split) * O * Mp;
 #pragma unroll
     for (int a = 0; a < GT; ++a) {
@@ -280,10 +291,19 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
 #pragma unroll
             for (int r = 0; r < 4; ++r) lds[w][jj * CW + c][q * 4 + r] = acc[a][c][r];
         __syncthreads();
-        for (int idx = threadIdx.x; idx < OT * 16; idx += blockDim.x) {
-            const int ol = idx >> 4, gl = idx & 15;
-            const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
-            if (o < O && g < M) out[o * Mp + g] = ((lds[0][ol][gl] + lds[1][ol][gl]) + lds[2][ol][gl]) + lds[3][ol][gl];
+        if constexpr (GSPLIT) {
+            for (int idx = lane; idx < OT * 16; idx += kWave) {
+                const int ol = idx >> 4, gl = idx & 15;
+                const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
+                if (o < O && g < M) out[o * Mp + g] = lds[w][ol][gl];
+            }
+        } else {
+            for (int idx = threadIdx.x; idx < OT * 16; idx += blockDim.x) {
+                const int ol = idx >> 4, gl = idx & 15;
+                const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
+                if (o < O && g < M)
+                    out[o * Mp + g] = ((lds[0][ol][gl] + lds[1][ol][gl]) + lds[2][ol][gl]) + lds[3][ol][gl];
+            }
         }
         __syncthreads();
     }
@@ -459,9 +479,11 @@ struct MfmaChoice {
 };
 
 // 16-group tiles per block: the smallest supported count that covers M, else
-// chunks of 16 tiles.  Depends on M only, so the workspace query can use it.
+// chunks of 16 tiles.  Up to 6 tiles the block's waves alternate token steps;
+// 8, 12 and 16 tiles are split between the waves (2, 3, 4 each).  Depends on M
+// only, so the workspace query can use it.
 void tiles_for(int64_t M, int* gt, int64_t* chunks) {
-    static const int kSupported[] = {1, 2, 3, 4, 6, 8, 12, 16};
+    static const int kSupported[] = {1, 2, 3, 4, 5, 6, 8, 12, 16};
     const int64_t need = ceil_div(M, 16);
     if (need <= 16) {
         for (int g : kSupported)
@@ -470,6 +492,10 @@ void tiles_for(int64_t M, int* gt, int64_t* chunks) {
     *gt = 16;
     *chunks = ceil_div(need, 16);
 }
+
+// S operand: the [N, M] array itself (direct gather, at most two group tiles)
+// or the packed fragment array.
+bool direct_s(int gt) { return gt <= 2; }
 
 MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan) {
     MfmaChoice ch{0, 0, 0};
@@ -482,41 +508,42 @@ MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan)
         return ch;
     if (chunks > 65535) return ch;
     if (static_cast<double>(plan.rows_per_split) * static_cast<double>(M) * 2.0 >= 2147483648.0) return ch;
-    int cw = gt <= 4 ? 8 : 4;
+    int cw = 8;
     while (cw >= 4 && (O % cw != 0 || g_align < 2 * cw)) cw >>= 1;
     if (cw < 4) return ch;
     ch.cw = cw; ch.gt = gt; ch.chunks = static_cast<int>(chunks);
     return ch;
 }
 
-// S operand: the [N, M] array itself (direct gather, at most two group tiles)
-// or the packed fragment array.
-bool direct_s(int gt) { return gt <= 2; }
-
-template <int CW, int GT, int NST, bool DIRECT>
+template <int CW, int GT, int NST, bool DIRECT, bool GSPLIT>
 hipError_t launch_mfma(const void* G, const void* s_operand, float* partial, int64_t N, int64_t O, int64_t M,
                        const WgradPlan& plan, int chunks, hipStream_t st) {
     dim3 grid(static_cast<unsigned>(ceil_div(O, 16 * CW)), static_cast<unsigned>(plan.splits),
               static_cast<unsigned>(chunks));
-    hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST, DIRECT>), grid, dim3(256), 0, st,
+    hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST, DIRECT, GSPLIT>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(G), s_operand, partial, N, O, M, plan.Mp, plan.rows_per_split,
                        plan.tiles_packed);
     return hipGetLastError();
 }
 
-#define VELORA_MFMA_CASE(CW, GT, NST, DIRECT) \
-    if (ch.cw == CW && ch.gt == GT)           \
-        return launch_mfma<CW, GT, NST, DIRECT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
+// (CW, tiles per block) -> kernel; GTW = tiles per wave
+#define VELORA_MFMA_CASE(CW, TILES, GTW, NST, DIRECT, GSPLIT) \
+    if (ch.cw == CW && ch.gt == TILES)                        \
+        return launch_mfma<CW, GTW, NST, DIRECT, GSPLIT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
 
 hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_operand, float* partial, int64_t N,
                          int64_t O, int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
     *handled = true;
-    VELORA_MFMA_CASE(8, 1, 3, true) VELORA_MFMA_CASE(8, 2, 3, true)
-    VELORA_MFMA_CASE(8, 3, 4, false) VELORA_MFMA_CASE(8, 4, 4, false)
-    VELORA_MFMA_CASE(4, 1, 4, true) VELORA_MFMA_CASE(4, 2, 4, true)
-    VELORA_MFMA_CASE(4, 3, 4, false) VELORA_MFMA_CASE(4, 4, 4, false)
-    VELORA_MFMA_CASE(4, 6, 3, false) VELORA_MFMA_CASE(4, 8, 4, false)
-    VELORA_MFMA_CASE(4, 12, 3, false) VELORA_MFMA_CASE(4, 16, 2, false)
+    VELORA_MFMA_CASE(8, 1, 1, 3, true, false) VELORA_MFMA_CASE(8, 2, 2, 3, true, false)
+    VELORA_MFMA_CASE(8, 3, 3, 4, false, false) VELORA_MFMA_CASE(8, 4, 4, 4, false, false)
+    VELORA_MFMA_CASE(8, 5, 5, 3, false, false) VELORA_MFMA_CASE(8, 6, 6, 3, false, false)
+    VELORA_MFMA_CASE(8, 8, 2, 3, false, true) VELORA_MFMA_CASE(8, 12, 3, 3, false, true)
+    VELORA_MFMA_CASE(8, 16, 4, 3, false, true)
+    VELORA_MFMA_CASE(4, 1, 1, 4, true, false) VELORA_MFMA_CASE(4, 2, 2, 4, true, false)
+    VELORA_MFMA_CASE(4, 3, 3, 4, false, false) VELORA_MFMA_CASE(4, 4, 4, 4, false, false)
+    VELORA_MFMA_CASE(4, 5, 5, 4, false, false) VELORA_MFMA_CASE(4, 6, 6, 3, false, false)
+    VELORA_MFMA_CASE(4, 8, 8, 4, false, false) VELORA_MFMA_CASE(4, 12, 12, 3, false, false)
+    VELORA_MFMA_CASE(4, 16, 16, 2, false, false)
     *handled = false;
     return hipSuccess;
 }
@@ -579,7 +606,7 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     // for a single group tile and one otherwise (register budget), and a second
     // round of blocks would pay the pipeline start-up twice.
     const int64_t blocks_per_cu = gt <= 1 ? 2 : 1;
-    const int64_t o_tiles = ceil_div(O, gt <= 4 ? 128 : 64) * chunks;
+    const int64_t o_tiles = ceil_div(O, 128) * chunks;
     int64_t splits = (static_cast<int64_t>(cfg.num_cus) * blocks_per_cu) / o_tiles;
     // ... but keep the partial write + re-read under ~10 % of the bytes the
     // two kernels must move anyway, and give each block at least 256 tokens.
