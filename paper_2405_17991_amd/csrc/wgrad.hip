@@ -131,14 +131,7 @@ struct WgradStage {
     uint32_t s[GT][DIRECT ? 8 : 4];
 };
 
-// GSPLIT (many group tiles): instead of alternating token steps, the four waves
-// all walk every step of the block's range and split the group tiles between
-// them (GT tiles each, 4*GT per block).  Each wave then keeps only GT*CW
-// accumulator tiles and re-reads S once per 128 output features instead of once
-// per 64; the price is that all four waves load the same G tile, which the
-// CU's vector cache serves after the first (so these loads are not marked
-// non-temporal).
-template <int CW, int GT, int NST, bool DIRECT, bool GSPLIT>
+template <int CW, int GT, int NST, bool DIRECT>
 __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t* __restrict__ G,
                                                                 const void* __restrict__ Sany,
                                                                 float* __restrict__ partial, int64_t N, int64_t O,
@@ -153,10 +146,9 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
     const int jj = lane & 15;
     const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
     const int split = blockIdx.y;
-    constexpr int kTilesPerBlock = GSPLIT ? GT * kWavesPerBlock : GT;
-    const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * kTilesPerBlock + (GSPLIT ? w * GT : 0);
-    const int step_first = GSPLIT ? 0 : w;                       // this wave's first step ...
-    constexpr int kStepStride = GSPLIT ? 1 : kWavesPerBlock;     // ... and the distance to its next
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * GT;
+    const int step_first = w;                          // this wave's first step ...
+    constexpr int kStepStride = kWavesPerBlock;        // ... and the distance to its next
     const int64_t kb = static_cast<int64_t>(split) * rows_per_split;
     int64_t ke = kb + rows_per_split;
     if (ke > N) ke = N;
@@ -215,7 +207,7 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char*>(gblock + (t < n_steps ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) sg.g[r] = load_g<CW, GSPLIT ? 0 : kStreamAux>(rsrc, voff[r]);
+        for (int r = 0; r < 8; ++r) sg.g[r] = load_g<CW, kStreamAux>(rsrc, voff[r]);
     };
     auto load_s_step = [&](WgradStage<CW, GT, DIRECT>& sg, int t) {
         const uint32_t off = static_cast<uint32_t>(t) * s_step_bytes;
@@ -280,9 +272,8 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
         }
     }
 
-    // Epilogue through LDS, one 16-group tile at a time, so that the partial
-    // tile is written with lanes running along g.  Alternating-step waves are
-    // summed in a fixed order; group-splitting waves each own their tiles.
+    // Sum the four waves in a fixed order through LDS, one 16-group tile at a
+    // time, and write the block's partial tile with lanes running along g.
     float* out = partial + static_cast<int64_t>(split) * O * Mp;
 #pragma unroll
     for (int a = 0; a < GT; ++a) {
@@ -291,19 +282,144 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
 #pragma unroll
             for (int r = 0; r < 4; ++r) lds[w][jj * CW + c][q * 4 + r] = acc[a][c][r];
         __syncthreads();
-        if constexpr (GSPLIT) {
-            for (int idx = lane; idx < OT * 16; idx += kWave) {
-                const int ol = idx >> 4, gl = idx & 15;
-                const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
-                if (o < O && g < M) out[o * Mp + g] = lds[w][ol][gl];
+        for (int idx = threadIdx.x; idx < OT * 16; idx += blockDim.x) {
+            const int ol = idx >> 4, gl = idx & 15;
+            const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
+            if (o < O && g < M) out[o * Mp + g] = ((lds[0][ol][gl] + lds[1][ol][gl]) + lds[2][ol][gl]) + lds[3][ol][gl];
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 1, MFMA path for many group tiles (8, 12 or 16 per block).
+//
+// With that many tiles a wave cannot hold accumulators for all of them, so the
+// four waves split the tiles (GTW each) and all walk every 32-token step of the
+// block's range.  They then need the same G tile (32 tokens x 128 features,
+// 8 KB): each wave fetches a quarter of it from HBM (its lanes' rows 2w, 2w+1
+// of every 8-row group) into a register ring NST steps deep, publishes it in a
+// double-buffered LDS tile, and after one barrier every wave reads the whole
+// tile back in the lane layout of the in-register transpose.  G is thus read
+// once per block, S (packed fragments) once per 128 output features.
+// grid = (o tiles of 128, splits, g chunks of 64*GTW groups)
+// ---------------------------------------------------------------------------
+template <int GTW, int NST>
+__global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint16_t* __restrict__ G,
+                                                                    const void* __restrict__ Spk,
+                                                                    float* __restrict__ partial, int64_t N,
+                                                                    int64_t O, int64_t M, int64_t Mp,
+                                                                    int64_t rows_per_split, int64_t tiles_packed) {
+    static_assert(NST % 2 == 0, "the LDS buffer index must be a compile-time function of the ring slot");
+    constexpr int CW = 8;
+    constexpr int OT = 16 * CW;
+    __shared__ uint4 gtile[2][kStep][16];              // [buffer][token][16-byte chunk of 8 features]
+    __shared__ float lds[kWavesPerBlock][OT][17];      // epilogue staging
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int q = lane >> 4;
+    const int jj = lane & 15;
+    const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
+    const int split = blockIdx.y;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * (GTW * kWavesPerBlock) + w * GTW;
+    const int64_t kb = static_cast<int64_t>(split) * rows_per_split;
+    int64_t ke = kb + rows_per_split;
+    if (ke > N) ke = N;
+    const int rows = static_cast<int>(ke - kb);
+    const int n_steps = (rows + kStep - 1) / kStep;
+    const bool col_ok = o0 + jj * CW < O;
+
+    const uint32_t row_bytes = static_cast<uint32_t>(O) * 2u;
+    uint32_t voff[2];                                  // this wave's two rows of every 8-row group
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+        voff[i] = col_ok ? static_cast<uint32_t>(q * 8 + 2 * w + i) * row_bytes + static_cast<uint32_t>(jj * CW * 2)
+                         : 0xFFFFFFFFu;
+    const char* gblock = reinterpret_cast<const char*>(G) + (kb * O + o0) * 2;
+    const uint32_t gblock_bytes = static_cast<uint32_t>(rows) * row_bytes - static_cast<uint32_t>(o0 * 2);
+    const uint32_t step_bytes = static_cast<uint32_t>(kStep) * row_bytes;
+    const uint32_t s_step_bytes = static_cast<uint32_t>(tiles_packed) * 1024u;
+    const char* sblock = reinterpret_cast<const char*>(Spk) + ((kb / kStep) * tiles_packed + tile0) * 1024;
+    const uint32_t sblock_bytes = static_cast<uint32_t>(n_steps) * s_step_bytes - static_cast<uint32_t>(tile0) * 1024u;
+    const uint32_t s_voff = static_cast<uint32_t>(lane) * 16u;
+
+    f32x4 acc[GTW][CW];
+#pragma unroll
+    for (int a = 0; a < GTW; ++a)
+#pragma unroll
+        for (int c = 0; c < CW; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 gr[NST][2];
+    u32x4 sr[NST][GTW];
+    auto load_g_step = [&](u32x4 (&dst)[2], int t) {
+        const uint32_t off = static_cast<uint32_t>(t) * step_bytes;
+        const uint32_t left = t < n_steps ? gblock_bytes - off : 0u;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(gblock + (t < n_steps ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[i], 0, kStreamAux);
+    };
+    auto load_s_step = [&](u32x4 (&dst)[GTW], int t) {
+        const uint32_t off = static_cast<uint32_t>(t) * s_step_bytes;
+        const uint32_t left = (t < n_steps && off < sblock_bytes) ? sblock_bytes - off : 0u;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(sblock + (left ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
+#pragma unroll
+        for (int a = 0; a < GTW; ++a) dst[a] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, s_voff + a * 1024u, 0, 0);
+    };
+
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+        load_g_step(gr[s], s);
+        load_s_step(sr[s], s);
+    }
+    for (int base = 0; base < n_steps; base += NST) {
+#pragma unroll
+        for (int s = 0; s < NST; ++s) {
+            const int tn = base + s + NST;
+            const int buf = s & 1;                     // == (base + s) & 1 because NST is even
+            // publish this wave's quarter of the step's G tile, refill the ring slot
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                gtile[buf][q * 8 + 2 * w + i][jj] = make_uint4(gr[s][i].x, gr[s][i].y, gr[s][i].z, gr[s][i].w);
+            load_g_step(gr[s], tn);
+            __syncthreads();
+            // the whole tile, in the (8 rows x 8 features per lane) layout of the transpose
+            RawRow<4> rowsv[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const uint4 x = gtile[buf][q * 8 + r][jj];
+                rowsv[r].w[0] = x.x; rowsv[r].w[1] = x.y; rowsv[r].w[2] = x.z; rowsv[r].w[3] = x.w;
             }
-        } else {
-            for (int idx = threadIdx.x; idx < OT * 16; idx += blockDim.x) {
-                const int ol = idx >> 4, gl = idx & 15;
-                const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
-                if (o < O && g < M)
-                    out[o * Mp + g] = ((lds[0][ol][gl] + lds[1][ol][gl]) + lds[2][ol][gl]) + lds[3][ol][gl];
+            bf16x8 gf[CW];
+#pragma unroll
+            for (int c = 0; c < CW; ++c) gf[c] = column_fragment(rowsv, c);
+#pragma unroll
+            for (int a = 0; a < GTW; ++a) {
+                const bf16x8 sf = __builtin_bit_cast(bf16x8, sr[s][a]);
+#pragma unroll
+                for (int c = 0; c < CW; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            load_s_step(sr[s], tn);
+        }
+    }
+
+    // every wave owns its tiles: stage through LDS only to write with lanes along g
+    float* out = partial + static_cast<int64_t>(split) * O * Mp;
+#pragma unroll
+    for (int a = 0; a < GTW; ++a) {
+#pragma unroll
+        for (int c = 0; c < CW; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) lds[w][jj * CW + c][q * 4 + r] = acc[a][c][r];
+        __syncthreads();
+        for (int idx = lane; idx < OT * 16; idx += kWave) {
+            const int ol = idx >> 4, gl = idx & 15;
+            const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
+            if (o < O && g < M) out[o * Mp + g] = lds[w][ol][gl];
         }
         __syncthreads();
     }
@@ -515,39 +631,53 @@ MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan)
     return ch;
 }
 
-template <int CW, int GT, int NST, bool DIRECT, bool GSPLIT>
+template <int CW, int GT, int NST, bool DIRECT>
 hipError_t launch_mfma(const void* G, const void* s_operand, float* partial, int64_t N, int64_t O, int64_t M,
                        const WgradPlan& plan, int chunks, hipStream_t st) {
     dim3 grid(static_cast<unsigned>(ceil_div(O, 16 * CW)), static_cast<unsigned>(plan.splits),
               static_cast<unsigned>(chunks));
-    hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST, DIRECT, GSPLIT>), grid, dim3(256), 0, st,
+    hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST, DIRECT>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(G), s_operand, partial, N, O, M, plan.Mp, plan.rows_per_split,
                        plan.tiles_packed);
     return hipGetLastError();
 }
 
-// (CW, tiles per block) -> kernel; GTW = tiles per wave
-#define VELORA_MFMA_CASE(CW, TILES, GTW, NST, DIRECT, GSPLIT) \
-    if (ch.cw == CW && ch.gt == TILES)                        \
-        return launch_mfma<CW, GTW, NST, DIRECT, GSPLIT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
+#define VELORA_MFMA_CASE(CW, GT, NST, DIRECT) \
+    if (ch.cw == CW && ch.gt == GT)           \
+        return launch_mfma<CW, GT, NST, DIRECT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
+
+template <int GTW, int NST>
+hipError_t launch_shared_g(const void* G, const void* s_operand, float* partial, int64_t N, int64_t O, int64_t M,
+                           const WgradPlan& plan, int chunks, hipStream_t st) {
+    dim3 grid(static_cast<unsigned>(ceil_div(O, 128)), static_cast<unsigned>(plan.splits),
+              static_cast<unsigned>(chunks));
+    hipLaunchKernelGGL((wgrad_partial_shared_g_kernel<GTW, NST>), grid, dim3(256), 0, st,
+                       static_cast<const uint16_t*>(G), s_operand, partial, N, O, M, plan.Mp, plan.rows_per_split,
+                       plan.tiles_packed);
+    return hipGetLastError();
+}
+
+#define VELORA_SHARED_G_CASE(TILES, GTW, NST) \
+    if (ch.cw == 8 && ch.gt == TILES)         \
+        return launch_shared_g<GTW, NST>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
 
 hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_operand, float* partial, int64_t N,
                          int64_t O, int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
     *handled = true;
-    VELORA_MFMA_CASE(8, 1, 1, 3, true, false) VELORA_MFMA_CASE(8, 2, 2, 3, true, false)
-    VELORA_MFMA_CASE(8, 3, 3, 4, false, false) VELORA_MFMA_CASE(8, 4, 4, 4, false, false)
-    VELORA_MFMA_CASE(8, 5, 5, 3, false, false) VELORA_MFMA_CASE(8, 6, 6, 3, false, false)
-    VELORA_MFMA_CASE(8, 8, 2, 3, false, true) VELORA_MFMA_CASE(8, 12, 3, 3, false, true)
-    VELORA_MFMA_CASE(8, 16, 4, 3, false, true)
-    VELORA_MFMA_CASE(4, 1, 1, 4, true, false) VELORA_MFMA_CASE(4, 2, 2, 4, true, false)
-    VELORA_MFMA_CASE(4, 3, 3, 4, false, false) VELORA_MFMA_CASE(4, 4, 4, 4, false, false)
-    VELORA_MFMA_CASE(4, 5, 5, 4, false, false) VELORA_MFMA_CASE(4, 6, 6, 3, false, false)
-    VELORA_MFMA_CASE(4, 8, 8, 4, false, false) VELORA_MFMA_CASE(4, 12, 12, 3, false, false)
-    VELORA_MFMA_CASE(4, 16, 16, 2, false, false)
+    VELORA_MFMA_CASE(8, 1, 3, true) VELORA_MFMA_CASE(8, 2, 3, true)
+    VELORA_MFMA_CASE(8, 3, 4, false) VELORA_MFMA_CASE(8, 4, 4, false)
+    VELORA_MFMA_CASE(8, 5, 3, false) VELORA_MFMA_CASE(8, 6, 3, false)
+    VELORA_SHARED_G_CASE(8, 2, 4) VELORA_SHARED_G_CASE(12, 3, 4) VELORA_SHARED_G_CASE(16, 4, 4)
+    VELORA_MFMA_CASE(4, 1, 4, true) VELORA_MFMA_CASE(4, 2, 4, true)
+    VELORA_MFMA_CASE(4, 3, 4, false) VELORA_MFMA_CASE(4, 4, 4, false)
+    VELORA_MFMA_CASE(4, 5, 4, false) VELORA_MFMA_CASE(4, 6, 3, false)
+    VELORA_MFMA_CASE(4, 8, 4, false) VELORA_MFMA_CASE(4, 12, 3, false)
+    VELORA_MFMA_CASE(4, 16, 2, false)
     *handled = false;
     return hipSuccess;
 }
 #undef VELORA_MFMA_CASE
+#undef VELORA_SHARED_G_CASE
 
 template <typename E>
 hipError_t launch_simple(const void* G, const void* S, float* partial, int64_t N, int64_t O, int64_t M,
