@@ -61,7 +61,8 @@ typedef enum {
     VELORA_OP_INIT_V = 0,
     VELORA_OP_COMPRESS = 1,
     VELORA_OP_RECONSTRUCT = 2,
-    VELORA_OP_WEIGHT_GRAD = 3
+    VELORA_OP_WEIGHT_GRAD = 3,
+    VELORA_OP_WEIGHT_GRAD_FACTOR = 4
 } velora_op;
 
 typedef void* velora_stream; /* hipStream_t */
@@ -132,6 +133,29 @@ velora_status velora_weight_grad(const void* G, const void* S, const float* v,
                                  int64_t N, int64_t O, int64_t D, int64_t M, velora_dtype in_dt,
                                  void* dW, velora_dtype dw_dt, int accumulate,
                                  void* ws, size_t ws_bytes, velora_stream stream);
+
+/*
+ * The factored hand-off of the same gradient.  Since the reconstruction of
+ * Sec. 3.2 is Xhat[n, g*d+j] = S[n,g]*v[j], Algorithm 1's grad_weight equals
+ * T (x) v with T[o, g] = sum_n G[n, o] * S[n, g]: d times smaller than dW.  A
+ * caller that reduces gradients across devices or applies the update itself
+ * can take T and expand later (or never materialise dW).
+ *
+ * velora_weight_grad_factor:  T[O, M] (float32, dense, overwritten) = G^T S.
+ *   G [N, O], S [N, M] device, dtype in_dt (read only); v is not needed.
+ *   ws >= velora_workspace_bytes(VELORA_OP_WEIGHT_GRAD_FACTOR, N, M, O, M, in_dt)
+ *   (pass D = M in the query; the factor does not depend on the sub-token size).
+ * velora_expand_factor:  dW[o, g*d + j] (+)= T[o, g] * v[j].
+ *   T [O, M] device float32, v [d] device float32 (read only); dW [O, D] device,
+ *   dtype dw_dt; accumulate as in velora_weight_grad.  No workspace.
+ * velora_weight_grad(...) is factor followed by expand (its token split may
+ * differ, so the two agree to rounding, not bit for bit).
+ */
+velora_status velora_weight_grad_factor(const void* G, const void* S, int64_t N, int64_t O, int64_t M,
+                                        velora_dtype in_dt, float* T, void* ws, size_t ws_bytes,
+                                        velora_stream stream);
+velora_status velora_expand_factor(const float* T, const float* v, int64_t O, int64_t D, int64_t M, void* dW,
+                                   velora_dtype dw_dt, int accumulate, velora_stream stream);
 
 #ifdef __cplusplus
 }

@@ -20,6 +20,7 @@ OP_INIT_V = 0
 OP_COMPRESS = 1
 OP_RECONSTRUCT = 2
 OP_WEIGHT_GRAD = 3
+OP_WEIGHT_GRAD_FACTOR = 4
 
 STATUS = {
     0: "VELORA_OK", 1: "VELORA_ERR_NULL", 2: "VELORA_ERR_SHAPE", 3: "VELORA_ERR_DTYPE",
@@ -28,7 +29,8 @@ STATUS = {
 
 EXPORTS = [
     "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
-    "velora_compress", "velora_reconstruct", "velora_weight_grad",
+    "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_factor",
+    "velora_expand_factor",
 ]
 
 
@@ -64,6 +66,10 @@ def _load() -> ctypes.CDLL:
     L.velora_reconstruct.restype = ci
     L.velora_weight_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, ci, ci, vp, sz, vp]
     L.velora_weight_grad.restype = ci
+    L.velora_weight_grad_factor.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
+    L.velora_weight_grad_factor.restype = ci
+    L.velora_expand_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp]
+    L.velora_expand_factor.restype = ci
     return L
 
 
@@ -216,4 +222,49 @@ def velora_weight_grad(G, S, v, D: int, dW=None, dw_dtype=None, accumulate: bool
     st = raw.velora_weight_grad(G.data_ptr(), S.data_ptr(), v.data_ptr(), N, O, D, M, _dt(G), dW.data_ptr(),
                                 _dt(dW), 1 if accumulate else 0, ws.data_ptr(), ws.numel(), _stream())
     _raise(st, "velora_weight_grad")
+    return dW
+
+
+def velora_weight_grad_factor(G, S, T=None, ws=None):
+    """T[O, M] = G^T S (float32): the factor of the weight gradient, d times smaller than dW."""
+    torch = _torch()
+    _check(G, "G", 2)
+    _check(S, "S", 2)
+    N, O = G.shape
+    N2, M = S.shape
+    if N2 != N:
+        raise ValueError("G and S must have the same number of tokens")
+    if G.dtype != S.dtype:
+        raise TypeError("G and S must share a dtype")
+    if T is None:
+        T = torch.empty((O, M), dtype=torch.float32, device=G.device)
+    _check(T, "T", 2)
+    if tuple(T.shape) != (O, M) or T.dtype != torch.float32:
+        raise ValueError(f"T must be float32 [{O}, {M}]")
+    need = velora_workspace_bytes(OP_WEIGHT_GRAD_FACTOR, N, M, O, M, _dt(G))
+    ws = _ws(need, G, ws)
+    st = raw.velora_weight_grad_factor(G.data_ptr(), S.data_ptr(), N, O, M, _dt(G), T.data_ptr(), ws.data_ptr(),
+                                       ws.numel(), _stream())
+    _raise(st, "velora_weight_grad_factor")
+    return T
+
+
+def velora_expand_factor(T, v, D: int, dW=None, dw_dtype=None, accumulate: bool = False):
+    """dW[o, g*d + j] (+)= T[o, g] * v[j]."""
+    torch = _torch()
+    _check(T, "T", 2)
+    _check(v, "v", 1)
+    O, M = T.shape
+    if T.dtype != torch.float32 or v.dtype != torch.float32:
+        raise TypeError("T and v must be float32")
+    if dW is None:
+        if accumulate:
+            raise ValueError("accumulate=True needs an existing dW")
+        dW = torch.empty((O, D), dtype=dw_dtype or torch.float32, device=T.device)
+    _check(dW, "dW", 2)
+    if tuple(dW.shape) != (O, D):
+        raise ValueError(f"dW must be [{O}, {D}]")
+    st = raw.velora_expand_factor(T.data_ptr(), v.data_ptr(), O, D, M, dW.data_ptr(), _dt(dW),
+                                  1 if accumulate else 0, _stream())
+    _raise(st, "velora_expand_factor")
     return dW

@@ -86,6 +86,9 @@ size_t velora_workspace_bytes(velora_op op, int64_t N, int64_t D, int64_t O, int
         case VELORA_OP_WEIGHT_GRAD:
             if (O <= 0 || !size_ok(N, O) || !size_ok(O, D)) return 0;
             return velora::plan_wgrad(N, O, D, M, in_dt == VELORA_BF16, cfg).ws_bytes;
+        case VELORA_OP_WEIGHT_GRAD_FACTOR:
+            if (O <= 0 || !size_ok(N, O) || !size_ok(O, M)) return 0;
+            return velora::plan_wgrad(N, O, M, M, in_dt == VELORA_BF16, cfg).ws_bytes;
         case VELORA_OP_COMPRESS:
         case VELORA_OP_RECONSTRUCT:
             return 0;
@@ -161,6 +164,35 @@ velora_status velora_weight_grad(const void* G, const void* S, const float* v, i
     return hip_status(velora::launch_wgrad(G, S, v, N, O, D, M, bf, ptr_align(G), ptr_align(S), ptr_align(v), dW,
                                            dw_dt == VELORA_BF16, ptr_align(dW), accumulate != 0, ws, plan, cfg,
                                            static_cast<hipStream_t>(stream)));
+}
+
+velora_status velora_weight_grad_factor(const void* G, const void* S, int64_t N, int64_t O, int64_t M,
+                                        velora_dtype in_dt, float* T, void* ws, size_t ws_bytes,
+                                        velora_stream stream) {
+    if (!G || !S || !T) return VELORA_ERR_NULL;
+    if (!dtype_ok(in_dt)) return VELORA_ERR_DTYPE;
+    if (N <= 0 || O <= 0 || M <= 0 || !size_ok(N, O) || !size_ok(N, M) || !size_ok(O, M) || O > INT32_MAX)
+        return VELORA_ERR_SHAPE;
+    const int eb = elem_bytes(in_dt);
+    if (ptr_align(G) < eb || ptr_align(S) < eb || ptr_align(T) < 4) return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool bf = in_dt == VELORA_BF16;
+    // the split plan of the factor does not depend on d; D = M stands for "no expansion"
+    const velora::WgradPlan plan = velora::plan_wgrad(N, O, M, M, bf, cfg);
+    if (!ws || ws_bytes < plan.ws_bytes) return VELORA_ERR_WORKSPACE;
+    if (ptr_align(ws) < 16) return VELORA_ERR_ALIGN;
+    return hip_status(velora::launch_wgrad_factor(G, S, N, O, M, bf, ptr_align(G), T, ws, plan,
+                                                  static_cast<hipStream_t>(stream)));
+}
+
+velora_status velora_expand_factor(const float* T, const float* v, int64_t O, int64_t D, int64_t M, void* dW,
+                                   velora_dtype dw_dt, int accumulate, velora_stream stream) {
+    if (!T || !v || !dW) return VELORA_ERR_NULL;
+    if (!dtype_ok(dw_dt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(O, D, M) || !size_ok(O, D) || D / M > INT32_MAX / 8 || O > INT32_MAX) return VELORA_ERR_SHAPE;
+    if (ptr_align(T) < 4 || ptr_align(v) < 4 || ptr_align(dW) < elem_bytes(dw_dt)) return VELORA_ERR_ALIGN;
+    return hip_status(velora::launch_expand_factor(T, v, ptr_align(v), dW, dw_dt == VELORA_BF16, ptr_align(dW),
+                                                   accumulate != 0, O, D, M, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

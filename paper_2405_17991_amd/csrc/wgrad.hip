@@ -691,8 +691,8 @@ hipError_t launch_simple(const void* G, const void* S, float* partial, int64_t N
 }
 
 template <bool OUT_BF16, bool VEC>
-hipError_t launch_expand(const float* partial, const float* v, void* dW, int64_t O, int64_t D, int64_t M,
-                         const WgradPlan& plan, bool accumulate, hipStream_t st) {
+hipError_t launch_expand(const float* partial, int splits, int64_t Mp, const float* v, void* dW, int64_t O, int64_t D,
+                         int64_t M, bool accumulate, hipStream_t st) {
     const int d = static_cast<int>(D / M);
     int d_shift = -1;
     if ((d & (d - 1)) == 0) {
@@ -709,7 +709,7 @@ hipError_t launch_expand(const float* partial, const float* v, void* dW, int64_t
     if (threads > kExpandThreads) threads = kExpandThreads;
     int rows_per_block = 1;
     if (threads < 256) {
-        while (rows_per_block < 16 && threads * rows_per_block * 2 <= 256 && rows_per_block * 2 * plan.splits <= kTChunk)
+        while (rows_per_block < 16 && threads * rows_per_block * 2 <= 256 && rows_per_block * 2 * splits <= kTChunk)
             rows_per_block *= 2;
         threads = threads * rows_per_block;
         threads = ceil_div(threads, 64) * 64;
@@ -717,8 +717,8 @@ hipError_t launch_expand(const float* partial, const float* v, void* dW, int64_t
         while (threads % rows_per_block) threads += 64;
     }
     hipLaunchKernelGGL((wgrad_expand_kernel<OUT_BF16, VEC>), dim3(static_cast<unsigned>(ceil_div(O, rows_per_block))),
-                       dim3(static_cast<unsigned>(threads)), 0, st, partial, v, dW, plan.splits, O, D, M, plan.Mp, d,
-                       d_shift, accumulate ? 1 : 0, rows_per_block);
+                       dim3(static_cast<unsigned>(threads)), 0, st, partial, v, dW, splits, O, D, M, Mp, d, d_shift,
+                       accumulate ? 1 : 0, rows_per_block);
     return hipGetLastError();
 }
 
@@ -766,15 +766,14 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     return p;
 }
 
-hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D, int64_t M,
-                        bool is_bf16, int g_align, int s_align, int v_align, void* dW, bool dw_bf16, int dw_align,
-                        bool accumulate, void* ws, const WgradPlan& plan, const LaunchCfg& cfg, hipStream_t st) {
-    (void)cfg;
+namespace {
+
+// pack (if needed) + partial kernel: leaves partial[splits][O][Mp] in the workspace
+hipError_t launch_partials(const void* G, const void* S, int64_t N, int64_t O, int64_t M, bool is_bf16, int g_align,
+                           void* ws, const WgradPlan& plan, int phases, hipStream_t st) {
     float* partial = static_cast<float*>(ws);
     hipError_t e = hipSuccess;
     bool done = false;
-    const int phases = env_int("VELORA_WGRAD_PHASES", 7);   // tuning aid: 1 pack, 2 partial, 4 expand
-    (void)s_align;
     if (is_bf16 && env_int("VELORA_WGRAD_FORCE_SIMPLE", 0) == 0) {
         const MfmaChoice ch = choose_mfma(O, M, g_align, plan);
         if (ch.cw != 0) {
@@ -797,17 +796,61 @@ hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N,
     if (!done) {
         e = is_bf16 ? launch_simple<Bf16Elem>(G, S, partial, N, O, M, plan, st)
                     : launch_simple<F32Elem>(G, S, partial, N, O, M, plan, st);
-        if (e != hipSuccess) return e;
     }
-    if (!(phases & 4)) return hipSuccess;
+    return e;
+}
+
+hipError_t expand_any(const float* partial, int splits, int64_t Mp, const float* v, int v_align, void* dW,
+                      bool dw_bf16, int dw_align, bool accumulate, int64_t O, int64_t D, int64_t M, hipStream_t st) {
     const int64_t d = D / M;
     const bool vec = (d % 4 == 0) && v_align >= 16 && dw_align >= (dw_bf16 ? 8 : 16);
     if (dw_bf16) {
-        return vec ? launch_expand<true, true>(partial, v, dW, O, D, M, plan, accumulate, st)
-                   : launch_expand<true, false>(partial, v, dW, O, D, M, plan, accumulate, st);
+        return vec ? launch_expand<true, true>(partial, splits, Mp, v, dW, O, D, M, accumulate, st)
+                   : launch_expand<true, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, st);
     }
-    return vec ? launch_expand<false, true>(partial, v, dW, O, D, M, plan, accumulate, st)
-               : launch_expand<false, false>(partial, v, dW, O, D, M, plan, accumulate, st);
+    return vec ? launch_expand<false, true>(partial, splits, Mp, v, dW, O, D, M, accumulate, st)
+               : launch_expand<false, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, st);
+}
+
+}  // namespace
+
+// T[o, g] = sum over splits of partial[split][o][g], fixed order; T is dense [O, M].
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ T,
+                                                          int splits, int64_t O, int64_t M, int64_t Mp) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= O * M) return;
+    const int64_t o = i / M, g = i - o * M;
+    const float* p = partial + o * Mp + g;
+    float s = 0.f;
+    for (int sp = 0; sp < splits; ++sp) s += p[sp * O * Mp];
+    T[i] = s;
+}
+
+hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D, int64_t M,
+                        bool is_bf16, int g_align, int s_align, int v_align, void* dW, bool dw_bf16, int dw_align,
+                        bool accumulate, void* ws, const WgradPlan& plan, const LaunchCfg& cfg, hipStream_t st) {
+    (void)cfg;
+    (void)s_align;
+    const int phases = env_int("VELORA_WGRAD_PHASES", 7);   // tuning aid: 1 pack, 2 partial, 4 expand
+    hipError_t e = launch_partials(G, S, N, O, M, is_bf16, g_align, ws, plan, phases, st);
+    if (e != hipSuccess) return e;
+    if (!(phases & 4)) return hipSuccess;
+    return expand_any(static_cast<const float*>(ws), plan.splits, plan.Mp, v, v_align, dW, dw_bf16, dw_align, accumulate,
+                      O, D, M, st);
+}
+
+hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t O, int64_t M, bool is_bf16,
+                               int g_align, float* T, void* ws, const WgradPlan& plan, hipStream_t st) {
+    hipError_t e = launch_partials(G, S, N, O, M, is_bf16, g_align, ws, plan, 7, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(O * M, 256))), dim3(256), 0, st,
+                       static_cast<const float*>(ws), T, plan.splits, O, M, plan.Mp);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_factor(const float* T, const float* v, int v_align, void* dW, bool dw_bf16, int dw_align,
+                                bool accumulate, int64_t O, int64_t D, int64_t M, hipStream_t st) {
+    return expand_any(T, 1, M, v, v_align, dW, dw_bf16, dw_align, accumulate, O, D, M, st);
 }
 
 }  // namespace velora

@@ -223,6 +223,35 @@ def test_weight_grad_bf16_output_and_accumulate(vl, N, O, D, d):
     assert rel_fro(to_host_f64(dWa), wl.to_f64(baseb, wl.BF16) + want) <= TOL_BF16_STORE
 
 
+@pytest.mark.parametrize("N,O,D,d,dtype", [
+    (256, 64, 64, 16, wl.F32), (1000, 256, 768, 64, wl.BF16), (450, 72, 1376, 32, wl.BF16),
+    (520, 120, 5120, 64, wl.BF16), (300, 64, 1728, 8, wl.BF16), (150, 30, 64, 16, wl.BF16),
+])
+def test_factored_handoff(vl, N, O, D, d, dtype):
+    # T = G^T S on its own, its expansion, and their agreement with weight_grad
+    torch = _torch()
+    M = D // d
+    G = wl.random_tensor(N, O, dtype, seed=N + 3, stream=7, sigma=0.02)
+    S = wl.random_tensor(N, M, dtype, seed=N + 4, stream=8)
+    v = wl.random_unit_v(d, seed=d + 2)
+    Gd, Sd, vd = to_dev(G, dtype), to_dev(S, dtype), to_dev(v, wl.F32)
+    T = vl.velora_weight_grad_factor(Gd, Sd)
+    T_ref, dW_ref = oracle.weight_grad_factored(G, S, v, D)
+    tol = TOL_F32 if dtype == wl.F32 else TOL_F32_FROM_BF16
+    assert T.shape == (O, M) and T.dtype == torch.float32
+    assert rel_fro(to_host_f64(T), T_ref) <= tol and rel_max(to_host_f64(T), T_ref) <= tol
+    dW = vl.velora_expand_factor(T, vd, D)
+    assert rel_fro(to_host_f64(dW), dW_ref) <= tol
+    # weight_grad is factor followed by expand (the token split may differ, so not bit for bit)
+    dW2 = vl.velora_weight_grad(Gd, Sd, vd, D)
+    assert rel_fro(to_host_f64(dW), to_host_f64(dW2)) <= 2e-6
+    # expanding an exactly known T: one float32 multiply per element
+    T1 = torch.arange(O * M, dtype=torch.float32, device="cuda").reshape(O, M) - 7.0
+    dW1 = vl.velora_expand_factor(T1, vd, D).cpu().numpy().reshape(O, M, d)
+    want = T1.cpu().numpy()[:, :, None] * v[None, None, :]
+    assert (dW1 == want).all()
+
+
 def test_weight_grad_single_one_copies_reconstructed_token(vl):
     # G = e_n e_o^T: row o of dW is the reconstructed token n, everything else 0.
     N, O, D, d = 160, 128, 256, 32
