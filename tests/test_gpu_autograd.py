@@ -1,0 +1,84 @@
+"""The autograd wrapper around the two VeLoRA kernels (paper Algorithm 1): the
+forward output is the dense product, the weight gradient is the one built from
+compressed activations, and what autograd keeps for backward shrinks by d."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_helpers import TOL_BF16_STORE, TOL_F32, rel_fro, to_dev, to_host_bits, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mods():
+    import __graft_entry__ as ge
+    ge.ensure_built()
+    import torch
+    from paper_2405_17991_amd import autograd as va
+    return torch, va
+
+
+@pytest.mark.parametrize("dtype,B,T,D,O,d", [("bf16", 4, 197, 768, 256, 64), ("f32", 2, 128, 64, 48, 16)])
+def test_layer_forward_backward(mods, dtype, B, T, D, O, d):
+    torch, va = mods
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    sdt = wl.BF16 if dtype == "bf16" else wl.F32
+    torch.manual_seed(0)
+    layer = va.VeLoRALinear(D, O, d, device="cuda", dtype=tdt)
+    Xh = wl.random_tensor(B * T, D, sdt, seed=7)
+    Xh = wl.to_storage(wl.to_f64(Xh, sdt).astype(np.float32) + 0.5, sdt)      # non-zero mean: well-conditioned v
+    Gh = wl.random_tensor(B * T, O, sdt, seed=8, sigma=0.02)
+    x = to_dev(Xh, sdt).reshape(B, T, D).requires_grad_(True)
+    out = layer(x)
+    assert out.shape == (B, T, O) and bool(layer.v_ready)
+    ref = torch.nn.functional.linear(x.detach(), layer.weight.detach())
+    assert torch.equal(out.detach(), ref)                                      # forward compute is preserved
+    g = to_dev(Gh, sdt).reshape(B, T, O)
+    out.backward(g)
+    # v: the normalised mean of the first batch's sub-tokens
+    v_ref, _, rc = oracle.init_v(Xh, D // d)
+    assert rc == 0
+    v_gpu = layer.v.cpu().numpy()
+    assert np.linalg.norm(v_gpu.astype(np.float64) - v_ref) <= 1e-5
+    # grad_weight = G^T Xhat with Xhat rebuilt from the stored S (oracle, from the definition)
+    _, S_store = oracle.compress(Xh, v_gpu, D // d)
+    want = oracle.weight_grad_bruteforce(Gh, S_store, v_gpu, D)
+    got = to_host_f64(layer.weight.grad)
+    assert got.shape == (O, D)
+    assert rel_fro(got, want) <= (2 * TOL_BF16_STORE if dtype == "bf16" else 10 * TOL_F32)
+    # grad_input is the untouched dense product
+    gi = torch.matmul(g.reshape(-1, O), layer.weight.detach()).reshape(B, T, D)
+    assert torch.equal(x.grad, gi)
+    # v stays frozen on later batches
+    before = layer.v.clone()
+    layer(x.detach() * 3.0)
+    assert torch.equal(layer.v, before)
+
+
+def test_saved_activation_shrinks_by_d(mods):
+    torch, va = mods
+    N, D, O, d = 2048, 1024, 512, 64
+    layer = va.VeLoRALinear(D, O, d, device="cuda", dtype=torch.bfloat16)
+    x = torch.randn(N, D, device="cuda", dtype=torch.bfloat16)
+    layer.init_v(x)
+
+    def saved_bytes(fn):
+        seen = {}
+
+        def pack(t):
+            if t.data_ptr() not in (layer.weight.data_ptr(), layer.v.data_ptr()):
+                seen[t.data_ptr()] = t.numel() * t.element_size()
+            return t
+
+        with torch.autograd.graph.saved_tensors_hooks(pack, lambda t: t):
+            fn()
+        return sum(seen.values())
+
+    base = saved_bytes(lambda: torch.nn.functional.linear(x.requires_grad_(True), layer.weight))
+    ours = saved_bytes(lambda: layer(x.requires_grad_(True)))
+    acc = va.saved_activation_bytes(N, D, d, 2)
+    assert base == acc["baseline"] == N * D * 2
+    assert ours == acc["velora"] == N * (D // d) * 2
+    assert base // ours == d
