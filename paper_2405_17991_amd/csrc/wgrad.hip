@@ -298,19 +298,22 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
 // four waves split the tiles (GTW each) and all walk every 32-token step of the
 // block's range.  They then need the same G tile (32 tokens x 128 features,
 // 8 KB): each wave fetches a quarter of it from HBM (its lanes' rows 2w, 2w+1
-// of every 8-row group) into a register ring NST steps deep, publishes it in a
+// of every 8-row group) into a register ring NG steps deep, publishes it in a
 // double-buffered LDS tile, and after one barrier every wave reads the whole
 // tile back in the lane layout of the in-register transpose.  G is thus read
-// once per block, S (packed fragments) once per 128 output features.
+// once per block, S (packed fragments) once per 128 output features.  A wave
+// only carries 2 KB of G per step, so the G ring is deep (NG = 8: 64 KB of HBM
+// reads in flight per block); S comes from L2 and needs a shorter ring (NS).
 // grid = (o tiles of 128, splits, g chunks of 64*GTW groups)
 // ---------------------------------------------------------------------------
-template <int GTW, int NST>
+template <int GTW, int NG, int NS>
 __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint16_t* __restrict__ G,
                                                                     const void* __restrict__ Spk,
                                                                     float* __restrict__ partial, int64_t N,
                                                                     int64_t O, int64_t M, int64_t Mp,
                                                                     int64_t rows_per_split, int64_t tiles_packed) {
-    static_assert(NST % 2 == 0, "the LDS buffer index must be a compile-time function of the ring slot");
+    static_assert(NG % 2 == 0, "the LDS buffer index must be a compile-time function of the ring slot");
+    static_assert(NG % NS == 0, "the S ring slot must be a compile-time function of the G ring slot");
     constexpr int CW = 8;
     constexpr int OT = 16 * CW;
     __shared__ uint4 gtile[2][kStep][16];              // [buffer][token][16-byte chunk of 8 features]
@@ -350,8 +353,8 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
 #pragma unroll
         for (int c = 0; c < CW; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 gr[NST][2];
-    u32x4 sr[NST][GTW];
+    u32x4 gr[NG][2];
+    u32x4 sr[NS][GTW];
     auto load_g_step = [&](u32x4 (&dst)[2], int t) {
         const uint32_t off = static_cast<uint32_t>(t) * step_bytes;
         const uint32_t left = t < n_steps ? gblock_bytes - off : 0u;
@@ -370,20 +373,20 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
     };
 
 #pragma unroll
-    for (int s = 0; s < NST; ++s) {
-        load_g_step(gr[s], s);
-        load_s_step(sr[s], s);
-    }
-    for (int base = 0; base < n_steps; base += NST) {
+    for (int s = 0; s < NG; ++s) load_g_step(gr[s], s);
 #pragma unroll
-        for (int s = 0; s < NST; ++s) {
-            const int tn = base + s + NST;
-            const int buf = s & 1;                     // == (base + s) & 1 because NST is even
+    for (int s = 0; s < NS; ++s) load_s_step(sr[s], s);
+    for (int base = 0; base < n_steps; base += NG) {
+#pragma unroll
+        for (int s = 0; s < NG; ++s) {
+            const int t = base + s;
+            const int buf = s & 1;                     // == t & 1 because NG is even
+            const int ss = s % NS;                     // == t % NS because NS divides NG
             // publish this wave's quarter of the step's G tile, refill the ring slot
 #pragma unroll
             for (int i = 0; i < 2; ++i)
                 gtile[buf][q * 8 + 2 * w + i][jj] = make_uint4(gr[s][i].x, gr[s][i].y, gr[s][i].z, gr[s][i].w);
-            load_g_step(gr[s], tn);
+            load_g_step(gr[s], t + NG);
             __syncthreads();
             // the whole tile, in the (8 rows x 8 features per lane) layout of the transpose
             RawRow<4> rowsv[8];
@@ -397,13 +400,13 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
             for (int c = 0; c < CW; ++c) gf[c] = column_fragment(rowsv, c);
 #pragma unroll
             for (int a = 0; a < GTW; ++a) {
-                const bf16x8 sf = __builtin_bit_cast(bf16x8, sr[s][a]);
+                const bf16x8 sf = __builtin_bit_cast(bf16x8, sr[ss][a]);
 #pragma unroll
                 for (int c = 0; c < CW; ++c)
                     acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            load_s_step(sr[s], tn);
+            load_s_step(sr[ss], t + NS);
         }
     }
 
@@ -646,20 +649,20 @@ hipError_t launch_mfma(const void* G, const void* s_operand, float* partial, int
     if (ch.cw == CW && ch.gt == GT)           \
         return launch_mfma<CW, GT, NST, DIRECT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
 
-template <int GTW, int NST>
+template <int GTW, int NG, int NS>
 hipError_t launch_shared_g(const void* G, const void* s_operand, float* partial, int64_t N, int64_t O, int64_t M,
                            const WgradPlan& plan, int chunks, hipStream_t st) {
     dim3 grid(static_cast<unsigned>(ceil_div(O, 128)), static_cast<unsigned>(plan.splits),
               static_cast<unsigned>(chunks));
-    hipLaunchKernelGGL((wgrad_partial_shared_g_kernel<GTW, NST>), grid, dim3(256), 0, st,
+    hipLaunchKernelGGL((wgrad_partial_shared_g_kernel<GTW, NG, NS>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(G), s_operand, partial, N, O, M, plan.Mp, plan.rows_per_split,
                        plan.tiles_packed);
     return hipGetLastError();
 }
 
-#define VELORA_SHARED_G_CASE(TILES, GTW, NST) \
-    if (ch.cw == 8 && ch.gt == TILES)         \
-        return launch_shared_g<GTW, NST>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
+#define VELORA_SHARED_G_CASE(TILES, GTW, NG, NS) \
+    if (ch.cw == 8 && ch.gt == TILES)            \
+        return launch_shared_g<GTW, NG, NS>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
 
 hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_operand, float* partial, int64_t N,
                          int64_t O, int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
@@ -667,7 +670,7 @@ hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_oper
     VELORA_MFMA_CASE(8, 1, 3, true) VELORA_MFMA_CASE(8, 2, 3, true)
     VELORA_MFMA_CASE(8, 3, 4, false) VELORA_MFMA_CASE(8, 4, 4, false)
     VELORA_MFMA_CASE(8, 5, 3, false) VELORA_MFMA_CASE(8, 6, 3, false)
-    VELORA_SHARED_G_CASE(8, 2, 4) VELORA_SHARED_G_CASE(12, 3, 4) VELORA_SHARED_G_CASE(16, 4, 4)
+    VELORA_SHARED_G_CASE(8, 2, 8, 4) VELORA_SHARED_G_CASE(12, 3, 8, 4) VELORA_SHARED_G_CASE(16, 4, 8, 4)
     VELORA_MFMA_CASE(4, 1, 4, true) VELORA_MFMA_CASE(4, 2, 4, true)
     VELORA_MFMA_CASE(4, 3, 4, false) VELORA_MFMA_CASE(4, 4, 4, false)
     VELORA_MFMA_CASE(4, 5, 4, false) VELORA_MFMA_CASE(4, 6, 3, false)
@@ -746,6 +749,14 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     if (splits > traffic_cap) splits = traffic_cap;
     const int64_t min_rows = is_bf16 ? 256 : 32;   // the plain-FMA kernel is latency-bound per token
     if (splits > ceil_div(N, min_rows)) splits = ceil_div(N, min_rows);
+    // Long token ranges amortise a block's start-up and epilogue: prefer ranges of
+    // 2048 tokens when that gives between 0.7 and 1 block per CU (measured on the
+    // layer shapes of the five configurations; between 1 and 2 blocks per CU the
+    // uneven load costs more than the longer ranges gain).
+    const int64_t long_splits = N / 2048;
+    if (is_bf16 && long_splits >= 1 && splits > long_splits && o_tiles * long_splits * 10 >= cfg.num_cus * 7 &&
+        o_tiles * long_splits <= cfg.num_cus)
+        splits = long_splits;
     const int forced = env_int("VELORA_WGRAD_SPLITS", 0);   // tuning aid; 0 = automatic
     if (forced > 0) splits = forced;
     if (splits < 1) splits = 1;
