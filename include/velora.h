@@ -97,6 +97,37 @@ velora_status velora_init_v(const void* X, int64_t N, int64_t D, int64_t M, velo
                             float* v, void* ws, size_t ws_bytes, velora_stream stream);
 
 /*
+ * Per-batch projection vector (the "running average" and instance-wise rows of
+ * the initialisation ablation, Sec. 5.2 / Table 4c; the paper gives no formula,
+ * this is the reading taken):
+ *     m_b = mean of this batch's N*M sub-tokens
+ *     m   = mean_state ? beta * mean_state + (1 - beta) * m_b : m_b
+ *     mean_state <- m (if given),   v = m / ||m||_2
+ * beta = 0 with a state (or no state at all) is the instance-wise variant: v
+ * follows every batch.  0 <= beta <= 1 (VELORA_ERR_SHAPE otherwise).
+ *   X [N, D] device (read only); mean_state [d] device float32 (read and
+ *   written) or NULL; v [d] device float32 (written); ws as for velora_init_v.
+ * Asynchronous.  A zero or non-finite m gives v[j] = 1/sqrt(d); the status word
+ * (0 or VELORA_ERR_DEGENERATE) is left in the first 4 bytes of ws.
+ */
+velora_status velora_update_v(const void* X, int64_t N, int64_t D, int64_t M, velora_dtype xdt,
+                              float* mean_state, float beta, float* v, void* ws, size_t ws_bytes,
+                              velora_stream stream);
+
+/*
+ * compress with the current vector and update the vector for the next batch in
+ * ONE pass over X (running average: batch t is compressed with the v formed
+ * from the batches before it):
+ *     S = compress(X, v_in);   (mean_state, v_out) updated from X as in velora_update_v.
+ * v_out may be the same buffer as v_in (it is written after S is complete).
+ * S is bit-identical to velora_compress(X, v_in).  Same workspace and status
+ * word as velora_update_v.
+ */
+velora_status velora_compress_update(const void* X, const float* v_in, int64_t N, int64_t D, int64_t M,
+                                     velora_dtype xdt, void* S, float* mean_state, float beta,
+                                     float* v_out, void* ws, size_t ws_bytes, velora_stream stream);
+
+/*
  * group + compress (Sec. 3.2, Eq. 1):  S[n, g] = sum_{j<d} X[n, g*d + j] * v[j].
  *   X [N, D] device, dtype xdt (read only);  v [d] device float32 (read only)
  *   S [N, M] device, dtype xdt (written; float32 accumulate, RNE on store)

@@ -51,6 +51,8 @@ def _load():
     L.velora_oracle_widen_bf16.restype = ctypes.c_double
     L.velora_oracle_init_v.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci]
     L.velora_oracle_init_v.restype = ci
+    L.velora_oracle_update_v.argtypes = [vp, ci, i64, i64, i64, vp, ctypes.c_double, vp, vp, ci]
+    L.velora_oracle_update_v.restype = ci
     L.velora_oracle_compress.argtypes = [vp, ci, vp, i64, i64, i64, vp, vp, ci]
     L.velora_oracle_compress.restype = None
     L.velora_oracle_reconstruct.argtypes = [vp, ci, vp, i64, i64, i64, vp, ci]
@@ -125,6 +127,21 @@ def init_v(X: np.ndarray, M: int, threads: int = 0) -> Tuple[np.ndarray, np.ndar
     v = np.empty(d, dtype=np.float32)
     rc = _load().velora_oracle_init_v(_p(X), _dt(X), N, D, M, _p(mean), _p(v), threads or default_threads())
     return v, mean, int(rc)
+
+
+def update_v(X: np.ndarray, M: int, state: Optional[np.ndarray] = None, beta: float = 0.0,
+             threads: int = 0) -> Tuple[np.ndarray, Optional[np.ndarray], int]:
+    """Per-batch vector.  -> (v float32[d], new state float32[d] or None, status 0 | 6)."""
+    X = _c(X)
+    N, D = X.shape
+    assert D % M == 0
+    d = D // M
+    v = np.empty(d, dtype=np.float32)
+    st_in = None if state is None else _v32(state, d)
+    st_out = None if state is None else np.empty(d, dtype=np.float32)
+    rc = _load().velora_oracle_update_v(_p(X), _dt(X), N, D, M, _p(st_in), float(beta), _p(st_out), _p(v),
+                                        threads or default_threads())
+    return v, st_out, int(rc)
 
 
 def compress(X: np.ndarray, v: np.ndarray, M: int, threads: int = 0) -> Tuple[np.ndarray, np.ndarray]:

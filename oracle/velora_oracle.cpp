@@ -15,6 +15,9 @@
 //   proj_v            : Sec. 3.2, (z . v) . v^T with v a fixed unit vector;
 //   init of v         : Sec. 3.3 "Cheap initialisation strategies" (average
 //                       of the first batch's sub-tokens) + unit length (3.2);
+//   per-batch v       : Sec. 5.2 "Initialisation strategy" / Table 4c (running
+//                       average, instance-wise); no formula is printed, the
+//                       reading is stated at the function;
 //   grad_weight       : Algorithm 1 (backward): grad_output^T @ input_hat.
 //
 // Naming: the paper writes M for the sub-token size.  Here d is the sub-token
@@ -131,6 +134,36 @@ int velora_oracle_init_v(const void* X, int dt, int64_t N, int64_t D, int64_t M,
     }
     if (mean_out) for (int64_t j = 0; j < d; ++j) mean_out[j] = m[j];
     double norm = std::sqrt(ss);
+    if (!finite || !(norm > 0.0) || !std::isfinite(norm)) {
+        for (int64_t j = 0; j < d; ++j) v_out[j] = static_cast<float>(1.0 / std::sqrt(static_cast<double>(d)));
+        return 6;
+    }
+    for (int64_t j = 0; j < d; ++j) v_out[j] = static_cast<float>(m[j] / norm);
+    return 0;
+}
+
+// Per-batch vector (the "running average" / instance-wise rows of the
+// initialisation ablation, Sec. 5.2, Table 4c).  The paper prints no formula;
+// the reading taken: m_b = this batch's sub-token average (as in init_v),
+// m = beta * state_in + (1 - beta) * m_b when a state is given, else m = m_b;
+// state_out = m rounded to float32; v = m / ||m|| (from the unrounded m).
+// Same degenerate rule and return value as velora_oracle_init_v.
+int velora_oracle_update_v(const void* X, int dt, int64_t N, int64_t D, int64_t M, const float* state_in,
+                           double beta, float* state_out, float* v_out, int nthreads) {
+    const int64_t d = D / M;
+    std::vector<double> mb(static_cast<size_t>(d));
+    std::vector<float> tmp(static_cast<size_t>(d));
+    velora_oracle_init_v(X, dt, N, D, M, mb.data(), tmp.data(), nthreads);
+    double ss = 0.0;
+    bool finite = true;
+    std::vector<double> m(static_cast<size_t>(d));
+    for (int64_t j = 0; j < d; ++j) {
+        m[j] = state_in ? beta * static_cast<double>(state_in[j]) + (1.0 - beta) * mb[j] : mb[j];
+        ss += m[j] * m[j];
+        if (!std::isfinite(m[j])) finite = false;
+    }
+    if (state_out) for (int64_t j = 0; j < d; ++j) state_out[j] = static_cast<float>(m[j]);
+    const double norm = std::sqrt(ss);
     if (!finite || !(norm > 0.0) || !std::isfinite(norm)) {
         for (int64_t j = 0; j < d; ++j) v_out[j] = static_cast<float>(1.0 / std::sqrt(static_cast<double>(d)));
         return 6;

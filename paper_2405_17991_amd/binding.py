@@ -30,7 +30,7 @@ STATUS = {
 EXPORTS = [
     "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
     "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_factor",
-    "velora_expand_factor",
+    "velora_expand_factor", "velora_update_v", "velora_compress_update",
 ]
 
 
@@ -70,6 +70,11 @@ def _load() -> ctypes.CDLL:
     L.velora_weight_grad_factor.restype = ci
     L.velora_expand_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp]
     L.velora_expand_factor.restype = ci
+    cf = ctypes.c_float
+    L.velora_update_v.argtypes = [vp, i64, i64, i64, ci, vp, cf, vp, vp, sz, vp]
+    L.velora_update_v.restype = ci
+    L.velora_compress_update.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp, cf, vp, vp, sz, vp]
+    L.velora_compress_update.restype = ci
     return L
 
 
@@ -268,3 +273,49 @@ def velora_expand_factor(T, v, D: int, dW=None, dw_dtype=None, accumulate: bool 
                                   1 if accumulate else 0, _stream())
     _raise(st, "velora_expand_factor")
     return dW
+
+
+def velora_update_v(X, M: int, mean_state=None, beta: float = 0.0, v=None, ws=None):
+    """Per-batch vector: v = normalise(beta * mean_state + (1 - beta) * batch mean); asynchronous."""
+    torch = _torch()
+    _check(X, "X", 2)
+    N, D = X.shape
+    d = D // M if M > 0 and D % M == 0 else 1
+    if v is None:
+        v = torch.empty(d, dtype=torch.float32, device=X.device)
+    _check(v, "v", 1)
+    if mean_state is not None:
+        _check(mean_state, "mean_state", 1)
+        if mean_state.dtype != torch.float32 or mean_state.numel() != d:
+            raise ValueError("mean_state must be float32 [d]")
+    need = velora_workspace_bytes(OP_INIT_V, N, D, 0, M, _dt(X))
+    ws = _ws(need, X, ws)
+    st = raw.velora_update_v(X.data_ptr(), N, D, M, _dt(X), None if mean_state is None else mean_state.data_ptr(),
+                             float(beta), v.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    _raise(st, "velora_update_v")
+    return v
+
+
+def velora_compress_update(X, v_in, M: int, mean_state=None, beta: float = 0.0, S=None, v_out=None, ws=None):
+    """One pass: S = compress(X, v_in) and (mean_state, v_out) updated from X.  -> (S, v_out)"""
+    torch = _torch()
+    _check(X, "X", 2)
+    _check(v_in, "v_in", 1)
+    N, D = X.shape
+    if v_in.dtype != torch.float32:
+        raise TypeError("v_in must be float32")
+    if S is None:
+        S = torch.empty((N, max(M, 1)), dtype=X.dtype, device=X.device)
+    _check(S, "S", 2)
+    if v_out is None:
+        v_out = torch.empty_like(v_in)
+    _check(v_out, "v_out", 1)
+    if mean_state is not None:
+        _check(mean_state, "mean_state", 1)
+    need = velora_workspace_bytes(OP_INIT_V, N, D, 0, M, _dt(X))
+    ws = _ws(need, X, ws)
+    st = raw.velora_compress_update(X.data_ptr(), v_in.data_ptr(), N, D, M, _dt(X), S.data_ptr(),
+                                    None if mean_state is None else mean_state.data_ptr(), float(beta),
+                                    v_out.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    _raise(st, "velora_compress_update")
+    return S, v_out

@@ -108,7 +108,7 @@ velora_status velora_init_v(const void* X, int64_t N, int64_t D, int64_t M, velo
     if (!ws || ws_bytes < plan.ws_bytes) return VELORA_ERR_WORKSPACE;
     if (ptr_align(ws) < 16) return VELORA_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = velora::launch_init_v(X, v, N * M, D / M, bf, ptr_align(X) >= 16, ws, plan, st);
+    hipError_t e = velora::launch_update_v(X, nullptr, 0.0, v, N * M, D / M, bf, ptr_align(X) >= 16, ws, plan, st);
     if (e != hipSuccess) return VELORA_ERR_HIP;
     int flag = -1;
     e = hipMemcpyAsync(&flag, ws, sizeof(int), hipMemcpyDeviceToHost, st);
@@ -117,6 +117,51 @@ velora_status velora_init_v(const void* X, int64_t N, int64_t D, int64_t M, velo
     if (e != hipSuccess) return VELORA_ERR_HIP;
     if (flag == 0) return VELORA_OK;
     return flag == VELORA_ERR_DEGENERATE ? VELORA_ERR_DEGENERATE : VELORA_ERR_HIP;
+}
+
+velora_status velora_update_v(const void* X, int64_t N, int64_t D, int64_t M, velora_dtype xdt, float* mean_state,
+                              float beta, float* v, void* ws, size_t ws_bytes, velora_stream stream) {
+    if (!X || !v) return VELORA_ERR_NULL;
+    if (!dtype_ok(xdt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(N, D, M) || !size_ok(N, D) || D / M > INT32_MAX / 8 || !(beta >= 0.f && beta <= 1.f))
+        return VELORA_ERR_SHAPE;
+    if (ptr_align(X) < elem_bytes(xdt) || ptr_align(v) < 4 || (mean_state && ptr_align(mean_state) < 4))
+        return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool bf = xdt == VELORA_BF16;
+    const velora::InitVPlan plan = velora::plan_init_v(N * M, D / M, bf, cfg);
+    if (!ws || ws_bytes < plan.ws_bytes) return VELORA_ERR_WORKSPACE;
+    if (ptr_align(ws) < 16) return VELORA_ERR_ALIGN;
+    return hip_status(velora::launch_update_v(X, mean_state, static_cast<double>(beta), v, N * M, D / M, bf,
+                                              ptr_align(X) >= 16, ws, plan, static_cast<hipStream_t>(stream)));
+}
+
+velora_status velora_compress_update(const void* X, const float* v_in, int64_t N, int64_t D, int64_t M,
+                                     velora_dtype xdt, void* S, float* mean_state, float beta, float* v_out,
+                                     void* ws, size_t ws_bytes, velora_stream stream) {
+    if (!X || !v_in || !S || !v_out) return VELORA_ERR_NULL;
+    if (!dtype_ok(xdt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(N, D, M) || !size_ok(N, D) || D / M > INT32_MAX / 8 || !(beta >= 0.f && beta <= 1.f))
+        return VELORA_ERR_SHAPE;
+    const int eb = elem_bytes(xdt);
+    if (ptr_align(X) < eb || ptr_align(S) < eb || ptr_align(v_in) < 4 || ptr_align(v_out) < 4 ||
+        (mean_state && ptr_align(mean_state) < 4))
+        return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool bf = xdt == VELORA_BF16;
+    const velora::InitVPlan plan = velora::plan_init_v(N * M, D / M, bf, cfg);
+    if (!ws || ws_bytes < plan.ws_bytes) return VELORA_ERR_WORKSPACE;
+    if (ptr_align(ws) < 16) return VELORA_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool vec_ok = ptr_align(X) >= 16;
+    if (velora::fused_compress_update_ok(D / M, bf, vec_ok))
+        return hip_status(velora::launch_compress_update(X, v_in, S, mean_state, static_cast<double>(beta), v_out,
+                                                         N * M, D / M, bf, ws, plan, st));
+    // shapes the one-pass kernel does not take: compress, then the update as a second pass
+    hipError_t e = velora::launch_compress(X, v_in, S, N * M, D / M, bf, vec_ok, cfg, st);
+    if (e != hipSuccess) return VELORA_ERR_HIP;
+    return hip_status(velora::launch_update_v(X, mean_state, static_cast<double>(beta), v_out, N * M, D / M, bf, vec_ok,
+                                              ws, plan, st));
 }
 
 velora_status velora_compress(const void* X, const float* v, int64_t N, int64_t D, int64_t M, velora_dtype xdt,

@@ -104,37 +104,53 @@ __global__ __launch_bounds__(256) void colsum_generic_kernel(const typename E::t
     }
 }
 
-// mean[j] = (sum over blocks of partial[b][j]) / n_sub, in float64, fixed order.
-// 32 columns x 8 slices of the block axis per 256-thread block.
+// Stage 1 of the combine: slice sl of the block axis, 32 columns per block;
+// slices[sl][j] = sum over the slice's blocks of partial[b][j], in float64, in a
+// fixed order (8 interleaved row lanes, then the lanes in order).
+constexpr int kSlices = 8;
+
 __global__ __launch_bounds__(256) void colsum_combine_kernel(const float* __restrict__ partial,
-                                                            double* __restrict__ mean, int blocks, int d,
-                                                            double inv_count) {
+                                                            double* __restrict__ slices, int blocks, int d) {
     __shared__ double red[8][32];
     const int c = threadIdx.x & 31;
     const int r = threadIdx.x >> 5;
     const int j = blockIdx.x * 32 + c;
+    const int per_slice = (blocks + kSlices - 1) / kSlices;
+    const int b0 = blockIdx.y * per_slice;
+    int b1 = b0 + per_slice;
+    if (b1 > blocks) b1 = blocks;
     double s = 0.0;
     if (j < d)
-        for (int b = r; b < blocks; b += 8) s += static_cast<double>(partial[static_cast<int64_t>(b) * d + j]);
+        for (int b = b0 + r; b < b1; b += 8) s += static_cast<double>(partial[static_cast<int64_t>(b) * d + j]);
     red[r][c] = s;
     __syncthreads();
     if (r == 0 && j < d) {
         double t = 0.0;
         for (int rr = 0; rr < 8; ++rr) t += red[rr][c];
-        mean[j] = t * inv_count;
+        slices[static_cast<int64_t>(blockIdx.y) * d + j] = t;
     }
 }
 
-// v = mean / ||mean||; flag = 0, or 6 (and v = 1/sqrt(d)) when the mean is zero
-// or not finite.  One block.
-__global__ __launch_bounds__(256) void normalise_v_kernel(const double* __restrict__ mean, float* __restrict__ v,
-                                                         int* __restrict__ flag, int d) {
+// Stage 2 (one block): batch mean m_b = (sum of slices) / n_sub; with a running
+// state, m = beta * state + (1 - beta) * m_b and state <- m (float32); v = m / ||m||.
+// flag = 0, or 6 (and v = 1/sqrt(d)) when m is zero or not finite.
+__global__ __launch_bounds__(256) void normalise_v_kernel(const double* __restrict__ slices, double* __restrict__ mean,
+                                                         float* __restrict__ state, double beta,
+                                                         float* __restrict__ v, int* __restrict__ flag, int d,
+                                                         double inv_count) {
     __shared__ double red[256];
     __shared__ int bad[256];
     double ss = 0.0;
     int nonfinite = 0;
     for (int j = threadIdx.x; j < d; j += blockDim.x) {
-        const double m = mean[j];
+        double m = 0.0;
+        for (int sl = 0; sl < kSlices; ++sl) m += slices[static_cast<int64_t>(sl) * d + j];
+        m *= inv_count;
+        if (state != nullptr) {
+            m = beta * static_cast<double>(state[j]) + (1.0 - beta) * m;
+            state[j] = static_cast<float>(m);
+        }
+        mean[j] = m;
         ss += m * m;
         if (!isfinite(m)) nonfinite = 1;
     }
@@ -153,6 +169,92 @@ __global__ __launch_bounds__(256) void normalise_v_kernel(const double* __restri
     for (int j = threadIdx.x; j < d; j += blockDim.x)
         v[j] = degenerate ? static_cast<float>(1.0 / sqrt(static_cast<double>(d))) : static_cast<float>(mean[j] / norm);
     if (threadIdx.x == 0) *flag = degenerate ? 6 : 0;
+}
+
+// ---------------------------------------------------------------------------
+// compress and column sums in ONE pass over X (running-average v): the same
+// loop as compress_vec_kernel with the projection vector of the previous
+// batches, plus the per-lane column sums that will form the next one.
+// ---------------------------------------------------------------------------
+template <typename E, int P, int L, int U>
+__global__ __launch_bounds__(256) void compress_colsum_vec_kernel(const uint4* __restrict__ X,
+                                                                 const float* __restrict__ v,
+                                                                 typename E::type* __restrict__ S,
+                                                                 float* __restrict__ partial, int64_t n_sub, int d) {
+    constexpr int kV = E::kPerVec;
+    constexpr int SEG = kWave / P;
+    constexpr int kVecPerSub = P * L;
+    constexpr int kWavesPerBlock = 256 / kWave;
+    __shared__ float lds[kWavesPerBlock][L * kV][kWave + 1];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wib = threadIdx.x / kWave;
+    const int p = lane % P;
+    const int seg = lane / P;
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * blockDim.x / kWave;
+    const int64_t n_chunks = ceil_div(n_sub, static_cast<int64_t>(SEG) * U);
+
+    float vf[L][kV], acc[L][kV];
+#pragma unroll
+    for (int l = 0; l < L; ++l)
+#pragma unroll
+        for (int e = 0; e < kV; ++e) {
+            vf[l][e] = v[(l * P + p) * kV + e];
+            acc[l][e] = 0.f;
+        }
+
+    for (int64_t chunk = wave; chunk < n_chunks; chunk += n_waves) {
+        const int64_t k0 = chunk * (SEG * U) + static_cast<int64_t>(seg) * U;
+        uint4 q[U][L];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                q[u][l] = make_uint4(0u, 0u, 0u, 0u);
+                if (k0 + u < n_sub) q[u][l] = load_stream16(&X[(k0 + u) * kVecPerSub + l * P + p]);
+            }
+        float sum[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float dot = 0.f;
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                float f[kV];
+                E::unpack(q[u][l], f);
+#pragma unroll
+                for (int e = 0; e < kV; ++e) {
+                    dot = fmaf(f[e], vf[l][e], dot);
+                    acc[l][e] += f[e];
+                }
+            }
+            sum[u] = group_sum<P>(dot);
+        }
+#pragma unroll
+        for (int u0 = 0; u0 < U; u0 += P) {
+            float val = sum[u0];
+#pragma unroll
+            for (int t = 1; t < P && u0 + t < U; ++t)
+                if (p == t) val = sum[u0 + t];
+            const int u = u0 + p;
+            if (u < U && k0 + u < n_sub) E::store(S, k0 + u, val);
+        }
+    }
+#pragma unroll
+    for (int l = 0; l < L; ++l)
+#pragma unroll
+        for (int e = 0; e < kV; ++e) lds[wib][l * kV + e][lane] = acc[l][e];
+    __syncthreads();
+    for (int j = threadIdx.x; j < d; j += blockDim.x) {
+        const int l = j / (P * kV);
+        const int rem = j - l * (P * kV);
+        const int pp = rem / kV;
+        const int e = rem - pp * kV;
+        float s = 0.f;
+        for (int w = 0; w < kWavesPerBlock; ++w)
+            for (int sg = 0; sg < SEG; ++sg) s += lds[w][l * kV + e][sg * P + pp];
+        partial[static_cast<int64_t>(blockIdx.x) * d + j] = s;
+    }
 }
 
 namespace {
@@ -208,6 +310,59 @@ hipError_t colsum_any(const void* X, float* partial, int64_t n_sub, int64_t d, b
     return hipGetLastError();
 }
 
+template <typename E, int P, int L, int U>
+hipError_t launch_compress_colsum_vec(const void* X, const float* v, void* S, float* partial, int64_t n_sub, int d,
+                                      int blocks, hipStream_t st) {
+    hipLaunchKernelGGL((compress_colsum_vec_kernel<E, P, L, U>), dim3(blocks), dim3(256), 0, st,
+                       static_cast<const uint4*>(X), v, static_cast<typename E::type*>(S), partial, n_sub, d);
+    return hipGetLastError();
+}
+
+template <typename E>
+hipError_t dispatch_compress_colsum(int vec_per_sub, const void* X, const float* v, void* S, float* partial,
+                                    int64_t n_sub, int d, int blocks, hipStream_t st) {
+    switch (vec_per_sub) {
+        case 1:   return launch_compress_colsum_vec<E, 1, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+        case 2:   return launch_compress_colsum_vec<E, 2, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+        case 4:   return launch_compress_colsum_vec<E, 4, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+        case 8:   return launch_compress_colsum_vec<E, 8, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+        case 16:  return launch_compress_colsum_vec<E, 16, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+        case 32:  return launch_compress_colsum_vec<E, 32, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+        case 64:  return launch_compress_colsum_vec<E, 64, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+        case 128: return launch_compress_colsum_vec<E, 64, 2, 4>(X, v, S, partial, n_sub, d, blocks, st);
+        default:  return launch_compress_colsum_vec<E, 64, 4, 2>(X, v, S, partial, n_sub, d, blocks, st);
+    }
+}
+
+struct WsView {
+    int* flag;
+    double* mean;
+    double* slices;
+    float* partial;
+};
+
+WsView ws_view(void* ws, const InitVPlan& plan) {
+    char* base = static_cast<char*>(ws);
+    WsView w;
+    w.flag = reinterpret_cast<int*>(base);
+    w.mean = reinterpret_cast<double*>(base + kFlagBytes);
+    w.slices = reinterpret_cast<double*>(base + plan.slices_off);
+    w.partial = reinterpret_cast<float*>(base + plan.partial_off);
+    return w;
+}
+
+hipError_t finish_v(const WsView& w, int blocks, int64_t n_sub, int64_t d, float* state, double beta, float* v,
+                    hipStream_t st) {
+    const int di = static_cast<int>(d);
+    hipLaunchKernelGGL(colsum_combine_kernel, dim3(static_cast<unsigned>(ceil_div(d, 32)), kSlices), dim3(256), 0, st,
+                       w.partial, w.slices, blocks, di);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(normalise_v_kernel, dim3(1), dim3(256), 0, st, w.slices, w.mean, state, beta, v, w.flag, di,
+                       1.0 / static_cast<double>(n_sub));
+    return hipGetLastError();
+}
+
 }  // namespace
 
 InitVPlan plan_init_v(int64_t n_sub, int64_t d, bool is_bf16, const LaunchCfg& cfg) {
@@ -220,27 +375,43 @@ InitVPlan plan_init_v(int64_t n_sub, int64_t d, bool is_bf16, const LaunchCfg& c
     if (blocks > ceil_div(work_items, 4)) blocks = ceil_div(work_items, 4);
     if (blocks < 1) blocks = 1;
     p.blocks = static_cast<int>(blocks);
-    p.partial_off = kFlagBytes + ceil_div(static_cast<int64_t>(d) * 8, 256) * 256;   // flag | mean[d] f64 | partial
-    p.ws_bytes = p.partial_off + static_cast<size_t>(blocks) * static_cast<size_t>(d) * sizeof(float);
+    // the fused compress + column-sum kernel runs compress's grid
+    int64_t fused = ceil_div(work_items, 4);
+    if (fused > cfg.max_blocks) fused = cfg.max_blocks;
+    if (fused < 1) fused = 1;
+    p.fused_blocks = static_cast<int>(fused);
+    const int64_t rows = blocks > fused ? blocks : fused;
+    // flag | mean[d] f64 | slices[kSlices][d] f64 | partial[rows][d] f32
+    p.slices_off = kFlagBytes + ceil_div(static_cast<int64_t>(d) * 8, 256) * 256;
+    p.partial_off = p.slices_off + ceil_div(static_cast<int64_t>(d) * 8 * kSlices, 256) * 256;
+    p.ws_bytes = p.partial_off + static_cast<size_t>(rows) * static_cast<size_t>(d) * sizeof(float);
     return p;
 }
 
-hipError_t launch_init_v(const void* X, float* v, int64_t n_sub, int64_t d, bool is_bf16, bool vec_ok,
-                         void* ws, const InitVPlan& plan, hipStream_t st) {
-    char* base = static_cast<char*>(ws);
-    int* flag = reinterpret_cast<int*>(base);
-    double* mean = reinterpret_cast<double*>(base + kFlagBytes);
-    float* partial = reinterpret_cast<float*>(base + plan.partial_off);
-    hipError_t e = is_bf16 ? colsum_any<Bf16Elem>(X, partial, n_sub, d, vec_ok, plan.blocks, st)
-                           : colsum_any<F32Elem>(X, partial, n_sub, d, vec_ok, plan.blocks, st);
+hipError_t launch_update_v(const void* X, float* state, double beta, float* v, int64_t n_sub, int64_t d,
+                           bool is_bf16, bool vec_ok, void* ws, const InitVPlan& plan, hipStream_t st) {
+    const WsView w = ws_view(ws, plan);
+    hipError_t e = is_bf16 ? colsum_any<Bf16Elem>(X, w.partial, n_sub, d, vec_ok, plan.blocks, st)
+                           : colsum_any<F32Elem>(X, w.partial, n_sub, d, vec_ok, plan.blocks, st);
     if (e != hipSuccess) return e;
+    return finish_v(w, plan.blocks, n_sub, d, state, beta, v, st);
+}
+
+bool fused_compress_update_ok(int64_t d, bool is_bf16, bool vec_ok) {
+    return vec_ok && vec_shape_ok(d, is_bf16 ? 8 : 4);
+}
+
+hipError_t launch_compress_update(const void* X, const float* v_in, void* S, float* state, double beta, float* v_out,
+                                  int64_t n_sub, int64_t d, bool is_bf16, void* ws, const InitVPlan& plan,
+                                  hipStream_t st) {
+    const WsView w = ws_view(ws, plan);
     const int di = static_cast<int>(d);
-    hipLaunchKernelGGL(colsum_combine_kernel, dim3(static_cast<unsigned>(ceil_div(d, 32))), dim3(256), 0, st,
-                       partial, mean, plan.blocks, di, 1.0 / static_cast<double>(n_sub));
-    e = hipGetLastError();
+    hipError_t e = is_bf16 ? dispatch_compress_colsum<Bf16Elem>(static_cast<int>(d / 8), X, v_in, S, w.partial, n_sub,
+                                                                di, plan.fused_blocks, st)
+                           : dispatch_compress_colsum<F32Elem>(static_cast<int>(d / 4), X, v_in, S, w.partial, n_sub,
+                                                               di, plan.fused_blocks, st);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(normalise_v_kernel, dim3(1), dim3(256), 0, st, mean, v, flag, di);
-    return hipGetLastError();
+    return finish_v(w, plan.fused_blocks, n_sub, d, state, beta, v_out, st);
 }
 
 }  // namespace velora

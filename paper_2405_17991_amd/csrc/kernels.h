@@ -20,15 +20,24 @@ hipError_t launch_reconstruct(const void* S, const float* v, void* Xhat, int64_t
                               bool vec_ok, const LaunchCfg& cfg, hipStream_t st);
 
 // ---- init_v.hip ----
-// Workspace layout: [int32 flag | pad to 256 B | float partial[blocks][d]].
+// Workspace layout: [int32 flag | pad to 256 B | mean[d] f64 | slices[8][d] f64 | float partial[rows][d]].
 struct InitVPlan {
-    int blocks;        // partial-sum blocks of the first kernel
-    size_t ws_bytes;   // total workspace
+    int blocks;         // partial-sum blocks of the stand-alone column-sum kernel
+    int fused_blocks;   // blocks of the fused compress + column-sum kernel
+    size_t ws_bytes;    // total workspace
+    size_t slices_off;
     size_t partial_off;
 };
 InitVPlan plan_init_v(int64_t n_sub, int64_t d, bool is_bf16, const LaunchCfg& cfg);
-hipError_t launch_init_v(const void* X, float* v, int64_t n_sub, int64_t d, bool is_bf16, bool vec_ok,
-                         void* ws, const InitVPlan& plan, hipStream_t st);
+// v = normalise(m), m = batch mean, or beta*state + (1-beta)*batch mean when state != nullptr (state <- m).
+// Leaves the status word (0 | 6) at the start of the workspace; does not synchronise.
+hipError_t launch_update_v(const void* X, float* state, double beta, float* v, int64_t n_sub, int64_t d,
+                           bool is_bf16, bool vec_ok, void* ws, const InitVPlan& plan, hipStream_t st);
+// One pass: S = compress(X, v_in) and the same update of (state, v_out) from this batch.
+bool fused_compress_update_ok(int64_t d, bool is_bf16, bool vec_ok);
+hipError_t launch_compress_update(const void* X, const float* v_in, void* S, float* state, double beta, float* v_out,
+                                  int64_t n_sub, int64_t d, bool is_bf16, void* ws, const InitVPlan& plan,
+                                  hipStream_t st);
 
 // ---- wgrad.hip ----
 // Workspace layout: float partial[splits][O][Mp] (Mp = M rounded up to 4),

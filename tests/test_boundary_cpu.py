@@ -27,7 +27,7 @@ def _declared_symbols():
 def test_header_symbols_are_exported(vl):
     names = _declared_symbols()
     assert {"velora_init_v", "velora_compress", "velora_reconstruct", "velora_weight_grad",
-            "velora_weight_grad_factor", "velora_expand_factor",
+            "velora_weight_grad_factor", "velora_expand_factor", "velora_update_v", "velora_compress_update",
             "velora_workspace_bytes", "velora_status_string", "velora_version"} <= set(names)
     lib = ctypes.CDLL(vl.lib_path())
     for n in names:
@@ -123,6 +123,24 @@ def test_factor_argument_errors(vl):
     assert e(P, P, 32, 16, 3, P, vl.F32, 0, None) == 2
     assert e(P, P, 32, 16, 4, P, 8, 0, None) == 3
     assert e(P, P, 32, 16, 4, P + 2, vl.F32, 0, None) == 4
+
+
+def test_update_v_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    need = vl.velora_workspace_bytes(vl.OP_INIT_V, 64, 16, 0, 4, vl.F32)
+    u = raw.velora_update_v
+    assert u(None, 64, 16, 4, vl.F32, None, 0.5, P, P, need, None) == 1
+    assert u(P, 64, 16, 4, vl.F32, None, 0.5, None, P, need, None) == 1
+    assert u(P, 64, 16, 4, vl.F32, None, 1.5, P, P, need, None) == 2      # beta outside [0, 1]
+    assert u(P, 64, 16, 4, vl.F32, None, -0.1, P, P, need, None) == 2
+    assert u(P, 64, 16, 3, vl.F32, None, 0.5, P, P, need, None) == 2
+    assert u(P, 64, 16, 4, vl.F32, P + 2, 0.5, P, P, need, None) == 4
+    assert u(P, 64, 16, 4, vl.F32, None, 0.5, P, P, need - 1, None) == 5
+    c = raw.velora_compress_update
+    assert c(P, None, 64, 16, 4, vl.F32, P, None, 0.5, P, P, need, None) == 1
+    assert c(P, P, 64, 16, 4, vl.F32, P, None, 0.5, None, P, need, None) == 1
+    assert c(P, P, 64, 16, 4, 2, P, None, 0.5, P, P, need, None) == 3
+    assert c(P, P, 64, 16, 4, vl.F32, P, None, 0.5, P, None, need, None) == 5
 
 
 def test_workspace_query(vl):

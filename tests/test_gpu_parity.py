@@ -155,6 +155,62 @@ def test_init_v_degenerate(vl):
     assert (v.cpu().numpy() == np.float32(1.0 / np.sqrt(32.0))).all()
 
 
+# ------------------------------------------------------------------ per-batch v
+@pytest.mark.parametrize("N,D,d,dtype", [
+    (4 * 197, 768, 64, wl.BF16), (600, 1024, 256, wl.BF16), (300, 2048, 1024, wl.BF16), (513, 96, 8, wl.F32),
+    (256, 64, 16, wl.F32), (100, 60, 12, wl.BF16), (77, 63, 7, wl.F32),
+])
+def test_update_v_and_fused_compress_update(vl, N, D, d, dtype):
+    torch = _torch()
+    M = D // d
+    beta = 0.75
+    batches = []
+    for i in range(3):
+        X32 = wl.random_tensor(N, D, wl.F32, seed=100 * i + d).astype(np.float32)
+        shift = np.tile(np.linspace(-1.0, 2.0, d, dtype=np.float32), M) * np.float32(1 + i)
+        batches.append(wl.to_storage(X32 + shift[None, :], dtype))
+    # --- velora_update_v chained over three batches against the oracle chain
+    state_ref = np.zeros(d, dtype=np.float32)
+    state = torch.zeros(d, dtype=torch.float32, device="cuda")
+    for X in batches:
+        v = vl.velora_update_v(to_dev(X, dtype), M, mean_state=state, beta=beta)
+        v_ref, state_ref, rc = oracle.update_v(X, M, state=state_ref, beta=beta)
+        assert rc == 0
+        assert np.linalg.norm(v.cpu().numpy().astype(np.float64) - v_ref) <= 1e-5
+        np.testing.assert_allclose(state.cpu().numpy(), state_ref, rtol=2e-6, atol=1e-6)
+    # instance-wise: no state
+    v_i = vl.velora_update_v(to_dev(batches[1], dtype), M)
+    v_i_ref, _, _ = oracle.init_v(batches[1], M)
+    assert np.linalg.norm(v_i.cpu().numpy().astype(np.float64) - v_i_ref) <= 1e-5
+    # --- one pass: compress with the vector of the batches before, update for the next
+    state_ref = np.zeros(d, dtype=np.float32)
+    state = torch.zeros(d, dtype=torch.float32, device="cuda")
+    v_cur_ref, _, _ = oracle.init_v(batches[0], M)                 # first batch: fixed-average start
+    v_cur = to_dev(v_cur_ref, wl.F32)
+    for X in batches:
+        Xd = to_dev(X, dtype)
+        S_plain = vl.velora_compress(Xd, v_cur, M)
+        S, v_next = vl.velora_compress_update(Xd, v_cur, M, mean_state=state, beta=beta)
+        assert torch.equal(S.view(torch.int16 if dtype == wl.BF16 else torch.int32),
+                           S_plain.view(torch.int16 if dtype == wl.BF16 else torch.int32))
+        S_exact, S_store = oracle.compress(X, v_cur.cpu().numpy(), M)
+        assert rel_fro(to_host_f64(S), S_exact) <= (TOL_F32 if dtype == wl.F32 else TOL_BF16_STORE)
+        v_next_ref, state_ref, _ = oracle.update_v(X, M, state=state_ref, beta=beta)
+        assert np.linalg.norm(v_next.cpu().numpy().astype(np.float64) - v_next_ref) <= 1e-5
+        v_cur = v_next
+
+
+def test_update_v_degenerate_status_word(vl):
+    torch = _torch()
+    X = torch.zeros((64, 128), dtype=torch.bfloat16, device="cuda")
+    need = vl.velora_workspace_bytes(vl.OP_INIT_V, 64, 128, 0, 4, vl.BF16)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    v = vl.velora_update_v(X, 4, ws=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 6
+    assert (v.cpu().numpy() == np.float32(1.0 / np.sqrt(32.0))).all()
+
+
 # ------------------------------------------------------------------ weight_grad
 WGRAD_CASES = [
     # (N, O, D, d, dtype)

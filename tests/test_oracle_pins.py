@@ -283,6 +283,55 @@ class TestInitV:
         assert rc == oracle.ERR_DEGENERATE and (v == np.float32(0.5)).all()
 
 
+# ------------------------------------------------------------------ per-batch v
+class TestUpdateV:
+    def test_reduces_to_init_v_without_state_or_with_beta_zero(self):
+        X = _rand((50, 96), 3) + np.float32(0.25)
+        v0, _, rc0 = oracle.init_v(X, 6)
+        v1, st1, rc1 = oracle.update_v(X, 6)
+        assert rc0 == rc1 == 0 and st1 is None and (v0 == v1).all()
+        state = _f32(np.linspace(-1, 1, 16))
+        v2, st2, _ = oracle.update_v(X, 6, state=state, beta=0.0)
+        assert (v2 == v0).all()
+        _, mean, _ = oracle.init_v(X, 6)
+        assert (st2 == mean.astype(np.float32)).all()
+
+    def test_beta_one_keeps_the_state(self):
+        X = _rand((20, 32), 4)
+        state = _f32([3.0, 0.0, -4.0, 0.0, 0.0, 0.0, 0.0, 0.0])
+        v, st, rc = oracle.update_v(X, 4, state=state, beta=1.0)
+        assert rc == 0 and (st == state).all()
+        np.testing.assert_allclose(v, state / 5.0, rtol=0, atol=1e-7)
+
+    def test_closed_form_on_constant_subtokens(self):
+        # every sub-token equals u, state w: m = beta*w + (1-beta)*u exactly (dyadic values)
+        u = np.array([1.0, -2.0, 0.5, 4.0])
+        w = np.array([-3.0, 2.0, 1.5, 0.0])
+        X = _f32(np.tile(u, (7, 3)))
+        for beta in (0.25, 0.5, 0.75):
+            v, st, rc = oracle.update_v(X, 3, state=_f32(w), beta=beta)
+            m = beta * w + (1 - beta) * u
+            assert (st == m.astype(np.float32)).all()
+            np.testing.assert_allclose(v, m / np.linalg.norm(m), rtol=0, atol=6e-8)
+
+    def test_chain_equals_exponential_average_of_batch_means(self):
+        d, M = 8, 4
+        batches = [_rand((30, d * M), 10 + i) + np.float32(i) for i in range(4)]
+        beta = 0.5
+        state = np.zeros(d, dtype=np.float32)
+        expect = np.zeros(d)
+        for X in batches:
+            v, state, _ = oracle.update_v(X, M, state=state, beta=beta)
+            mb = X.astype(np.float64).reshape(-1, d).mean(0)
+            expect = beta * expect + (1 - beta) * mb
+        np.testing.assert_allclose(state, expect, rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(v, expect / np.linalg.norm(expect), rtol=0, atol=2e-6)
+
+    def test_degenerate(self):
+        v, st, rc = oracle.update_v(np.zeros((4, 8), dtype=np.float32), 2, state=np.zeros(4, dtype=np.float32), beta=0.5)
+        assert rc == oracle.ERR_DEGENERATE and (v == np.float32(0.5)).all() and (st == 0).all()
+
+
 # ------------------------------------------------------------------ weight gradient
 class TestWeightGrad:
     @pytest.mark.parametrize("N,O,D,d,dtype", [
