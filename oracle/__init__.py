@@ -221,3 +221,37 @@ def linear(X: np.ndarray, W: np.ndarray, threads: int = 0) -> np.ndarray:
     Y = np.empty((N, O), dtype=np.float64)
     _load().velora_oracle_linear(_p(X), _p(W), _dt(X), N, D, O, _p(Y), threads or default_threads())
     return Y
+
+
+def adamw_step_factor(T: np.ndarray, v: np.ndarray, W: np.ndarray, exp_avg: np.ndarray, exp_avg_sq: np.ndarray,
+                      lr: float, beta1: float, beta2: float, eps: float, weight_decay: float, step: int,
+                      grad_scale: float = 1.0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """One AdamW step (the optimiser of the paper's training set-ups, Sec. 4;
+    decoupled weight decay, bias-corrected moments) on a weight whose gradient is
+    given in the factored form of Sec. 3.2's reconstruction,
+    dW[o, g*d + j] = grad_scale * T[o, g] * v[j].  Everything in float64:
+
+        W   <- W * (1 - lr * weight_decay)
+        m   <- beta1 * m + (1 - beta1) * dW
+        u   <- beta2 * u + (1 - beta2) * dW^2
+        W   <- W - lr / (1 - beta1^step) * m / (sqrt(u) / sqrt(1 - beta2^step) + eps)
+
+    W float64[O, D] (widen bf16 storage before calling), m = exp_avg, u = exp_avg_sq
+    float64[O, D], step >= 1.  -> (W_new, m_new, u_new), float64, inputs untouched.
+    """
+    T = np.asarray(T, dtype=np.float64)
+    vv = np.asarray(v, dtype=np.float64).reshape(1, -1)
+    W = np.asarray(W, dtype=np.float64)
+    m = np.asarray(exp_avg, dtype=np.float64)
+    u = np.asarray(exp_avg_sq, dtype=np.float64)
+    O, M = T.shape
+    d = vv.shape[1]
+    assert W.shape == (O, M * d) and m.shape == W.shape and u.shape == W.shape and step >= 1
+    dW = float(grad_scale) * np.kron(T, vv)           # [O, M*d], column g*d + j holds T[o, g] * v[j]
+    W1 = W * (1.0 - lr * weight_decay)
+    m1 = beta1 * m + (1.0 - beta1) * dW
+    u1 = beta2 * u + (1.0 - beta2) * dW * dW
+    bc1 = 1.0 - beta1 ** step
+    bc2 = 1.0 - beta2 ** step
+    W2 = W1 - (lr / bc1) * m1 / (np.sqrt(u1) / np.sqrt(bc2) + eps)
+    return W2, m1, u1

@@ -452,3 +452,85 @@ class TestLinear:
         W = _rand((7, 20), 2, dtype)
         Y = oracle.linear(X, W)
         np.testing.assert_allclose(Y, wl.to_f64(X, dtype) @ wl.to_f64(W, dtype).T, rtol=1e-13, atol=1e-15)
+
+
+# ------------------------------------------------------------------ AdamW on the factored gradient
+class TestAdamWFactor:
+    """The fused optimiser step of the factored gradient, pinned to the library
+    optimiser (torch.optim.AdamW on the CPU, float64, fed the expanded gradient)
+    and to closed forms."""
+
+    HYP = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=1e-2)
+
+    def _case(self, O=7, M=3, d=4, seed=0):
+        rng = np.random.default_rng(seed)
+        T = rng.standard_normal((O, M))
+        v = rng.standard_normal(d)
+        v /= np.linalg.norm(v)
+        W = rng.standard_normal((O, M * d)) * 0.1
+        return T, v, W
+
+    def test_matches_library_adamw_over_several_steps(self):
+        import torch
+        T0, v, W0 = self._case()
+        h = self.HYP
+        p = torch.nn.Parameter(torch.tensor(W0, dtype=torch.float64))
+        opt = torch.optim.AdamW([p], lr=h["lr"], betas=(h["beta1"], h["beta2"]), eps=h["eps"],
+                                weight_decay=h["weight_decay"])
+        W, m, u = W0, np.zeros_like(W0), np.zeros_like(W0)
+        for step in range(1, 6):
+            T = T0 * (1.0 + 0.3 * step) * (-1.0) ** step
+            # the library is fed the gradient in its plain definition (Algorithm 1 backward)
+            G = np.zeros_like(W0)
+            for o in range(T.shape[0]):
+                for g in range(T.shape[1]):
+                    for j in range(v.size):
+                        G[o, g * v.size + j] = 0.5 * T[o, g] * v[j]
+            p.grad = torch.tensor(G, dtype=torch.float64)
+            opt.step()
+            W, m, u = oracle.adamw_step_factor(T, v, W, m, u, step=step, grad_scale=0.5, **h)
+            np.testing.assert_allclose(W, p.detach().numpy(), rtol=1e-12, atol=1e-14)
+            st = opt.state[p]
+            np.testing.assert_allclose(m, st["exp_avg"].numpy(), rtol=1e-12, atol=1e-16)
+            np.testing.assert_allclose(u, st["exp_avg_sq"].numpy(), rtol=1e-12, atol=1e-18)
+
+    def test_first_step_moves_by_lr_times_sign(self):
+        # m = (1-b1) g, u = (1-b2) g^2 and both bias corrections cancel: step = lr * g / (|g| + eps)
+        T, v, W = self._case(seed=1)
+        z = np.zeros_like(W)
+        W1, m1, u1 = oracle.adamw_step_factor(T, v, W, z, z, lr=1e-2, beta1=0.9, beta2=0.99, eps=0.0,
+                                              weight_decay=0.0, step=1)
+        g = np.kron(T, v.reshape(1, -1))
+        np.testing.assert_allclose(W1, W - 1e-2 * np.sign(g), rtol=0, atol=1e-15)
+        np.testing.assert_allclose(m1, 0.1 * g, rtol=1e-13)
+        np.testing.assert_allclose(u1, 0.01 * g * g, rtol=1e-12)
+
+    def test_zero_gradient_leaves_only_decoupled_decay(self):
+        T, v, W = self._case(seed=2)
+        z = np.zeros_like(W)
+        W1, m1, u1 = oracle.adamw_step_factor(np.zeros_like(T), v, W, z, z, lr=0.1, beta1=0.9, beta2=0.999,
+                                              eps=1e-8, weight_decay=0.5, step=3)
+        np.testing.assert_allclose(W1, W * (1 - 0.05), rtol=1e-15)
+        assert not m1.any() and not u1.any()
+
+    def test_gradient_layout_is_group_major(self):
+        # a single non-zero T[o, g] with v = e_j touches exactly column g*d + j of row o
+        O, M, d = 3, 4, 5
+        T = np.zeros((O, M)); T[1, 2] = 2.0
+        v = np.zeros(d); v[3] = 1.0
+        z = np.zeros((O, M * d))
+        _, m1, _ = oracle.adamw_step_factor(T, v, z, z, z, lr=1e-3, beta1=0.5, beta2=0.5, eps=1e-8,
+                                            weight_decay=0.0, step=1)
+        expect = np.zeros((O, M * d)); expect[1, 2 * d + 3] = 1.0
+        assert (m1 == expect).all()
+
+    def test_agrees_with_weight_grad_of_the_same_inputs(self):
+        # the factor this step consumes is the one weight_grad_factored hands over
+        X = _rand((40, 24), 5); Gm = _rand((40, 6), 6, sigma=0.02)
+        v, _, _ = oracle.init_v(X, 3)
+        S, _ = oracle.compress(X, v, 3)
+        T, dW = oracle.weight_grad_factored(Gm, S.astype(np.float32), v, 24)
+        z = np.zeros((6, 24))
+        _, m1, _ = oracle.adamw_step_factor(T, v, z, z, z, lr=1e-3, beta1=0.0, beta2=0.5, eps=1e-8,
+                                            weight_decay=0.0, step=1)
+        np.testing.assert_allclose(m1, dW, rtol=1e-12, atol=1e-18)
