@@ -188,6 +188,28 @@ velora_status velora_weight_grad_factor(const void* G, const void* S, int64_t N,
 velora_status velora_expand_factor(const float* T, const float* v, int64_t O, int64_t D, int64_t M, void* dW,
                                    velora_dtype dw_dt, int accumulate, velora_stream stream);
 
+/*
+ * AdamW step taken straight from the factored gradient (the paper's training
+ * set-ups, Sec. 4, use AdamW; the gradient is Algorithm 1's grad_weight in the
+ * factored form above).  With g[o, g*d + j] = grad_scale * T[o, g] * v[j], in
+ * place and in float32:
+ *     W <- W * (1 - lr * weight_decay)
+ *     exp_avg    <- beta1 * exp_avg    + (1 - beta1) * g
+ *     exp_avg_sq <- beta2 * exp_avg_sq + (1 - beta2) * g^2
+ *     W <- W - lr / (1 - beta1^step) * exp_avg / (sqrt(exp_avg_sq) / sqrt(1 - beta2^step) + eps)
+ * (decoupled weight decay, bias-corrected moments; step counts from 1).  dW is
+ * never materialised: the call moves W and the two moments through HBM once.
+ *   T [O, M], v [d] device float32 (read only)
+ *   W [O, D] device, dtype w_dt (float32, or bfloat16 rounded RNE on store)
+ *   exp_avg, exp_avg_sq [O, D] device float32 (read and written)
+ * VELORA_ERR_SHAPE also for step < 1, a beta outside [0, 1), eps < 0 or a
+ * non-finite lr / weight_decay / grad_scale.  No workspace.
+ */
+velora_status velora_adamw_step_factor(const float* T, const float* v, int64_t O, int64_t D, int64_t M, void* W,
+                                       velora_dtype w_dt, float* exp_avg, float* exp_avg_sq, float lr, float beta1,
+                                       float beta2, float eps, float weight_decay, int64_t step, float grad_scale,
+                                       velora_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

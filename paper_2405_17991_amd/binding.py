@@ -30,7 +30,7 @@ STATUS = {
 EXPORTS = [
     "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
     "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_factor",
-    "velora_expand_factor", "velora_update_v", "velora_compress_update",
+    "velora_expand_factor", "velora_update_v", "velora_compress_update", "velora_adamw_step_factor",
 ]
 
 
@@ -70,6 +70,9 @@ def _load() -> ctypes.CDLL:
     L.velora_weight_grad_factor.restype = ci
     L.velora_expand_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp]
     L.velora_expand_factor.restype = ci
+    cf = ctypes.c_float
+    L.velora_adamw_step_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, cf, cf, cf, cf, cf, i64, cf, vp]
+    L.velora_adamw_step_factor.restype = ci
     cf = ctypes.c_float
     L.velora_update_v.argtypes = [vp, i64, i64, i64, ci, vp, cf, vp, vp, sz, vp]
     L.velora_update_v.restype = ci
@@ -273,6 +276,32 @@ def velora_expand_factor(T, v, D: int, dW=None, dw_dtype=None, accumulate: bool 
                                   1 if accumulate else 0, _stream())
     _raise(st, "velora_expand_factor")
     return dW
+
+
+def velora_adamw_step_factor(T, v, W, exp_avg, exp_avg_sq, *, lr: float, beta1: float = 0.9, beta2: float = 0.999,
+                             eps: float = 1e-8, weight_decay: float = 1e-2, step: int, grad_scale: float = 1.0):
+    """One in-place AdamW step on W[O, D] from the factored gradient grad_scale * T (x) v."""
+    torch = _torch()
+    _check(T, "T", 2)
+    _check(v, "v", 1)
+    _check(W, "W", 2)
+    _check(exp_avg, "exp_avg", 2)
+    _check(exp_avg_sq, "exp_avg_sq", 2)
+    O, M = T.shape
+    D = W.shape[1]
+    if T.dtype != torch.float32 or v.dtype != torch.float32:
+        raise TypeError("T and v must be float32")
+    if exp_avg.dtype != torch.float32 or exp_avg_sq.dtype != torch.float32:
+        raise TypeError("exp_avg and exp_avg_sq must be float32")
+    if W.shape[0] != O or tuple(exp_avg.shape) != tuple(W.shape) or tuple(exp_avg_sq.shape) != tuple(W.shape):
+        raise ValueError(f"W, exp_avg and exp_avg_sq must be [{O}, D]")
+    if M <= 0 or D % M or v.numel() != D // M:
+        raise ValueError("v must be [D / M]")
+    st = raw.velora_adamw_step_factor(T.data_ptr(), v.data_ptr(), O, D, M, W.data_ptr(), _dt(W), exp_avg.data_ptr(),
+                                      exp_avg_sq.data_ptr(), float(lr), float(beta1), float(beta2), float(eps),
+                                      float(weight_decay), int(step), float(grad_scale), _stream())
+    _raise(st, "velora_adamw_step_factor")
+    return W
 
 
 def velora_update_v(X, M: int, mean_state=None, beta: float = 0.0, v=None, ws=None):

@@ -8,6 +8,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <cmath>
+
 namespace {
 
 using velora::LaunchCfg;
@@ -238,6 +240,38 @@ velora_status velora_expand_factor(const float* T, const float* v, int64_t O, in
     if (ptr_align(T) < 4 || ptr_align(v) < 4 || ptr_align(dW) < elem_bytes(dw_dt)) return VELORA_ERR_ALIGN;
     return hip_status(velora::launch_expand_factor(T, v, ptr_align(v), dW, dw_dt == VELORA_BF16, ptr_align(dW),
                                                    accumulate != 0, O, D, M, static_cast<hipStream_t>(stream)));
+}
+
+velora_status velora_adamw_step_factor(const float* T, const float* v, int64_t O, int64_t D, int64_t M, void* W,
+                                       velora_dtype w_dt, float* exp_avg, float* exp_avg_sq, float lr, float beta1,
+                                       float beta2, float eps, float weight_decay, int64_t step, float grad_scale,
+                                       velora_stream stream) {
+    if (!T || !v || !W || !exp_avg || !exp_avg_sq) return VELORA_ERR_NULL;
+    if (!dtype_ok(w_dt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(O, D, M) || !size_ok(O, D)) return VELORA_ERR_SHAPE;
+    if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f) ||
+        !std::isfinite(lr) || !std::isfinite(weight_decay) || !std::isfinite(grad_scale))
+        return VELORA_ERR_SHAPE;
+    if (ptr_align(T) < 4 || ptr_align(v) < 4 || ptr_align(exp_avg) < 4 || ptr_align(exp_avg_sq) < 4 ||
+        ptr_align(W) < elem_bytes(w_dt))
+        return VELORA_ERR_ALIGN;
+    const int64_t d = D / M;
+    const bool vec_ok = d % 4 == 0 && ptr_align(v) >= 16 && ptr_align(exp_avg) >= 16 && ptr_align(exp_avg_sq) >= 16 &&
+                        ptr_align(W) >= (w_dt == VELORA_BF16 ? 8 : 16);
+    velora::AdamWScalars a;
+    const double bc1 = 1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(step));
+    const double bc2 = 1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(step));
+    a.decay = static_cast<float>(1.0 - static_cast<double>(lr) * static_cast<double>(weight_decay));
+    a.beta1 = beta1;
+    a.one_minus_beta1 = static_cast<float>(1.0 - static_cast<double>(beta1));
+    a.beta2 = beta2;
+    a.one_minus_beta2 = static_cast<float>(1.0 - static_cast<double>(beta2));
+    a.step_size = static_cast<float>(static_cast<double>(lr) / bc1);
+    a.inv_sqrt_bc2 = static_cast<float>(1.0 / std::sqrt(bc2));
+    a.eps = eps;
+    a.grad_scale = grad_scale;
+    return hip_status(velora::launch_adamw_factor(T, v, W, w_dt == VELORA_BF16, exp_avg, exp_avg_sq, O, D, M, vec_ok, a,
+                                                  static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

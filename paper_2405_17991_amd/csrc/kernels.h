@@ -64,4 +64,20 @@ hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t 
 hipError_t launch_expand_factor(const float* T, const float* v, int v_align, void* dW, bool dw_bf16, int dw_align,
                                 bool accumulate, int64_t O, int64_t D, int64_t M, hipStream_t st);
 
+// ---- adamw.hip ----
+// Scalars of one AdamW step, precomputed on the host in double precision.
+struct AdamWScalars {
+    float decay;            // 1 - lr * weight_decay
+    float beta1, one_minus_beta1;
+    float beta2, one_minus_beta2;
+    float step_size;        // lr / (1 - beta1^step)
+    float inv_sqrt_bc2;     // 1 / sqrt(1 - beta2^step)
+    float eps;
+    float grad_scale;
+};
+// W, exp_avg, exp_avg_sq [O, D] updated in place from the gradient grad_scale * T (x) v.
+// vec_ok: d % 4 == 0 and all five pointers 16-byte aligned (8 for a bf16 W).
+hipError_t launch_adamw_factor(const float* T, const float* v, void* W, bool w_bf16, float* exp_avg, float* exp_avg_sq,
+                               int64_t O, int64_t D, int64_t M, bool vec_ok, const AdamWScalars& a, hipStream_t st);
+
 }  // namespace velora

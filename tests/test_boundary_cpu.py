@@ -125,6 +125,24 @@ def test_factor_argument_errors(vl):
     assert e(P, P, 32, 16, 4, P + 2, vl.F32, 0, None) == 4
 
 
+def test_adamw_step_factor_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    a = raw.velora_adamw_step_factor
+    ok = (1e-3, 0.9, 0.999, 1e-8, 0.01, 1, 1.0, None)
+    assert a(None, P, 32, 16, 4, P, vl.F32, P, P, *ok) == 1
+    assert a(P, P, 32, 16, 4, P, vl.F32, None, P, *ok) == 1
+    assert a(P, P, 32, 16, 4, P, 5, P, P, *ok) == 3
+    assert a(P, P, 32, 16, 3, P, vl.F32, P, P, *ok) == 2                           # M does not divide D
+    assert a(P, P, 32, 16, 4, P, vl.F32, P, P, 1e-3, 0.9, 0.999, 1e-8, 0.01, 0, 1.0, None) == 2   # step < 1
+    assert a(P, P, 32, 16, 4, P, vl.F32, P, P, 1e-3, 1.0, 0.999, 1e-8, 0.01, 1, 1.0, None) == 2   # beta1 = 1
+    assert a(P, P, 32, 16, 4, P, vl.F32, P, P, 1e-3, 0.9, -0.1, 1e-8, 0.01, 1, 1.0, None) == 2    # beta2 < 0
+    assert a(P, P, 32, 16, 4, P, vl.F32, P, P, 1e-3, 0.9, 0.999, -1.0, 0.01, 1, 1.0, None) == 2   # eps < 0
+    assert a(P, P, 32, 16, 4, P, vl.F32, P, P, float("nan"), 0.9, 0.999, 1e-8, 0.01, 1, 1.0, None) == 2
+    assert a(P, P, 32, 16, 4, P + 2, vl.F32, P, P, *ok) == 4
+    assert a(P, P, 32, 16, 4, P + 1, vl.BF16, P, P, *ok) == 4
+    assert a(P, P, 32, 16, 4, P, vl.F32, P + 2, P, *ok) == 4
+
+
 def test_update_v_argument_errors(vl):
     from paper_2405_17991_amd.binding import raw
     need = vl.velora_workspace_bytes(vl.OP_INIT_V, 64, 16, 0, 4, vl.F32)
