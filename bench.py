@@ -124,6 +124,36 @@ def _time_steps(torch, ring, steps, warmup, with_events):
     return dt, c, w
 
 
+def _adamw_record(vl, torch, sh, v, dev, steps):
+    """The optimiser step fed by the factored gradient (not part of `value`): W
+    and both moments in float32 stream through HBM once, dW is never formed."""
+    sets = max(2, -(-RING_BYTES // (sh.O * sh.D * 12)))
+    W = [torch.randn((sh.O, sh.D), device=dev) * 0.05 for _ in range(sets)]
+    m = [torch.zeros((sh.O, sh.D), device=dev) for _ in range(sets)]
+    u = [torch.zeros((sh.O, sh.D), device=dev) for _ in range(sets)]
+    T = torch.randn((sh.O, sh.M), device=dev) * 0.02
+
+    def run(i):
+        r = i % sets
+        vl.velora_adamw_step_factor(T, v, W[r], m[r], u[r], lr=1e-3, step=1 + i // sets)
+
+    for i in range(3):
+        run(i)
+    n_batches = max(1, steps // EVENT_BATCH)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_batches)]
+    for b in range(n_batches):
+        ev[b][0].record()
+        for i in range(EVENT_BATCH):
+            run(3 + b * EVENT_BATCH + i)
+        ev[b][1].record()
+    torch.cuda.synchronize()
+    us = sum(e[0].elapsed_time(e[1]) for e in ev) / (n_batches * EVENT_BATCH) * 1e3
+    nbytes = sh.O * sh.D * 24 + sh.O * sh.M * 4 + sh.d * 4
+    return {"kernel": "adamw_factor_vec_kernel", "bound": "hbm", "avg_us": round(us, 2), "algorithmic_bytes": nbytes,
+            "achieved": round(nbytes / us * 1e-3, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(nbytes / us * 1e-3 / HBM_PEAK_GBPS, 4), "W_dtype": "f32", "ring_sets": sets}
+
+
 def _device_inputs(torch, sh, dev):
     """Synthetic layer inputs drawn on the device (sweep only: the kernels have
     no data-dependent control flow, so timing needs the shape and dtype, and
@@ -285,6 +315,8 @@ def main():
     }
     v_host = v.cpu().numpy()
     del ring, X0, G0
+    torch.cuda.empty_cache()
+    out["adamw_step_factor"] = _adamw_record(vl, torch, sh, v, dev, args.steps)
     torch.cuda.empty_cache()
 
     # ---------------- every layer shape of the five configurations
