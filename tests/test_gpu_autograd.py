@@ -82,3 +82,37 @@ def test_saved_activation_shrinks_by_d(mods):
     assert base == acc["baseline"] == N * D * 2
     assert ours == acc["velora"] == N * (D // d) * 2
     assert base // ours == d
+
+
+def test_device_memory_held_between_forward_and_backward(mods):
+    # the allocator's view of the same claim, at a LLaMA-7B-like layer width: after the forward,
+    # with the caller's own reference to the activation dropped, a plain linear keeps it alive
+    # (N*D*2 bytes) while the VeLoRA layer keeps only S (N*D/d*2 bytes, up to allocator rounding)
+    torch, va = mods
+    N, D, O, d = 4096, 4096, 1024, 256
+    layer = va.VeLoRALinear(D, O, d, device="cuda", dtype=torch.bfloat16)
+    layer.init_v(torch.randn(N, D, device="cuda", dtype=torch.bfloat16))
+
+    def held(fn):
+        # the layer input is a non-leaf activation (as inside a network): once the caller drops
+        # it, only what autograd saved keeps memory alive
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        leaf = torch.zeros(N, 1, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+        noise = torch.randn(N, D, device="cuda", dtype=torch.bfloat16)
+        base = torch.cuda.memory_allocated()
+        xin = noise + leaf                            # add saves nothing for its backward
+        y = fn(xin)
+        out_bytes = y.numel() * y.element_size()
+        del xin
+        torch.cuda.synchronize()
+        kept = torch.cuda.memory_allocated() - base - out_bytes
+        y.sum().backward()
+        assert leaf.grad is not None
+        return kept
+
+    plain = held(lambda t: torch.nn.functional.linear(t, layer.weight))
+    ours = held(lambda t: layer(t))
+    assert plain >= N * D * 2                        # the input itself is still held for backward
+    assert ours <= N * (D // d) * 2 + (2 << 20)      # only S (plus allocator block rounding)
+    assert plain - ours >= N * D * 2 - N * (D // d) * 2 - (2 << 20)
