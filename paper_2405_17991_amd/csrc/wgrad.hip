@@ -612,9 +612,10 @@ void tiles_for(int64_t M, int* gt, int64_t* chunks) {
     *chunks = ceil_div(need, 16);
 }
 
-// S operand: the [N, M] array itself (direct gather, at most two group tiles)
-// or the packed fragment array.
-bool direct_s(int gt) { return gt <= 2; }
+// S operand: the [N, M] array itself (direct gather, at most three group tiles:
+// beyond that the 8 two-byte loads per tile and step cost more registers and
+// issue slots than the packing pre-pass does time) or the packed fragment array.
+bool direct_s(int gt) { return gt <= 3; }
 
 MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan) {
     MfmaChoice ch{0, 0, 0};
@@ -668,11 +669,11 @@ hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_oper
                          int64_t O, int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
     *handled = true;
     VELORA_MFMA_CASE(8, 1, 3, true) VELORA_MFMA_CASE(8, 2, 3, true)
-    VELORA_MFMA_CASE(8, 3, 4, false) VELORA_MFMA_CASE(8, 4, 4, false)
+    VELORA_MFMA_CASE(8, 3, 4, true) VELORA_MFMA_CASE(8, 4, 4, false)
     VELORA_MFMA_CASE(8, 5, 3, false) VELORA_MFMA_CASE(8, 6, 3, false)
     VELORA_SHARED_G_CASE(8, 2, 8, 4) VELORA_SHARED_G_CASE(12, 3, 8, 4) VELORA_SHARED_G_CASE(16, 4, 8, 4)
     VELORA_MFMA_CASE(4, 1, 4, true) VELORA_MFMA_CASE(4, 2, 4, true)
-    VELORA_MFMA_CASE(4, 3, 4, false) VELORA_MFMA_CASE(4, 4, 4, false)
+    VELORA_MFMA_CASE(4, 3, 4, true) VELORA_MFMA_CASE(4, 4, 4, false)
     VELORA_MFMA_CASE(4, 5, 4, false) VELORA_MFMA_CASE(4, 6, 3, false)
     VELORA_MFMA_CASE(4, 8, 4, false) VELORA_MFMA_CASE(4, 12, 3, false)
     VELORA_MFMA_CASE(4, 16, 2, false)
