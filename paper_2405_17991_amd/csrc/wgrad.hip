@@ -302,8 +302,11 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
 // double-buffered LDS tile, and after one barrier every wave reads the whole
 // tile back in the lane layout of the in-register transpose.  G is thus read
 // once per block, S (packed fragments) once per 128 output features.  A wave
-// only carries 2 KB of G per step, so the G ring is deep (NG = 8: 64 KB of HBM
-// reads in flight per block); S comes from L2 and needs a shorter ring (NS).
+// only carries 2 KB of G per step, so the G ring is deep (NG = 8); S comes from
+// L2 and needs a shorter ring (NS).  What bounds this kernel is the number of
+// cache-line requests a CU can have outstanding below its L1 (about 64): per
+// step a block asks for 64 lines of G and 32 * GTW lines of S, so at 16 tiles
+// two thirds of the requests are S re-reads served by L2.
 // grid = (o tiles of 128, splits, g chunks of 64*GTW groups)
 // ---------------------------------------------------------------------------
 template <int GTW, int NG, int NS>
@@ -376,28 +379,46 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
     for (int s = 0; s < NG; ++s) load_g_step(gr[s], s);
 #pragma unroll
     for (int s = 0; s < NS; ++s) load_s_step(sr[s], s);
+    // Software pipeline: while the matrix pipe works on step t, the wave
+    // publishes its quarter of step t+1, reads the whole tile t+1 back and
+    // transposes it, so LDS latency and the v_perm work hide under the MFMAs.
+    // One barrier per step is enough with two LDS buffers: a wave writes
+    // buffer (t+1)&1 only after the barrier of step t-1, which every wave
+    // passes with its reads of tile t-1 already in registers.
+    auto publish = [&](const u32x4 (&src)[2], int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            gtile[buf][q * 8 + 2 * w + i][jj] = make_uint4(src[i].x, src[i].y, src[i].z, src[i].w);
+    };
+    auto read_tile = [&](RawRow<4> (&rowsv)[8], int buf) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint4 x = gtile[buf][q * 8 + r][jj];
+            rowsv[r].w[0] = x.x; rowsv[r].w[1] = x.y; rowsv[r].w[2] = x.z; rowsv[r].w[3] = x.w;
+        }
+    };
+    bf16x8 gf[CW];
+    {
+        publish(gr[0], 0);
+        load_g_step(gr[0], NG);
+        __syncthreads();
+        RawRow<4> rowsv[8];
+        read_tile(rowsv, 0);
+#pragma unroll
+        for (int c = 0; c < CW; ++c) gf[c] = column_fragment(rowsv, c);
+    }
     for (int base = 0; base < n_steps; base += NG) {
 #pragma unroll
         for (int s = 0; s < NG; ++s) {
             const int t = base + s;
-            const int buf = s & 1;                     // == t & 1 because NG is even
-            const int ss = s % NS;                     // == t % NS because NS divides NG
-            // publish this wave's quarter of the step's G tile, refill the ring slot
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                gtile[buf][q * 8 + 2 * w + i][jj] = make_uint4(gr[s][i].x, gr[s][i].y, gr[s][i].z, gr[s][i].w);
-            load_g_step(gr[s], t + NG);
+            const int sn = (s + 1) % NG;           // ring slot of step t+1
+            const int bufn = (s + 1) & 1;          // == (t+1) & 1 because NG is even
+            const int ss = s % NS;                 // == t % NS because NS divides NG
+            publish(gr[sn], bufn);
+            load_g_step(gr[sn], t + 1 + NG);
             __syncthreads();
-            // the whole tile, in the (8 rows x 8 features per lane) layout of the transpose
             RawRow<4> rowsv[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const uint4 x = gtile[buf][q * 8 + r][jj];
-                rowsv[r].w[0] = x.x; rowsv[r].w[1] = x.y; rowsv[r].w[2] = x.z; rowsv[r].w[3] = x.w;
-            }
-            bf16x8 gf[CW];
-#pragma unroll
-            for (int c = 0; c < CW; ++c) gf[c] = column_fragment(rowsv, c);
+            read_tile(rowsv, bufn);
 #pragma unroll
             for (int a = 0; a < GTW; ++a) {
                 const bf16x8 sf = __builtin_bit_cast(bf16x8, sr[ss][a]);
@@ -405,6 +426,8 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
                 for (int c = 0; c < CW; ++c)
                     acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
             }
+#pragma unroll
+            for (int c = 0; c < CW; ++c) gf[c] = column_fragment(rowsv, c);
             __builtin_amdgcn_sched_barrier(0);
             load_s_step(sr[ss], t + NS);
         }
