@@ -124,6 +124,48 @@ def _time_steps(torch, ring, steps, warmup, with_events):
     return dt, c, w
 
 
+def _event_avg_us(torch, fn, launches):
+    """Mean microseconds per launch of fn(i), EVENT_BATCH launches between two events."""
+    for i in range(3):
+        fn(i)
+    n_batches = max(1, launches // EVENT_BATCH)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_batches)]
+    for b in range(n_batches):
+        ev[b][0].record()
+        for i in range(EVENT_BATCH):
+            fn(3 + b * EVENT_BATCH + i)
+        ev[b][1].record()
+    torch.cuda.synchronize()
+    return sum(e[0].elapsed_time(e[1]) for e in ev) / (n_batches * EVENT_BATCH) * 1e3
+
+
+def _other_steps_record(vl, torch, sh, ring, launches):
+    """The remaining steps of the path, each on its own: init_v (one-off per
+    layer), the per-batch-v variants, and the materialising reconstruct."""
+    R = ring.R
+    eb = sh.elem_bytes
+    x_bytes = sh.N * sh.D * eb
+    s_bytes = sh.N * sh.M * eb
+    need = vl.velora_workspace_bytes(vl.OP_INIT_V, sh.N, sh.D, 0, sh.M, vl.BF16 if sh.dtype == "bf16" else vl.F32)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=ring.X[0].device)
+    vbuf = torch.empty(sh.d, dtype=torch.float32, device=ring.X[0].device)
+    state = torch.zeros(sh.d, dtype=torch.float32, device=ring.X[0].device)
+    out = {}
+    t = _event_avg_us(torch, lambda i: vl.velora_update_v(ring.X[i % R], sh.M, v=vbuf, ws=ws), launches)
+    out["init_v"] = {"avg_us": round(t, 2), "algorithmic_bytes": x_bytes,
+                     "frac": round(x_bytes / t * 1e-3 / HBM_PEAK_GBPS, 4),
+                     "note": "velora_update_v without a state: the same kernels as velora_init_v, minus its final synchronise"}
+    t = _event_avg_us(torch, lambda i: vl.velora_compress_update(ring.X[i % R], ring.v, sh.M, mean_state=state, beta=0.9,
+                                                                 S=ring.S[i % R], v_out=vbuf, ws=ws), launches)
+    out["compress_update"] = {"avg_us": round(t, 2), "algorithmic_bytes": x_bytes + s_bytes,
+                              "frac": round((x_bytes + s_bytes) / t * 1e-3 / HBM_PEAK_GBPS, 4)}
+    Xhat = torch.empty_like(ring.X[0])
+    t = _event_avg_us(torch, lambda i: vl.velora_reconstruct(ring.S[i % R], ring.v, sh.D, Xhat=Xhat), launches)
+    out["reconstruct"] = {"avg_us": round(t, 2), "algorithmic_bytes": x_bytes + s_bytes,
+                          "frac": round((x_bytes + s_bytes) / t * 1e-3 / HBM_PEAK_GBPS, 4)}
+    return out
+
+
 def _adamw_record(vl, torch, sh, v, dev, steps):
     """The optimiser step fed by the factored gradient (not part of `value`): W
     and both moments in float32 stream through HBM once, dW is never formed."""
@@ -314,6 +356,7 @@ def main():
                         "workspace_MB": round(ring.ws_bytes / 1e6, 2)},
     }
     v_host = v.cpu().numpy()
+    out["other_steps"] = _other_steps_record(vl, torch, sh, ring, args.steps)
     del ring, X0, G0
     torch.cuda.empty_cache()
     out["adamw_step_factor"] = _adamw_record(vl, torch, sh, v, dev, args.steps)

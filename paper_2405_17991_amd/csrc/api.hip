@@ -187,7 +187,7 @@ velora_status velora_reconstruct(const void* S, const float* v, int64_t N, int64
     const int eb = elem_bytes(dt);
     if (ptr_align(S) < eb || ptr_align(Xhat) < eb || ptr_align(v) < 4) return VELORA_ERR_ALIGN;
     const LaunchCfg cfg = current_cfg();
-    const bool vec_ok = ptr_align(Xhat) >= 16;
+    const bool vec_ok = ptr_align(Xhat) >= 16 && ptr_align(v) >= 16;
     return hip_status(velora::launch_reconstruct(S, v, Xhat, N * M, D / M, dt == VELORA_BF16, vec_ok, cfg,
                                                  static_cast<hipStream_t>(stream)));
 }

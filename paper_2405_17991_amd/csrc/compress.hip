@@ -106,31 +106,68 @@ __global__ __launch_bounds__(256) void compress_generic_kernel(const typename E:
 }
 
 // ---------------------------------------------------------------------------
-// reconstruct + ungroup: every lane writes one 16-byte vector of Xhat.
+// reconstruct + ungroup (Sec. 3.2): Xhat[k*d + j] = S[k] * v[j].  Write-bound.
+// The grid's thread count is a multiple of the 16-byte vectors per sub-token
+// (vps, host-checked), so a thread keeps the same position j inside the
+// sub-token for the whole grid-stride loop: its slice of v lives in registers
+// and the loop body is one 2/4-byte load of S, kV multiplies and one streaming
+// 16-byte store; consecutive threads write consecutive vectors.
 // ---------------------------------------------------------------------------
-template <typename E>
+typedef uint32_t u32x4_store __attribute__((ext_vector_type(4)));
+
+template <typename E, int kUnroll>
 __global__ __launch_bounds__(256) void reconstruct_vec_kernel(const typename E::type* __restrict__ S,
                                                              const float* __restrict__ v,
                                                              uint4* __restrict__ Xhat,
-                                                             int64_t n_vec, int d) {
+                                                             int64_t n_sub, int vps) {
     constexpr int kV = E::kPerVec;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
-        const int64_t e0 = i * kV;
-        const int64_t k = e0 / d;
-        const int j0 = static_cast<int>(e0 - k * d);
-        const float s = E::load(S, k);
-        float f[kV];
+    const int64_t n_threads = static_cast<int64_t>(gridDim.x) * blockDim.x;     // a multiple of vps
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t k_step = n_threads / vps;
+    const int64_t k_base = t / vps;
+    const int jv = static_cast<int>(t - k_base * vps);
+    // Sub-tokens of one trip: kUnroll per thread.  When a wave spans whole
+    // sub-tokens (vps divides 64) they are chosen so that the wave's kUnroll
+    // stores form one contiguous run of Xhat; otherwise they are k_step apart.
+    int64_t k, u_stride;
+    if (kWave % vps == 0) {
+        const int wsub = kWave / vps;
+        k = (k_base / wsub) * (static_cast<int64_t>(wsub) * kUnroll) + k_base % wsub;
+        u_stride = wsub;
+    } else {
+        k = k_base;
+        u_stride = k_step;
+    }
+    float vf[kV];
 #pragma unroll
-        for (int e = 0; e < kV; ++e) f[e] = s * v[j0 + e];
-        uint4 out;
-        if constexpr (kV == 4) {
-            out = make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
-        } else {
-            out = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
-                             pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+    for (int e = 0; e < kV; e += 4) {
+        const float4 q = *reinterpret_cast<const float4*>(v + jv * kV + e);
+        vf[e] = q.x; vf[e + 1] = q.y; vf[e + 2] = q.z; vf[e + 3] = q.w;
+    }
+    for (; k < n_sub; k += kUnroll * k_step) {
+        float sv[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t kk = k + u * u_stride;
+            sv[u] = kk < n_sub ? E::load(S, kk) : 0.f;
         }
-        Xhat[i] = out;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t kk = k + u * u_stride;
+            if (kk >= n_sub) continue;
+            float f[kV];
+#pragma unroll
+            for (int e = 0; e < kV; ++e) f[e] = sv[u] * vf[e];
+            u32x4_store out;
+            if constexpr (kV == 4) {
+                out = u32x4_store{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                                  __float_as_uint(f[3])};
+            } else {
+                out = u32x4_store{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                                  pack_bf16x2(f[6], f[7])};
+            }
+            __builtin_nontemporal_store(out, reinterpret_cast<u32x4_store*>(Xhat + kk * vps + jv));
+        }
     }
 }
 
@@ -211,12 +248,20 @@ template <typename E>
 hipError_t reconstruct_any(const void* S, const float* v, void* Xhat, int64_t n_sub, int64_t d, bool vec_ok,
                            const LaunchCfg& cfg, hipStream_t st) {
     const int64_t n_elem = n_sub * d;
+    // the streaming kernel wants (grid * 256) % vps == 0: grid a multiple of vps / gcd(vps, 256)
+    int64_t vps = d / E::kPerVec, grid_quantum = 0;
     if (vec_ok && d % E::kPerVec == 0) {
+        int64_t g = vps, h = kBlock;
+        while (h) { const int64_t r = g % h; g = h; h = r; }
+        grid_quantum = vps / g;
+    }
+    if (grid_quantum > 0 && grid_quantum <= 64) {
         const int64_t n_vec = n_elem / E::kPerVec;
-        const int grid = grid_for(ceil_div(n_vec, kBlock), 1, cfg.max_blocks * 4);
-        hipLaunchKernelGGL((reconstruct_vec_kernel<E>), dim3(grid), dim3(kBlock), 0, st,
-                           static_cast<const typename E::type*>(S), v, static_cast<uint4*>(Xhat), n_vec,
-                           static_cast<int>(d));
+        int64_t grid = grid_for(ceil_div(n_vec, kBlock * 4), 1, cfg.max_blocks);
+        grid = ceil_div(grid, grid_quantum) * grid_quantum;
+        hipLaunchKernelGGL((reconstruct_vec_kernel<E, 4>), dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
+                           static_cast<const typename E::type*>(S), v, static_cast<uint4*>(Xhat), n_sub,
+                           static_cast<int>(vps));
     } else {
         const int grid = grid_for(ceil_div(n_elem, kBlock), 1, cfg.max_blocks * 4);
         hipLaunchKernelGGL((reconstruct_generic_kernel<E>), dim3(grid), dim3(kBlock), 0, st,

@@ -41,8 +41,8 @@ hipError_t launch_compress_update(const void* X, const float* v_in, void* S, flo
 
 // ---- wgrad.hip ----
 // Workspace layout: float partial[splits][O][Mp] (Mp = M rounded up to 4),
-// then, for bf16 inputs, S re-laid out as MFMA fragments
-// (ceil(N/32) steps x tiles_packed tiles x 1 KiB).
+// then, for bf16 inputs with more than three 16-group tiles (M > 48), S re-laid
+// out as MFMA fragments (ceil(N/32) steps x tiles_packed tiles x 1 KiB).
 struct WgradPlan {
     int splits;        // number of token ranges (split-K)
     int64_t rows_per_split;

@@ -43,13 +43,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // future steps can be kept in flight in a register ring (NST stages), which is
 // what a bandwidth-bound kernel needs.
 //
-// S (small, re-read by every column tile): a tiny pre-pass re-lays it out as
-// ready-made A fragments (pack kernel below), so the main loop fetches one
-// 16-byte fragment per lane and 16-group tile with no transposition at all.
+// S (small, re-read by every column tile).  Up to three group tiles (DIRECT):
+// lane (jj, q) gathers its eight values S[8q + e][16*tile + jj] with 2-byte
+// loads and pairs them up in registers.  More tiles: a tiny pre-pass re-lays S
+// out as ready-made A fragments (pack kernel below), so the main loop fetches
+// one 16-byte fragment per lane and 16-group tile with no transposition at all.
 //
 //   CW   G columns per lane (8 -> 16-byte loads, 4 -> 8-byte)
 //   GT   16-group tiles per block (the block covers 16*GT groups g)
 //   NST  ring depth: 32-token steps in flight per wave
+//   DIRECT  S operand is S[N, M] itself rather than the packed fragments
 // Block = 4 waves; the waves take alternate 32-token steps of the block's token
 // range and are summed through LDS at the end in a fixed order.
 // grid = (o tiles of 16*CW, splits, g chunks of 16*GT)
