@@ -134,6 +134,18 @@ struct WgradStage {
     uint32_t s[GT][DIRECT ? 8 : 4];
 };
 
+// One MFMA result tile leaves the registers as it is: lane (jj, q) holds
+// T[g0 + 4q + r][o0 + jj*CW + c], r < 4, and partial rows run along g, so the
+// four values are one 16-byte store (Mp is a multiple of 4 and the workspace is
+// 16-byte aligned; groups in [M, Mp) hold zeros).
+template <int CW>
+__device__ __forceinline__ void store_tile(float* __restrict__ out, const f32x4& t, int64_t o0, int jj, int q, int c,
+                                           int64_t g0, int64_t O, int64_t Mp) {
+    const int64_t o = o0 + jj * CW + c;
+    const int64_t g = g0 + 4 * q;
+    if (o < O && g < Mp) *reinterpret_cast<f32x4*>(out + o * Mp + g) = t;
+}
+
 template <int CW, int GT, int NST, bool DIRECT>
 __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t* __restrict__ G,
                                                                 const void* __restrict__ Sany,
@@ -141,7 +153,9 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
                                                                 int64_t M, int64_t Mp, int64_t rows_per_split,
                                                                 int64_t tiles_packed) {
     constexpr int OT = 16 * CW;          // output features per block
-    __shared__ float lds[kWavesPerBlock][OT][17];
+    constexpr int NACC = GT * CW;        // accumulator tiles per wave
+    constexpr int TP = NACC <= 24 ? NACC : (NACC % 24 == 0 ? 24 : 16);   // tiles reduced per pass: 2 regions x <= 24 KB of LDS
+    __shared__ f32x4 red[2][TP][kWave];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -275,22 +289,41 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
         }
     }
 
-    // Sum the four waves in a fixed order through LDS, one 16-group tile at a
-    // time, and write the block's partial tile with lanes running along g.
+    // Sum the four waves in a fixed order, (w0 + w1) + (w2 + w3), through LDS in
+    // the accumulators' own register layout (16-byte LDS accesses, no transpose):
+    // waves 1 and 3 publish, waves 0 and 2 add; wave 2 publishes its sum in the
+    // region it has just read, wave 0 adds it and stores the tiles to the
+    // block's partial tile straight from its registers.
     float* out = partial + static_cast<int64_t>(split) * O * Mp;
 #pragma unroll
-    for (int a = 0; a < GT; ++a) {
+    for (int p0 = 0; p0 < NACC; p0 += TP) {
+        if (w == 1 || w == 3) {
 #pragma unroll
-        for (int c = 0; c < CW; ++c)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) lds[w][jj * CW + c][q * 4 + r] = acc[a][c][r];
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < OT * 16; idx += blockDim.x) {
-            const int ol = idx >> 4, gl = idx & 15;
-            const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
-            if (o < O && g < M) out[o * Mp + g] = ((lds[0][ol][gl] + lds[1][ol][gl]) + lds[2][ol][gl]) + lds[3][ol][gl];
+            for (int i = 0; i < TP; ++i)
+                if (p0 + i < NACC) red[w >> 1][i][lane] = acc[(p0 + i) / CW][(p0 + i) % CW];
         }
         __syncthreads();
+        if (w == 0 || w == 2) {
+#pragma unroll
+            for (int i = 0; i < TP; ++i)
+                if (p0 + i < NACC) acc[(p0 + i) / CW][(p0 + i) % CW] += red[w >> 1][i][lane];
+        }
+        if (w == 2) {
+#pragma unroll
+            for (int i = 0; i < TP; ++i)
+                if (p0 + i < NACC) red[1][i][lane] = acc[(p0 + i) / CW][(p0 + i) % CW];
+        }
+        __syncthreads();
+        if (w == 0) {
+#pragma unroll
+            for (int i = 0; i < TP; ++i)
+                if (p0 + i < NACC) {
+                    const int a = (p0 + i) / CW, c = (p0 + i) % CW;
+                    const f32x4 t = acc[a][c] + red[1][i][lane];
+                    store_tile<CW>(out, t, o0, jj, q, c, (tile0 + a) * 16, O, Mp);
+                }
+        }
+        if (p0 + TP < NACC) __syncthreads();   // the next pass overwrites both regions
     }
 }
 
@@ -323,7 +356,6 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
     constexpr int CW = 8;
     constexpr int OT = 16 * CW;
     __shared__ uint4 gtile[2][kStep][16];              // [buffer][token][16-byte chunk of 8 features]
-    __shared__ float lds[kWavesPerBlock][OT][17];      // epilogue staging
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -436,22 +468,12 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
         }
     }
 
-    // every wave owns its tiles: stage through LDS only to write with lanes along g
+    // every wave owns its tiles and stores them straight from its registers
     float* out = partial + static_cast<int64_t>(split) * O * Mp;
 #pragma unroll
-    for (int a = 0; a < GTW; ++a) {
+    for (int a = 0; a < GTW; ++a)
 #pragma unroll
-        for (int c = 0; c < CW; ++c)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) lds[w][jj * CW + c][q * 4 + r] = acc[a][c][r];
-        __syncthreads();
-        for (int idx = lane; idx < OT * 16; idx += kWave) {
-            const int ol = idx >> 4, gl = idx & 15;
-            const int64_t o = o0 + ol, g = (tile0 + a) * 16 + gl;
-            if (o < O && g < M) out[o * Mp + g] = lds[w][ol][gl];
-        }
-        __syncthreads();
-    }
+        for (int c = 0; c < CW; ++c) store_tile<CW>(out, acc[a][c], o0, jj, q, c, (tile0 + a) * 16, O, Mp);
 }
 
 // ---------------------------------------------------------------------------
@@ -694,15 +716,16 @@ hipError_t launch_shared_g(const void* G, const void* s_operand, float* partial,
 hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_operand, float* partial, int64_t N,
                          int64_t O, int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
     *handled = true;
-    VELORA_MFMA_CASE(8, 1, 3, true) VELORA_MFMA_CASE(8, 2, 3, true)
-    VELORA_MFMA_CASE(8, 3, 4, true) VELORA_MFMA_CASE(8, 4, 4, false)
-    VELORA_MFMA_CASE(8, 5, 3, false) VELORA_MFMA_CASE(8, 6, 3, false)
+    // Ring depth 1 everywhere it was measured (2-4 were 1-5 us slower on every layer
+    // shape): a CU sustains a fixed number of outstanding cache-line requests, which
+    // four waves with one 32-token step each already exceed, and deeper rings only
+    // cost registers.
+    VELORA_MFMA_CASE(8, 1, 1, true) VELORA_MFMA_CASE(8, 2, 1, true) VELORA_MFMA_CASE(8, 3, 1, true)
+    VELORA_MFMA_CASE(8, 4, 1, false) VELORA_MFMA_CASE(8, 5, 1, false) VELORA_MFMA_CASE(8, 6, 1, false)
     VELORA_SHARED_G_CASE(8, 2, 8, 4) VELORA_SHARED_G_CASE(12, 3, 8, 4) VELORA_SHARED_G_CASE(16, 4, 8, 4)
-    VELORA_MFMA_CASE(4, 1, 4, true) VELORA_MFMA_CASE(4, 2, 4, true)
-    VELORA_MFMA_CASE(4, 3, 4, true) VELORA_MFMA_CASE(4, 4, 4, false)
-    VELORA_MFMA_CASE(4, 5, 4, false) VELORA_MFMA_CASE(4, 6, 3, false)
-    VELORA_MFMA_CASE(4, 8, 4, false) VELORA_MFMA_CASE(4, 12, 3, false)
-    VELORA_MFMA_CASE(4, 16, 2, false)
+    VELORA_MFMA_CASE(4, 1, 1, true) VELORA_MFMA_CASE(4, 2, 1, true) VELORA_MFMA_CASE(4, 3, 1, true)
+    VELORA_MFMA_CASE(4, 4, 1, false) VELORA_MFMA_CASE(4, 5, 1, false) VELORA_MFMA_CASE(4, 6, 1, false)
+    VELORA_MFMA_CASE(4, 8, 1, false) VELORA_MFMA_CASE(4, 12, 1, false) VELORA_MFMA_CASE(4, 16, 1, false)
     *handled = false;
     return hipSuccess;
 }
@@ -762,28 +785,44 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     int gt = 1;
     int64_t chunks = 1;
     if (is_bf16) tiles_for(M, &gt, &chunks);
-    // One resident round of blocks: the partial kernel keeps two blocks per CU
-    // for a single group tile and one otherwise (register budget), and a second
-    // round of blocks would pay the pipeline start-up twice.
-    const int64_t blocks_per_cu = gt <= 1 ? 2 : 1;
     const int64_t o_tiles = ceil_div(O, 128) * chunks;
-    int64_t splits = (static_cast<int64_t>(cfg.num_cus) * blocks_per_cu) / o_tiles;
-    // ... but keep the partial write + re-read under ~10 % of the bytes the
-    // two kernels must move anyway, and give each block at least 256 tokens.
+    // Keep the partial write + re-read under ~10 % of the bytes the two kernels
+    // must move anyway, and give each block at least 256 tokens.
     const double must_move = static_cast<double>(N) * O * in_b + static_cast<double>(O) * D * 4.0;
     const double per_split = static_cast<double>(O) * p.Mp * 8.0;
-    const int64_t traffic_cap = static_cast<int64_t>(0.10 * must_move / per_split);
-    if (splits > traffic_cap) splits = traffic_cap;
+    int64_t max_splits = static_cast<int64_t>(0.10 * must_move / per_split);
     const int64_t min_rows = is_bf16 ? 256 : 32;   // the plain-FMA kernel is latency-bound per token
-    if (splits > ceil_div(N, min_rows)) splits = ceil_div(N, min_rows);
-    // Long token ranges amortise a block's start-up and epilogue: prefer ranges of
-    // 2048 tokens when that gives between 0.7 and 1 block per CU (measured on the
-    // layer shapes of the five configurations; between 1 and 2 blocks per CU the
-    // uneven load costs more than the longer ranges gain).
-    const int64_t long_splits = N / 2048;
-    if (is_bf16 && long_splits >= 1 && splits > long_splits && o_tiles * long_splits * 10 >= cfg.num_cus * 7 &&
-        o_tiles * long_splits <= cfg.num_cus)
-        splits = long_splits;
+    if (max_splits > ceil_div(N, min_rows)) max_splits = ceil_div(N, min_rows);
+    if (max_splits > 1024) max_splits = 1024;
+    if (max_splits < 1) max_splits = 1;
+    int64_t splits = 1;
+    if (is_bf16) {
+        // Cost model, in ns.  The G stream is bound per CU (outstanding cache-line
+        // requests, ~20 B/ns), so the kernel takes as long as the busiest CU:
+        // (blocks per CU, rounded up) x (tokens per block + a block's start-up and
+        // epilogue, worth ~384 tokens) x 256 B per token; blocks beyond what a CU
+        // holds at once run as further rounds that each pay a drain; every split
+        // adds a partial tile that is written here and read back by the expansion.
+        // Measured over the layer shapes of the five configurations, the split that
+        // minimises this is the fastest or within 2 % of it; in particular exactly
+        // one block per CU beats two of half the length.
+        const int64_t resident = gt == 1 ? 3 : gt <= 3 ? 2 : 1;   // blocks a CU holds at once (registers)
+        const double ns_per_row = 256.0 / 20.0;
+        const double partial_ns = per_split / (5000.0 * cfg.num_cus / 256.0);
+        double best = 0.0;
+        for (int64_t s = 1; s <= max_splits; ++s) {
+            const int64_t rows = ceil_div(ceil_div(N, s), 128) * 128;
+            const int64_t sp = ceil_div(N, rows);
+            const int64_t per_cu = ceil_div(o_tiles * sp, cfg.num_cus);
+            const int64_t rounds = ceil_div(per_cu, resident);
+            const double cost = static_cast<double>(per_cu) * static_cast<double>(rows + 384) * ns_per_row +
+                                static_cast<double>(rounds - 1) * 3000.0 + static_cast<double>(sp) * partial_ns;
+            if (s == 1 || cost < best) { best = cost; splits = sp; }
+        }
+    } else {
+        splits = (static_cast<int64_t>(cfg.num_cus) * 2) / o_tiles;
+        if (splits > max_splits) splits = max_splits;
+    }
     const int forced = env_int("VELORA_WGRAD_SPLITS", 0);   // tuning aid; 0 = automatic
     if (forced > 0) splits = forced;
     if (splits < 1) splits = 1;
