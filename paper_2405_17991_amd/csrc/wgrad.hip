@@ -786,11 +786,11 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     int64_t chunks = 1;
     if (is_bf16) tiles_for(M, &gt, &chunks);
     const int64_t o_tiles = ceil_div(O, 128) * chunks;
-    // Keep the partial write + re-read under ~10 % of the bytes the two kernels
+    // Keep the partial write + re-read under ~15 % of the bytes the two kernels
     // must move anyway, and give each block at least 256 tokens.
     const double must_move = static_cast<double>(N) * O * in_b + static_cast<double>(O) * D * 4.0;
     const double per_split = static_cast<double>(O) * p.Mp * 8.0;
-    int64_t max_splits = static_cast<int64_t>(0.10 * must_move / per_split);
+    int64_t max_splits = static_cast<int64_t>(0.15 * must_move / per_split);
     const int64_t min_rows = is_bf16 ? 256 : 32;   // the plain-FMA kernel is latency-bound per token
     if (max_splits > ceil_div(N, min_rows)) max_splits = ceil_div(N, min_rows);
     if (max_splits > 1024) max_splits = 1024;
