@@ -120,8 +120,18 @@ __global__ __launch_bounds__(256) void colsum_combine_kernel(const float* __rest
     int b1 = b0 + per_slice;
     if (b1 > blocks) b1 = blocks;
     double s = 0.0;
-    if (j < d)
-        for (int b = b0 + r; b < b1; b += 8) s += static_cast<double>(partial[static_cast<int64_t>(b) * d + j]);
+    if (j < d) {
+        // eight loads in flight per thread; the additions keep their order
+        int b = b0 + r;
+        for (; b + 56 < b1; b += 64) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = partial[static_cast<int64_t>(b + 8 * u) * d + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += static_cast<double>(t[u]);
+        }
+        for (; b < b1; b += 8) s += static_cast<double>(partial[static_cast<int64_t>(b) * d + j]);
+    }
     red[r][c] = s;
     __syncthreads();
     if (r == 0 && j < d) {
