@@ -786,13 +786,10 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     int64_t chunks = 1;
     if (is_bf16) tiles_for(M, &gt, &chunks);
     const int64_t o_tiles = ceil_div(O, 128) * chunks;
-    // Keep the partial write + re-read under ~15 % of the bytes the two kernels
-    // must move anyway, and give each block at least 256 tokens.
-    const double must_move = static_cast<double>(N) * O * in_b + static_cast<double>(O) * D * 4.0;
+    // Each split writes a partial tile that the second kernel reads back.
     const double per_split = static_cast<double>(O) * p.Mp * 8.0;
-    int64_t max_splits = static_cast<int64_t>(0.15 * must_move / per_split);
     const int64_t min_rows = is_bf16 ? 256 : 32;   // the plain-FMA kernel is latency-bound per token
-    if (max_splits > ceil_div(N, min_rows)) max_splits = ceil_div(N, min_rows);
+    int64_t max_splits = ceil_div(N, min_rows);
     if (max_splits > 1024) max_splits = 1024;
     if (max_splits < 1) max_splits = 1;
     int64_t splits = 1;
@@ -820,7 +817,11 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
             if (s == 1 || cost < best) { best = cost; splits = sp; }
         }
     } else {
+        // plain-FMA kernel: two blocks per CU, partial traffic under ~15 % of what the call must move
+        const double must_move = static_cast<double>(N) * O * in_b + static_cast<double>(O) * D * 4.0;
+        const int64_t traffic_cap = static_cast<int64_t>(0.15 * must_move / per_split);
         splits = (static_cast<int64_t>(cfg.num_cus) * 2) / o_tiles;
+        if (splits > traffic_cap) splits = traffic_cap;
         if (splits > max_splits) splits = max_splits;
     }
     const int forced = env_int("VELORA_WGRAD_SPLITS", 0);   // tuning aid; 0 = automatic
@@ -898,8 +899,17 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
     if (i >= O * M) return;
     const int64_t o = i / M, g = i - o * M;
     const float* p = partial + o * Mp + g;
+    const int64_t stride = O * Mp;
     float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp) s += p[sp * O * Mp];
+    int sp = 0;
+    for (; sp + 8 <= splits; sp += 8) {           // eight loads in flight; the additions keep their order
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = p[(sp + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += t[u];
+    }
+    for (; sp < splits; ++sp) s += p[sp * stride];
     T[i] = s;
 }
 
