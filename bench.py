@@ -39,8 +39,8 @@ METRIC = "compress GB/s (% HBM peak); weight-grad TFLOP/s (% MFMA peak), 1 MI355
 def _parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--dw-dtype", choices=["f32", "bf16"], default="f32")
     ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape sweep")
@@ -137,6 +137,31 @@ def _event_avg_us(torch, fn, launches):
         ev[b][1].record()
     torch.cuda.synchronize()
     return sum(e[0].elapsed_time(e[1]) for e in ev) / (n_batches * EVENT_BATCH) * 1e3
+
+
+def _graph_step_us(torch, ring, steps):
+    """The same step replayed from a captured HIP graph (one graph holding one
+    step per ring set): what remains when the host's launch work is taken out."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for r in range(ring.R):
+            ring.step(r)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for r in range(ring.R):
+            ring.step(r)
+    reps = max(1, steps // ring.R)
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / (reps * ring.R) * 1e6
 
 
 def _other_steps_record(vl, torch, sh, ring, launches):
@@ -356,6 +381,7 @@ def main():
                         "workspace_MB": round(ring.ws_bytes / 1e6, 2)},
     }
     v_host = v.cpu().numpy()
+    out["graph_replay_us_per_step"] = round(_graph_step_us(torch, ring, args.steps), 2)
     out["other_steps"] = _other_steps_record(vl, torch, sh, ring, args.steps)
     del ring, X0, G0
     torch.cuda.empty_cache()
@@ -370,7 +396,10 @@ def main():
             vs = vl.velora_init_v(Xs, s.M, allow_degenerate=True)
             r = Ring(vl, torch, s, Xs, Gs, vs, dw_dtype)
             _, cu, wu = _time_steps(torch, r, args.shape_steps, 3, with_events=True)
-            recs.append(_shape_record(s, cu, wu, dw_b, r.ws_bytes))
+            rec = _shape_record(s, cu, wu, dw_b, r.ws_bytes)
+            dt_s, _, _ = _time_steps(torch, r, args.shape_steps, 3, with_events=False)
+            rec["step_us"] = round(dt_s / args.shape_steps * 1e6, 2)
+            recs.append(rec)
             del r, Xs, Gs
             torch.cuda.empty_cache()
         out["shapes"] = recs
