@@ -255,3 +255,31 @@ def adamw_step_factor(T: np.ndarray, v: np.ndarray, W: np.ndarray, exp_avg: np.n
     bc2 = 1.0 - beta2 ** step
     W2 = W1 - (lr / bc1) * m1 / (np.sqrt(u1) / np.sqrt(bc2) + eps)
     return W2, m1, u1
+
+
+def swiglu_compress(gate: np.ndarray, up: np.ndarray, v: np.ndarray, M: int,
+                    threads: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """The input of an LLaMA-style down projection, produced and compressed in one
+    go: X = silu(gate) * up with silu(x) = x / (1 + exp(-x)) (float64), stored in the
+    inputs' dtype (one round-to-nearest-even for bfloat16); then Sec. 3.2's
+    compress applied to the STORED X, exactly as `compress` would be applied to it
+    afterwards.  gate, up: [N, D] storage arrays of one dtype.
+    -> (X_exact float64[N, D], X_store storage[N, D], S_exact float64[N, M], S_store storage[N, M])
+    """
+    gate, up = _c(gate), _c(up)
+    assert gate.shape == up.shape and _dt(gate) == _dt(up)
+    if _dt(gate) == DT_BF16:
+        g = (gate.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        u = (up.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    else:
+        g, u = gate.astype(np.float64), up.astype(np.float64)
+    X_exact = g / (1.0 + np.exp(-g)) * u
+    if _dt(gate) == DT_BF16:
+        f = X_exact.astype(np.float32)                      # float64 -> float32 -> bfloat16: the double
+        b = f.view(np.uint32)                               # rounding can differ from a single one only in
+        lsb = (b >> 16) & 1                                 # ties that float32 cannot represent apart
+        X_store = ((b + 0x7FFF + lsb) >> 16).astype(np.uint16)
+    else:
+        X_store = X_exact.astype(np.float32)
+    S_exact, S_store = compress(X_store, v, M, threads=threads)
+    return X_exact, X_store, S_exact, S_store

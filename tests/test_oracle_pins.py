@@ -534,3 +534,40 @@ class TestAdamWFactor:
         _, m1, _ = oracle.adamw_step_factor(T, v, z, z, z, lr=1e-3, beta1=0.0, beta2=0.5, eps=1e-8,
                                             weight_decay=0.0, step=1)
         np.testing.assert_allclose(m1, dW, rtol=1e-12, atol=1e-18)
+
+
+# ------------------------------------------------------------------ producer-side fusion: silu(gate) * up, then compress
+class TestSwigluCompress:
+    def test_matches_library_silu_times_up(self):
+        import torch
+        g = _rand((9, 32), 21, sigma=3.0); u = _rand((9, 32), 22)
+        v = oracle.init_v(_rand((9, 32), 23) + np.float32(0.5), 4)[0]
+        X, Xs, S, Ss = oracle.swiglu_compress(g, u, v, 4)
+        ref = (torch.nn.functional.silu(torch.tensor(g, dtype=torch.float64)) * torch.tensor(u, dtype=torch.float64)).numpy()
+        np.testing.assert_allclose(X, ref, rtol=1e-14, atol=1e-300)
+        assert Xs.dtype == np.float32 and (Xs == ref.astype(np.float32)).all()
+
+    def test_silu_closed_forms(self):
+        x = np.array([[0.0, 1.0, -1.0, 20.0, -20.0, 0.5, -0.5, 3.0]], dtype=np.float32)
+        one = np.ones_like(x)
+        v = np.zeros(8, dtype=np.float32); v[0] = 1.0
+        X, _, _, _ = oracle.swiglu_compress(x, one, v, 1)
+        assert X[0, 0] == 0.0
+        np.testing.assert_allclose(X[0, 1] - X[0, 2], 1.0, rtol=1e-15)          # silu(x) - silu(-x) = x
+        np.testing.assert_allclose(X[0, 5] - X[0, 6], 0.5, rtol=1e-15)
+        np.testing.assert_allclose(X[0, 3], 20.0 / (1.0 + np.exp(-20.0)), rtol=1e-15)
+        np.testing.assert_allclose(X[0, 1], 1.0 / (1.0 + np.exp(-1.0)), rtol=1e-15)
+        assert abs(X[0, 4]) < 1e-7                                              # silu(-20) ~ -4e-8
+
+    def test_compress_is_taken_from_the_stored_activation(self):
+        g = wl.to_storage(_rand((6, 16), 31, sigma=2.0), wl.BF16); u = wl.to_storage(_rand((6, 16), 32), wl.BF16)
+        v = wl.random_unit_v(8, 5)
+        X, Xs, S, Ss = oracle.swiglu_compress(g, u, v, 2)
+        assert Xs.dtype == np.uint16
+        # the stored activation is the bfloat16 nearest to the exact value ...
+        near = wl.f32_to_bf16_bits(X.astype(np.float32))
+        assert (Xs == near).all()
+        assert np.abs(wl.bf16_bits_to_f32(Xs).astype(np.float64) - X).max() <= np.abs(X).max() * 2.0 ** -8
+        # ... and S is what compress gives on exactly those stored bits
+        S2, Ss2 = oracle.compress(Xs, v, 2)
+        assert (S == S2).all() and (Ss == Ss2).all()
