@@ -191,6 +191,22 @@ def _other_steps_record(vl, torch, sh, ring, launches):
     return out
 
 
+def _swiglu_record(vl, torch, sh, v, dev, launches):
+    """Producer-side fusion: X = silu(gate) * up written and compressed in one pass
+    (not part of `value`).  Bytes: gate and up in, X and S out."""
+    sets = 2
+    gate = [torch.randn((sh.N, sh.D), device=dev).mul_(2.0).to(torch.bfloat16) for _ in range(sets)]
+    up = [torch.randn((sh.N, sh.D), device=dev).to(torch.bfloat16) for _ in range(sets)]
+    X = [torch.empty((sh.N, sh.D), device=dev, dtype=torch.bfloat16) for _ in range(sets)]
+    S = torch.empty((sh.N, sh.M), device=dev, dtype=torch.bfloat16)
+    us = _event_avg_us(torch, lambda i: vl.velora_swiglu_compress(gate[i % sets], up[i % sets], v, sh.M,
+                                                                  X=X[i % sets], S=S), launches)
+    nbytes = 3 * sh.N * sh.D * 2 + sh.N * sh.M * 2 + sh.d * 4
+    return {"kernel": "swiglu_compress_vec_kernel", "bound": "hbm", "avg_us": round(us, 2), "algorithmic_bytes": nbytes,
+            "achieved": round(nbytes / us * 1e-3, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(nbytes / us * 1e-3 / HBM_PEAK_GBPS, 4)}
+
+
 def _adamw_record(vl, torch, sh, v, dev, steps):
     """The optimiser step fed by the factored gradient (not part of `value`): W
     and both moments in float32 stream through HBM once, dW is never formed."""
@@ -386,6 +402,9 @@ def main():
     del ring, X0, G0
     torch.cuda.empty_cache()
     out["adamw_step_factor"] = _adamw_record(vl, torch, sh, v, dev, args.steps)
+    torch.cuda.empty_cache()
+    if sh.dtype == wl.BF16:
+        out["swiglu_compress"] = _swiglu_record(vl, torch, sh, v, dev, args.steps)
     torch.cuda.empty_cache()
 
     # ---------------- every layer shape of the five configurations

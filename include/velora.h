@@ -136,6 +136,22 @@ velora_status velora_compress(const void* X, const float* v, int64_t N, int64_t 
                               velora_dtype xdt, void* S, velora_stream stream);
 
 /*
+ * The same compress, taken where X is produced.  The layer the paper compresses
+ * first is the MLP down projection of an LLaMA block (Sec. 4), whose input is
+ * the elementwise product X = silu(gate) * up, silu(x) = x / (1 + exp(-x)).  This
+ * call writes X and, in the same pass and from the very values it stores,
+ * S = compress(group(X), v) (Sec. 3.2, Eq. 1): X is never re-read for
+ * compression.  float32 arithmetic, one RNE rounding when X is stored; S is what
+ * velora_compress returns on the stored X (bit for bit when gate, up and X are
+ * 16-byte aligned and d is a multiple of 8 (bf16) or 4 (f32); otherwise X is
+ * written first and compressed by a second launch).
+ *   gate, up [N, D] device, dtype dt (read only);  v [d] device float32 (read only)
+ *   X [N, D] and S [N, M] device, dtype dt (written).  X may alias gate or up.
+ */
+velora_status velora_swiglu_compress(const void* gate, const void* up, const float* v, int64_t N, int64_t D,
+                                     int64_t M, velora_dtype dt, void* X, void* S, velora_stream stream);
+
+/*
  * reconstruct + ungroup (Sec. 3.2, second equation):  Xhat[n, g*d + j] = S[n, g] * v[j].
  * The materialising form; velora_weight_grad never needs it.
  *   S [N, M] device, dtype dt (read only);  v [d] device float32 (read only)

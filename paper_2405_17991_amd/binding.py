@@ -31,6 +31,7 @@ EXPORTS = [
     "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
     "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_factor",
     "velora_expand_factor", "velora_update_v", "velora_compress_update", "velora_adamw_step_factor",
+    "velora_swiglu_compress",
 ]
 
 
@@ -70,9 +71,13 @@ def _load() -> ctypes.CDLL:
     L.velora_weight_grad_factor.restype = ci
     L.velora_expand_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp]
     L.velora_expand_factor.restype = ci
+    L.velora_swiglu_compress.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, vp]
+    L.velora_swiglu_compress.restype = ci
     cf = ctypes.c_float
     L.velora_adamw_step_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, cf, cf, cf, cf, cf, i64, cf, vp]
     L.velora_adamw_step_factor.restype = ci
+    L.velora_swiglu_compress.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, vp]
+    L.velora_swiglu_compress.restype = ci
     cf = ctypes.c_float
     L.velora_update_v.argtypes = [vp, i64, i64, i64, ci, vp, cf, vp, vp, sz, vp]
     L.velora_update_v.restype = ci
@@ -186,6 +191,31 @@ def velora_compress(X, v, M: int, S=None):
     st = raw.velora_compress(X.data_ptr(), v.data_ptr(), N, D, M, _dt(X), S.data_ptr(), _stream())
     _raise(st, "velora_compress")
     return S
+
+
+def velora_swiglu_compress(gate, up, v, M: int, X=None, S=None):
+    """X = silu(gate) * up and S = compress(X, v) in one pass.  -> (X, S)"""
+    torch = _torch()
+    _check(gate, "gate", 2)
+    _check(up, "up", 2)
+    _check(v, "v", 1)
+    if gate.shape != up.shape or gate.dtype != up.dtype:
+        raise ValueError("gate and up must have the same shape and dtype")
+    if v.dtype != torch.float32:
+        raise TypeError("v must be float32")
+    N, D = gate.shape
+    if X is None:
+        X = torch.empty_like(gate)
+    if S is None:
+        S = torch.empty((N, max(M, 1)), dtype=gate.dtype, device=gate.device)
+    _check(X, "X", 2)
+    _check(S, "S", 2)
+    if tuple(X.shape) != (N, D) or X.dtype != gate.dtype or tuple(S.shape) != (N, M) or S.dtype != gate.dtype:
+        raise ValueError("X must be [N, D] and S [N, M] in the inputs' dtype")
+    st = raw.velora_swiglu_compress(gate.data_ptr(), up.data_ptr(), v.data_ptr(), N, D, M, _dt(gate), X.data_ptr(),
+                                    S.data_ptr(), _stream())
+    _raise(st, "velora_swiglu_compress")
+    return X, S
 
 
 def velora_reconstruct(S, v, D: int, Xhat=None):

@@ -19,6 +19,12 @@ hipError_t launch_compress(const void* X, const float* v, void* S, int64_t n_sub
 hipError_t launch_reconstruct(const void* S, const float* v, void* Xhat, int64_t n_sub, int64_t d, bool is_bf16,
                               bool vec_ok, const LaunchCfg& cfg, hipStream_t st);
 
+// ---- swiglu.hip ----
+// X = silu(gate) * up stored in the inputs' dtype, and S = compress(X, v) from the stored values, one pass.
+// vec_ok: gate, up, X 16-byte aligned (then d % 8 == 0 (bf16) / d % 4 == 0 (f32) takes the fused kernel).
+hipError_t launch_swiglu_compress(const void* gate, const void* up, const float* v, void* X, void* S, int64_t n_sub,
+                                  int64_t d, bool is_bf16, bool vec_ok, const LaunchCfg& cfg, hipStream_t st);
+
 // ---- init_v.hip ----
 // Workspace layout: [int32 flag | pad to 256 B | mean[d] f64 | slices[8][d] f64 | float partial[rows][d]].
 struct InitVPlan {

@@ -125,6 +125,18 @@ def test_factor_argument_errors(vl):
     assert e(P, P, 32, 16, 4, P + 2, vl.F32, 0, None) == 4
 
 
+def test_swiglu_compress_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    f = raw.velora_swiglu_compress
+    assert f(None, P, P, 8, 16, 4, vl.BF16, P, P, None) == 1
+    assert f(P, P, P, 8, 16, 4, vl.BF16, None, P, None) == 1
+    assert f(P, P, P, 8, 16, 4, 9, P, P, None) == 3
+    assert f(P, P, P, 8, 16, 5, vl.BF16, P, P, None) == 2
+    assert f(P, P, P, 0, 16, 4, vl.BF16, P, P, None) == 2
+    assert f(P, P + 1, P, 8, 16, 4, vl.BF16, P, P, None) == 4
+    assert f(P, P, P + 2, 8, 16, 4, vl.F32, P, P, None) == 4
+
+
 def test_adamw_step_factor_argument_errors(vl):
     from paper_2405_17991_amd.binding import raw
     a = raw.velora_adamw_step_factor
