@@ -283,3 +283,29 @@ def swiglu_compress(gate: np.ndarray, up: np.ndarray, v: np.ndarray, M: int,
         X_store = X_exact.astype(np.float32)
     S_exact, S_store = compress(X_store, v, M, threads=threads)
     return X_exact, X_store, S_exact, S_store
+
+
+def rmsnorm_compress(H: np.ndarray, gamma: np.ndarray, eps: float, v: np.ndarray, M: int,
+                     threads: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """The input of an LLaMA-style attention projection, produced and compressed in
+    one go: X[n, :] = H[n, :] / sqrt(mean_j H[n, j]^2 + eps) * gamma (float64),
+    stored in H's dtype (one round-to-nearest-even for bfloat16); then Sec. 3.2's
+    compress applied to the STORED X.  H: [N, D] storage array; gamma: float32 [D].
+    -> (X_exact float64[N, D], X_store storage[N, D], S_exact float64[N, M], S_store storage[N, M])
+    """
+    H = _c(H)
+    if _dt(H) == DT_BF16:
+        h = (H.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    else:
+        h = H.astype(np.float64)
+    g = np.asarray(gamma, dtype=np.float32).astype(np.float64).reshape(1, -1)
+    assert g.shape[1] == h.shape[1]
+    ms = (h * h).mean(axis=1, keepdims=True)
+    X_exact = h / np.sqrt(ms + float(eps)) * g
+    if _dt(H) == DT_BF16:
+        b = X_exact.astype(np.float32).view(np.uint32)
+        X_store = ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+    else:
+        X_store = X_exact.astype(np.float32)
+    S_exact, S_store = compress(X_store, v, M, threads=threads)
+    return X_exact, X_store, S_exact, S_store

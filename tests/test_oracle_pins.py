@@ -571,3 +571,40 @@ class TestSwigluCompress:
         # ... and S is what compress gives on exactly those stored bits
         S2, Ss2 = oracle.compress(Xs, v, 2)
         assert (S == S2).all() and (Ss == Ss2).all()
+
+
+class TestRmsnormCompress:
+    def test_matches_library_rms_norm(self):
+        import torch
+        H = _rand((11, 48), 41, sigma=1.5); gamma = _f32(np.linspace(0.5, 1.5, 48))
+        v = wl.random_unit_v(8, 2)
+        X, Xs, S, Ss = oracle.rmsnorm_compress(H, gamma, 1e-5, v, 6)
+        ref = torch.nn.functional.rms_norm(torch.tensor(H, dtype=torch.float64), (48,),
+                                           torch.tensor(gamma, dtype=torch.float64), 1e-5).numpy()
+        np.testing.assert_allclose(X, ref, rtol=1e-13, atol=1e-300)
+        S2, Ss2 = oracle.compress(Xs, v, 6)
+        assert (S == S2).all() and (Ss == Ss2).all()
+
+    def test_closed_forms(self):
+        # a constant row c normalises to sign(c) (eps = 0); gamma scales columns; rows are independent
+        H = _f32([[3.0] * 8, [-2.0] * 8, [1.0, -1.0] * 4])
+        gamma = _f32([1, 2, 3, 4, 5, 6, 7, 8])
+        v = _f32([1, 0, 0, 0])
+        X, _, S, _ = oracle.rmsnorm_compress(H, gamma, 0.0, v, 2)
+        np.testing.assert_allclose(X[0], gamma, rtol=1e-15)
+        np.testing.assert_allclose(X[1], -gamma.astype(np.float64), rtol=1e-15)
+        np.testing.assert_allclose(X[2], gamma * np.array([1, -1] * 4), rtol=1e-15)
+        np.testing.assert_allclose(S[0], [1.0, 5.0], rtol=1e-7)      # v = e_0 picks columns 0 and 4
+        # unit RMS before gamma: mean square of X / gamma is 1
+        Hr = _rand((5, 64), 43, sigma=4.0)
+        Xr, _, _, _ = oracle.rmsnorm_compress(Hr, np.ones(64, dtype=np.float32), 0.0, wl.random_unit_v(16, 1), 4)
+        np.testing.assert_allclose((Xr ** 2).mean(axis=1), 1.0, rtol=1e-13)
+
+    def test_eps_matters_only_for_tiny_rows(self):
+        H = _f32([[1e-4] * 16])
+        v = wl.random_unit_v(16, 1)
+        X0, _, _, _ = oracle.rmsnorm_compress(H, np.ones(16, dtype=np.float32), 0.0, v, 1)
+        X1, _, _, _ = oracle.rmsnorm_compress(H, np.ones(16, dtype=np.float32), 1e-6, v, 1)
+        np.testing.assert_allclose(X0[0], 1.0, rtol=1e-6)
+        h = np.float64(np.float32(1e-4))
+        np.testing.assert_allclose(X1[0], h / np.sqrt(h * h + 1e-6), rtol=1e-12)
