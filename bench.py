@@ -207,6 +207,24 @@ def _swiglu_record(vl, torch, sh, v, dev, launches):
             "frac": round(nbytes / us * 1e-3 / HBM_PEAK_GBPS, 4)}
 
 
+def _rmsnorm_record(vl, torch, wl, dev, launches):
+    """Producer-side fusion for the attention projections' input (LLaMA-7B-like:
+    N=16384, D=4096, d=256): X = RMSNorm(H) written and compressed in one pass."""
+    sh = wl.shape_by_name("cfg4_attn")
+    sets = 4
+    H = [torch.randn((sh.N, sh.D), device=dev).to(torch.bfloat16) for _ in range(sets)]
+    X = [torch.empty((sh.N, sh.D), device=dev, dtype=torch.bfloat16) for _ in range(sets)]
+    S = torch.empty((sh.N, sh.M), device=dev, dtype=torch.bfloat16)
+    gamma = torch.ones(sh.D, device=dev)
+    v = torch.nn.functional.normalize(torch.randn(sh.d, device=dev), dim=0)
+    us = _event_avg_us(torch, lambda i: vl.velora_rmsnorm_compress(H[i % sets], gamma, 1e-5, v, sh.M, X=X[i % sets], S=S),
+                       launches)
+    nbytes = 2 * sh.N * sh.D * 2 + sh.N * sh.M * 2 + sh.D * 4 + sh.d * 4
+    return {"kernel": "rmsnorm_compress_row_kernel", "workload": sh.name, "bound": "hbm", "avg_us": round(us, 2),
+            "algorithmic_bytes": nbytes, "achieved": round(nbytes / us * 1e-3, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(nbytes / us * 1e-3 / HBM_PEAK_GBPS, 4)}
+
+
 def _adamw_record(vl, torch, sh, v, dev, steps):
     """The optimiser step fed by the factored gradient (not part of `value`): W
     and both moments in float32 stream through HBM once, dW is never formed."""
@@ -405,6 +423,8 @@ def main():
     torch.cuda.empty_cache()
     if sh.dtype == wl.BF16:
         out["swiglu_compress"] = _swiglu_record(vl, torch, sh, v, dev, args.steps)
+        torch.cuda.empty_cache()
+        out["rmsnorm_compress"] = _rmsnorm_record(vl, torch, wl, dev, args.steps)
     torch.cuda.empty_cache()
 
     # ---------------- every layer shape of the five configurations

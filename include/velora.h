@@ -152,6 +152,24 @@ velora_status velora_swiglu_compress(const void* gate, const void* up, const flo
                                      int64_t M, velora_dtype dt, void* X, void* S, velora_stream stream);
 
 /*
+ * The other producer: the attention projections of an LLaMA block (the paper
+ * compresses the value projection's input, Sec. 4) read X = RMSNorm(H),
+ *     X[n, j] = H[n, j] / sqrt(mean_j H[n, j]^2 + eps) * gamma[j].
+ * This call writes X and, from the values it stores, S = compress(group(X), v)
+ * (Sec. 3.2, Eq. 1) in one pass over H.  float32 arithmetic, one RNE rounding
+ * when X is stored; S is what velora_compress returns on the stored X (bit for
+ * bit in the fused kernel: H, X, gamma 16-byte aligned, d / 8 (bf16) or d / 4
+ * (f32) a power of two <= 64, D <= 8192 (bf16) or 4096 (f32); otherwise X is
+ * written first and compressed by a second launch).
+ *   H [N, D] device, dtype dt (read only); gamma [D], v [d] device float32 (read only)
+ *   X [N, D] and S [N, M] device, dtype dt (written).  X may alias H.
+ * eps < 0 is VELORA_ERR_SHAPE.
+ */
+velora_status velora_rmsnorm_compress(const void* H, const float* gamma, float eps, const float* v, int64_t N,
+                                      int64_t D, int64_t M, velora_dtype dt, void* X, void* S,
+                                      velora_stream stream);
+
+/*
  * reconstruct + ungroup (Sec. 3.2, second equation):  Xhat[n, g*d + j] = S[n, g] * v[j].
  * The materialising form; velora_weight_grad never needs it.
  *   S [N, M] device, dtype dt (read only);  v [d] device float32 (read only)

@@ -31,7 +31,7 @@ EXPORTS = [
     "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
     "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_factor",
     "velora_expand_factor", "velora_update_v", "velora_compress_update", "velora_adamw_step_factor",
-    "velora_swiglu_compress",
+    "velora_swiglu_compress", "velora_rmsnorm_compress",
 ]
 
 
@@ -73,6 +73,8 @@ def _load() -> ctypes.CDLL:
     L.velora_expand_factor.restype = ci
     L.velora_swiglu_compress.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, vp]
     L.velora_swiglu_compress.restype = ci
+    L.velora_rmsnorm_compress.argtypes = [vp, vp, ctypes.c_float, vp, i64, i64, i64, ci, vp, vp, vp]
+    L.velora_rmsnorm_compress.restype = ci
     cf = ctypes.c_float
     L.velora_adamw_step_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, cf, cf, cf, cf, cf, i64, cf, vp]
     L.velora_adamw_step_factor.restype = ci
@@ -215,6 +217,31 @@ def velora_swiglu_compress(gate, up, v, M: int, X=None, S=None):
     st = raw.velora_swiglu_compress(gate.data_ptr(), up.data_ptr(), v.data_ptr(), N, D, M, _dt(gate), X.data_ptr(),
                                     S.data_ptr(), _stream())
     _raise(st, "velora_swiglu_compress")
+    return X, S
+
+
+def velora_rmsnorm_compress(H, gamma, eps: float, v, M: int, X=None, S=None):
+    """X = RMSNorm(H) * gamma and S = compress(X, v) in one pass.  -> (X, S)"""
+    torch = _torch()
+    _check(H, "H", 2)
+    _check(gamma, "gamma", 1)
+    _check(v, "v", 1)
+    if v.dtype != torch.float32 or gamma.dtype != torch.float32:
+        raise TypeError("gamma and v must be float32")
+    N, D = H.shape
+    if gamma.numel() != D:
+        raise ValueError("gamma must be [D]")
+    if X is None:
+        X = torch.empty_like(H)
+    if S is None:
+        S = torch.empty((N, max(M, 1)), dtype=H.dtype, device=H.device)
+    _check(X, "X", 2)
+    _check(S, "S", 2)
+    if tuple(X.shape) != (N, D) or X.dtype != H.dtype or tuple(S.shape) != (N, M) or S.dtype != H.dtype:
+        raise ValueError("X must be [N, D] and S [N, M] in H's dtype")
+    st = raw.velora_rmsnorm_compress(H.data_ptr(), gamma.data_ptr(), float(eps), v.data_ptr(), N, D, M, _dt(H),
+                                     X.data_ptr(), S.data_ptr(), _stream())
+    _raise(st, "velora_rmsnorm_compress")
     return X, S
 
 

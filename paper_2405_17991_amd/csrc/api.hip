@@ -1,6 +1,6 @@
 // C-ABI entry points of libvelora: argument validation, launch planning and
 // error mapping.  Nothing here touches device memory contents; the arithmetic
-// lives in compress.hip, swiglu.hip, init_v.hip, wgrad.hip and adamw.hip.
+// lives in compress.hip, swiglu.hip, rmsnorm.hip, init_v.hip, wgrad.hip and adamw.hip.
 #include "../../include/velora.h"
 
 #include <atomic>
@@ -191,6 +191,21 @@ velora_status velora_swiglu_compress(const void* gate, const void* up, const flo
     const bool vec_ok = ptr_align(gate) >= 16 && ptr_align(up) >= 16 && ptr_align(X) >= 16;
     return hip_status(velora::launch_swiglu_compress(gate, up, v, X, S, N * M, D / M, dt == VELORA_BF16, vec_ok, cfg,
                                                      static_cast<hipStream_t>(stream)));
+}
+
+velora_status velora_rmsnorm_compress(const void* H, const float* gamma, float eps, const float* v, int64_t N,
+                                      int64_t D, int64_t M, velora_dtype dt, void* X, void* S,
+                                      velora_stream stream) {
+    if (!H || !gamma || !v || !X || !S) return VELORA_ERR_NULL;
+    if (!dtype_ok(dt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(N, D, M) || !size_ok(N, D) || D / M > INT32_MAX / 8 || !(eps >= 0.f)) return VELORA_ERR_SHAPE;
+    const int eb = elem_bytes(dt);
+    if (ptr_align(H) < eb || ptr_align(X) < eb || ptr_align(S) < eb || ptr_align(v) < 4 || ptr_align(gamma) < 4)
+        return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool vec_ok = ptr_align(H) >= 16 && ptr_align(X) >= 16 && ptr_align(gamma) >= 16;
+    return hip_status(velora::launch_rmsnorm_compress(H, gamma, v, X, S, N, D, M, eps, dt == VELORA_BF16, vec_ok, cfg,
+                                                      static_cast<hipStream_t>(stream)));
 }
 
 velora_status velora_reconstruct(const void* S, const float* v, int64_t N, int64_t D, int64_t M, velora_dtype dt,

@@ -25,6 +25,14 @@ hipError_t launch_reconstruct(const void* S, const float* v, void* Xhat, int64_t
 hipError_t launch_swiglu_compress(const void* gate, const void* up, const float* v, void* X, void* S, int64_t n_sub,
                                   int64_t d, bool is_bf16, bool vec_ok, const LaunchCfg& cfg, hipStream_t st);
 
+// ---- rmsnorm.hip ----
+// X = H / sqrt(mean(H^2) + eps) * gamma stored in H's dtype, and S = compress(X, v) from the stored values.
+// vec_ok: H, X, gamma and v 16-byte aligned (then a power-of-two d / kPerVec <= 64 and a row of at most
+// 1024 vectors take the fused kernel).
+hipError_t launch_rmsnorm_compress(const void* H, const float* gamma, const float* v, void* X, void* S, int64_t N,
+                                   int64_t D, int64_t M, float eps, bool is_bf16, bool vec_ok, const LaunchCfg& cfg,
+                                   hipStream_t st);
+
 // ---- init_v.hip ----
 // Workspace layout: [int32 flag | pad to 256 B | mean[d] f64 | slices[8][d] f64 | float partial[rows][d]].
 struct InitVPlan {

@@ -137,6 +137,18 @@ def test_swiglu_compress_argument_errors(vl):
     assert f(P, P, P + 2, 8, 16, 4, vl.F32, P, P, None) == 4
 
 
+def test_rmsnorm_compress_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    f = raw.velora_rmsnorm_compress
+    assert f(None, P, 1e-6, P, 8, 16, 4, vl.BF16, P, P, None) == 1
+    assert f(P, None, 1e-6, P, 8, 16, 4, vl.BF16, P, P, None) == 1
+    assert f(P, P, 1e-6, P, 8, 16, 4, 7, P, P, None) == 3
+    assert f(P, P, 1e-6, P, 8, 16, 3, vl.BF16, P, P, None) == 2
+    assert f(P, P, -1.0, P, 8, 16, 4, vl.BF16, P, P, None) == 2
+    assert f(P, P + 2, 1e-6, P, 8, 16, 4, vl.BF16, P, P, None) == 4
+    assert f(P + 1, P, 1e-6, P, 8, 16, 4, vl.BF16, P, P, None) == 4
+
+
 def test_adamw_step_factor_argument_errors(vl):
     from paper_2405_17991_amd.binding import raw
     a = raw.velora_adamw_step_factor
