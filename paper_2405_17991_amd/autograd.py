@@ -12,6 +12,10 @@ from the first batch (Sec. 3.3) and then frozen.
 Only the two VeLoRA steps run in this package's kernels; the two dense GEMMs
 are not part of the method and use ``torch.matmul``.  The saved activation
 shrinks from ``N*D`` to ``N*M = N*D/d`` elements (Sec. 3.2).
+
+``VeLoRALlamaMLP`` applies the same rule to a whole gated MLP block: the block
+input is compressed once for the gate and up projections, and the down
+projection's input is compressed by the kernel that produces it.
 """
 from __future__ import annotations
 
@@ -90,3 +94,106 @@ def saved_activation_bytes(N: int, D: int, d: int, elem_bytes: int = 2) -> dict:
     """Closed form behind the paper's activation-memory tables: what one layer
     keeps for backward with and without VeLoRA (ratio = d)."""
     return {"baseline": N * D * elem_bytes, "velora": N * (D // d) * elem_bytes, "ratio": float(d)}
+
+
+class _SharedInputLinearsFunction(torch.autograd.Function):
+    """Two bias-free linears on the same input (an MLP's gate and up projections):
+    the input is compressed ONCE and both weight gradients are formed from the
+    same S (Algorithm 1 applied to each layer; the saved tensor is shared)."""
+
+    @staticmethod
+    def forward(ctx, input, w_a, w_b, v, M):
+        D = input.shape[-1]
+        x2 = input.reshape(-1, D)
+        if not x2.is_contiguous():
+            x2 = x2.contiguous()
+        S = _b.velora_compress(x2, v, M)
+        out_a = torch.matmul(x2, w_a.t())
+        out_b = torch.matmul(x2, w_b.t())
+        ctx.save_for_backward(S, w_a, w_b, v)
+        ctx.in_shape = input.shape
+        lead = input.shape[:-1]
+        return out_a.reshape(*lead, w_a.shape[0]), out_b.reshape(*lead, w_b.shape[0])
+
+    @staticmethod
+    def backward(ctx, g_a, g_b):
+        S, w_a, w_b, v = ctx.saved_tensors
+        D = w_a.shape[1]
+        ga = g_a.reshape(-1, w_a.shape[0]).contiguous()
+        gb = g_b.reshape(-1, w_b.shape[0]).contiguous()
+        grad_input = None
+        if ctx.needs_input_grad[0]:
+            grad_input = (torch.matmul(ga, w_a) + torch.matmul(gb, w_b)).reshape(ctx.in_shape)
+        dwa = _b.velora_weight_grad(ga, S, v, D, dw_dtype=w_a.dtype) if ctx.needs_input_grad[1] else None
+        dwb = _b.velora_weight_grad(gb, S, v, D, dw_dtype=w_b.dtype) if ctx.needs_input_grad[2] else None
+        return grad_input, dwa, dwb, None, None
+
+
+class _SwiGLUDownFunction(torch.autograd.Function):
+    """``out = (silu(gate) * up) @ weight.T`` with the product compressed where it is
+    produced (``velora_swiglu_compress``): the product itself is not kept for
+    backward, only S; gate and up stay because the activation's own backward
+    needs them."""
+
+    @staticmethod
+    def forward(ctx, gate, up, weight, v, M):
+        F = gate.shape[-1]
+        g2 = gate.reshape(-1, F).contiguous()
+        u2 = up.reshape(-1, F).contiguous()
+        X, S = _b.velora_swiglu_compress(g2, u2, v, M)
+        out = torch.matmul(X, weight.t())
+        del X
+        ctx.save_for_backward(g2, u2, S, weight, v)
+        ctx.in_shape = gate.shape
+        return out.reshape(*gate.shape[:-1], weight.shape[0])
+
+    @staticmethod
+    def backward(ctx, grad_output):
+        g2, u2, S, weight, v = ctx.saved_tensors
+        O, F = weight.shape
+        go = grad_output.reshape(-1, O).contiguous()
+        grad_w = _b.velora_weight_grad(go, S, v, F, dw_dtype=weight.dtype) if ctx.needs_input_grad[2] else None
+        grad_gate = grad_up = None
+        if ctx.needs_input_grad[0] or ctx.needs_input_grad[1]:
+            dX = torch.matmul(go, weight).float()
+            gf = g2.float()
+            sig = torch.sigmoid(gf)
+            grad_up = (dX * gf * sig).to(u2.dtype).reshape(ctx.in_shape)
+            grad_gate = (dX * u2.float() * sig * (1.0 + gf * (1.0 - sig))).to(g2.dtype).reshape(ctx.in_shape)
+        return grad_gate, grad_up, grad_w, None, None
+
+
+class VeLoRALlamaMLP(torch.nn.Module):
+    """LLaMA-style gated MLP, ``down(silu(gate(h)) * up(h))``, with VeLoRA on all three
+    projections: ``h`` is compressed once for gate and up, and the down
+    projection's input is compressed in the kernel that produces it.  Per token the
+    block keeps ``hidden/d_h + inter/d_ff`` scalars in place of ``hidden + inter``
+    saved inputs (gate and up themselves are still kept for the activation)."""
+
+    def __init__(self, hidden: int, inter: int, d_hidden: int, d_inter: int, device=None, dtype=None):
+        super().__init__()
+        if hidden % d_hidden or inter % d_inter:
+            raise ValueError("the sub-token sizes must divide the layer widths")
+        self.hidden, self.inter = hidden, inter
+        self.M_h, self.M_f = hidden // d_hidden, inter // d_inter
+        mk = lambda o, i: torch.nn.Parameter(torch.nn.init.normal_(torch.empty((o, i), device=device, dtype=dtype),
+                                                                    std=i ** -0.5))
+        self.w_gate, self.w_up, self.w_down = mk(inter, hidden), mk(inter, hidden), mk(hidden, inter)
+        self.register_buffer("v_h", torch.zeros(d_hidden, device=device, dtype=torch.float32))
+        self.register_buffer("v_f", torch.zeros(d_inter, device=device, dtype=torch.float32))
+        self.register_buffer("v_ready", torch.zeros((), device=device, dtype=torch.bool))
+
+    @torch.no_grad()
+    def init_v(self, h: torch.Tensor) -> None:
+        """Both vectors from the first batch (Sec. 3.3): v_h from h, v_f from the first silu(gate)*up."""
+        h2 = h.reshape(-1, self.hidden).contiguous()
+        _b.velora_init_v(h2, self.M_h, v=self.v_h, allow_degenerate=True)
+        x = torch.nn.functional.silu(torch.matmul(h2, self.w_gate.t())) * torch.matmul(h2, self.w_up.t())
+        _b.velora_init_v(x.contiguous(), self.M_f, v=self.v_f, allow_degenerate=True)
+        self.v_ready.fill_(True)
+
+    def forward(self, h: torch.Tensor) -> torch.Tensor:
+        if not bool(self.v_ready):
+            self.init_v(h.detach())
+        gate, up = _SharedInputLinearsFunction.apply(h, self.w_gate, self.w_up, self.v_h, self.M_h)
+        return _SwiGLUDownFunction.apply(gate, up, self.w_down, self.v_f, self.M_f)

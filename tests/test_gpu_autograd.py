@@ -116,3 +116,72 @@ def test_device_memory_held_between_forward_and_backward(mods):
     assert plain >= N * D * 2                        # the input itself is still held for backward
     assert ours <= N * (D // d) * 2 + (2 << 20)      # only S (plus allocator block rounding)
     assert plain - ours >= N * D * 2 - N * (D // d) * 2 - (2 << 20)
+
+
+def _reference_mlp_grads(torch, h, wg, wu, wd, v_h, v_f, gout):
+    """The same block written with plain torch ops: dense forward, and for every weight
+    the paper's backward rule grad_weight = grad_output^T @ reconstruct(compress(input))."""
+    d_h, d_f = v_h.numel(), v_f.numel()
+
+    def proj(x, v, d):       # reconstruct(compress(x)), S rounded to the storage dtype as the library stores it
+        n, D = x.shape
+        z = x.float().reshape(n, D // d, d)
+        s = (z @ v).to(x.dtype).float()
+        return (s.unsqueeze(-1) * v).reshape(n, D)
+
+    hf = h.float()
+    gate = (h @ wg.t()); up = (h @ wu.t())
+    X = (torch.nn.functional.silu(gate.float()) * up.float()).to(h.dtype)
+    out = X @ wd.t()
+    go = gout.float()
+    dWd = go.t() @ proj(X, v_f, d_f)
+    dX = go @ wd.float()
+    gf = gate.float(); sig = torch.sigmoid(gf)
+    dup = (dX * gf * sig).to(h.dtype); dgate = (dX * up.float() * sig * (1 + gf * (1 - sig))).to(h.dtype)
+    ph = proj(h, v_h, d_h)
+    dWg = dgate.float().t() @ ph
+    dWu = dup.float().t() @ ph
+    dh = dgate.float() @ wg.float() + dup.float() @ wu.float()
+    return out, dWg, dWu, dWd, dh
+
+
+def test_llama_mlp_block_matches_the_same_rule_in_plain_torch(mods):
+    torch, va = mods
+    torch.manual_seed(3)
+    N, H, F, d_h, d_f = 512, 256, 704, 64, 64
+    blk = va.VeLoRALlamaMLP(H, F, d_h, d_f, device="cuda", dtype=torch.bfloat16)
+    h = torch.randn(N, H, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    gout = (torch.randn(N, H, device="cuda") * 0.05).to(torch.bfloat16)
+    out = blk(h)
+    out.backward(gout)
+    torch.cuda.synchronize()
+    ro, rg, ru, rd, rh = _reference_mlp_grads(torch, h.detach(), blk.w_gate.detach(), blk.w_up.detach(),
+                                              blk.w_down.detach(), blk.v_h, blk.v_f, gout)
+
+    def rel(a, b):
+        return ((a.float() - b.float()).norm() / b.float().norm()).item()
+
+    assert rel(out, ro) <= 2e-2
+    assert rel(blk.w_gate.grad, rg) <= 2e-2 and rel(blk.w_up.grad, ru) <= 2e-2 and rel(blk.w_down.grad, rd) <= 2e-2
+    assert rel(h.grad, rh) <= 2e-2
+
+
+def test_llama_mlp_block_keeps_scalars_instead_of_inputs(mods):
+    torch, va = mods
+    N, H, F, d_h, d_f = 2048, 1024, 2816, 128, 128
+    blk = va.VeLoRALlamaMLP(H, F, d_h, d_f, device="cuda", dtype=torch.bfloat16)
+    blk.init_v(torch.randn(N, H, device="cuda", dtype=torch.bfloat16))
+    params = {p.data_ptr() for p in blk.parameters()} | {blk.v_h.data_ptr(), blk.v_f.data_ptr()}
+    seen = {}
+
+    def pack(t):
+        if t.data_ptr() not in params:
+            seen[t.data_ptr()] = t.numel() * t.element_size()
+        return t
+
+    h = torch.randn(N, H, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    with torch.autograd.graph.saved_tensors_hooks(pack, lambda t: t):
+        blk(h)
+    # gate and up (for the activation's backward) plus one scalar per sub-token of h and of the product;
+    # neither h (N*H) nor the product (N*F) is kept
+    assert sum(seen.values()) == 2 * N * F * 2 + N * (H // d_h) * 2 + N * (F // d_f) * 2
