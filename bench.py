@@ -393,7 +393,7 @@ def main():
 
     cb, wb = sh.compress_bytes(), sh.wgrad_bytes(dw_b)
     c_gbps, w_gbps = cb / c_us * 1e-3, wb / w_us * 1e-3
-    traffic = _traffic(args.workload)
+    traffic = _traffic(args.workload) if args.dw_dtype == "f32" else None   # the committed counters are for fp32 dW
     out = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",

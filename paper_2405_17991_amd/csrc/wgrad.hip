@@ -543,7 +543,8 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
                                                                      const float* __restrict__ v,
                                                                      void* __restrict__ dW, int splits, int64_t O,
                                                                      int64_t D, int64_t M, int64_t Mp, int d,
-                                                                     int d_shift, int accumulate, int rows_per_block) {
+                                                                     int d_shift, int accumulate, int rows_per_block,
+                                                                     int vec8) {
     __shared__ float P[kTChunk];     // partials of the block's rows: [row][split][group]
     __shared__ float T[kTChunk / 2];  // their sums: [row][group]
     const int64_t split_stride = O * Mp;
@@ -581,7 +582,47 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
             const float* Tr = T + r * mchunk;
             const int64_t c_begin = gc0 * d;
             const int64_t c_count = static_cast<int64_t>(gcn) * d;
-            if constexpr (VEC) {
+            if constexpr (VEC && OUT_BF16) {
+                // eight bf16 = one 16-byte store per thread and trip when the sub-token size allows it
+                if (vec8) {
+                    for (int64_t i = p; i < c_count / 8; i += tpr) {
+                        const int64_t cl = i * 8;
+                        const int gl = d_shift >= 0 ? static_cast<int>(cl >> d_shift) : static_cast<int>(cl / d);
+                        const int j = static_cast<int>(cl - static_cast<int64_t>(gl) * d);
+                        const float tg = Tr[gl];
+                        const float4 va = *reinterpret_cast<const float4*>(v + j);
+                        const float4 vb = *reinterpret_cast<const float4*>(v + j + 4);
+                        float r[8] = {tg * va.x, tg * va.y, tg * va.z, tg * va.w, tg * vb.x, tg * vb.y, tg * vb.z, tg * vb.w};
+                        const int64_t e = o * D + c_begin + cl;
+                        uint4* q = reinterpret_cast<uint4*>(static_cast<uint16_t*>(dW) + e);
+                        if (accumulate) {
+                            const uint4 old = *q;
+                            r[0] += bf16_lo(old.x); r[1] += bf16_hi(old.x); r[2] += bf16_lo(old.y); r[3] += bf16_hi(old.y);
+                            r[4] += bf16_lo(old.z); r[5] += bf16_hi(old.z); r[6] += bf16_lo(old.w); r[7] += bf16_hi(old.w);
+                        }
+                        const u32x4 packed_out = {pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]),
+                                                  pack_bf16x2(r[4], r[5]), pack_bf16x2(r[6], r[7])};
+                        __builtin_nontemporal_store(packed_out, reinterpret_cast<u32x4*>(q));
+                    }
+                } else {
+                    for (int64_t i = p; i < c_count / 4; i += tpr) {
+                        const int64_t cl = i * 4;
+                        const int gl = d_shift >= 0 ? static_cast<int>(cl >> d_shift) : static_cast<int>(cl / d);
+                        const int j = static_cast<int>(cl - static_cast<int64_t>(gl) * d);
+                        const float tg = Tr[gl];
+                        const float4 vv = *reinterpret_cast<const float4*>(v + j);
+                        float r0 = tg * vv.x, r1 = tg * vv.y, r2 = tg * vv.z, r3 = tg * vv.w;
+                        const int64_t e = o * D + c_begin + cl;
+                        uint2* q = reinterpret_cast<uint2*>(static_cast<uint16_t*>(dW) + e);
+                        if (accumulate) {
+                            const uint2 old = *q;
+                            r0 += bf16_lo(old.x); r1 += bf16_hi(old.x); r2 += bf16_lo(old.y); r3 += bf16_hi(old.y);
+                        }
+                        const u32x2 packed_out = {pack_bf16x2(r0, r1), pack_bf16x2(r2, r3)};
+                        __builtin_nontemporal_store(packed_out, reinterpret_cast<u32x2*>(q));
+                    }
+                }
+            } else if constexpr (VEC) {
                 for (int64_t i = p; i < c_count / 4; i += tpr) {
                     const int64_t cl = i * 4;
                     const int gl = d_shift >= 0 ? static_cast<int>(cl >> d_shift) : static_cast<int>(cl / d);
@@ -590,23 +631,13 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
                     const float4 vv = *reinterpret_cast<const float4*>(v + j);
                     float r0 = tg * vv.x, r1 = tg * vv.y, r2 = tg * vv.z, r3 = tg * vv.w;
                     const int64_t e = o * D + c_begin + cl;
-                    if constexpr (OUT_BF16) {
-                        uint2* q = reinterpret_cast<uint2*>(static_cast<uint16_t*>(dW) + e);
-                        if (accumulate) {
-                            const uint2 old = *q;
-                            r0 += bf16_lo(old.x); r1 += bf16_hi(old.x); r2 += bf16_lo(old.y); r3 += bf16_hi(old.y);
-                        }
-                        const u32x2 packed_out = {pack_bf16x2(r0, r1), pack_bf16x2(r2, r3)};
-                        __builtin_nontemporal_store(packed_out, reinterpret_cast<u32x2*>(q));
-                    } else {
-                        float4* q = reinterpret_cast<float4*>(static_cast<float*>(dW) + e);
-                        if (accumulate) {
-                            const float4 old = *q;
-                            r0 += old.x; r1 += old.y; r2 += old.z; r3 += old.w;
-                        }
-                        const f32x4 out4 = {r0, r1, r2, r3};
-                        __builtin_nontemporal_store(out4, reinterpret_cast<f32x4*>(q));
+                    float4* q = reinterpret_cast<float4*>(static_cast<float*>(dW) + e);
+                    if (accumulate) {
+                        const float4 old = *q;
+                        r0 += old.x; r1 += old.y; r2 += old.z; r3 += old.w;
                     }
+                    const f32x4 out4 = {r0, r1, r2, r3};
+                    __builtin_nontemporal_store(out4, reinterpret_cast<f32x4*>(q));
                 }
             } else {
                 for (int64_t cl = p; cl < c_count; cl += tpr) {
@@ -745,7 +776,7 @@ hipError_t launch_simple(const void* G, const void* S, float* partial, int64_t N
 
 template <bool OUT_BF16, bool VEC>
 hipError_t launch_expand(const float* partial, int splits, int64_t Mp, const float* v, void* dW, int64_t O, int64_t D,
-                         int64_t M, bool accumulate, hipStream_t st) {
+                         int64_t M, bool accumulate, bool dw_align16, hipStream_t st) {
     const int d = static_cast<int>(D / M);
     int d_shift = -1;
     if ((d & (d - 1)) == 0) {
@@ -756,7 +787,8 @@ hipError_t launch_expand(const float* partial, int splits, int64_t Mp, const flo
     // 256..1024 threads; short rows are grouped (power of two, <= 16 rows).
     // (measured: 4 stores per thread is at or near the best block shape for
     // every layer shape of the five configurations)
-    const int64_t per_row = ceil_div(D, 4);
+    const bool vec8 = OUT_BF16 && VEC && d % 8 == 0 && dw_align16;
+    const int64_t per_row = ceil_div(D, vec8 ? 8 : 4);
     const int spt = 4;
     int64_t threads = ceil_div(ceil_div(per_row, spt), 64) * 64;
     if (threads > kExpandThreads) threads = kExpandThreads;
@@ -771,7 +803,7 @@ hipError_t launch_expand(const float* partial, int splits, int64_t Mp, const flo
     }
     hipLaunchKernelGGL((wgrad_expand_kernel<OUT_BF16, VEC>), dim3(static_cast<unsigned>(ceil_div(O, rows_per_block))),
                        dim3(static_cast<unsigned>(threads)), 0, st, partial, v, dW, splits, O, D, M, Mp, d, d_shift,
-                       accumulate ? 1 : 0, rows_per_block);
+                       accumulate ? 1 : 0, rows_per_block, vec8 ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -883,11 +915,11 @@ hipError_t expand_any(const float* partial, int splits, int64_t Mp, const float*
     const int64_t d = D / M;
     const bool vec = (d % 4 == 0) && v_align >= 16 && dw_align >= (dw_bf16 ? 8 : 16);
     if (dw_bf16) {
-        return vec ? launch_expand<true, true>(partial, splits, Mp, v, dW, O, D, M, accumulate, st)
-                   : launch_expand<true, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, st);
+        return vec ? launch_expand<true, true>(partial, splits, Mp, v, dW, O, D, M, accumulate, dw_align >= 16, st)
+                   : launch_expand<true, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, false, st);
     }
-    return vec ? launch_expand<false, true>(partial, splits, Mp, v, dW, O, D, M, accumulate, st)
-               : launch_expand<false, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, st);
+    return vec ? launch_expand<false, true>(partial, splits, Mp, v, dW, O, D, M, accumulate, true, st)
+               : launch_expand<false, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, false, st);
 }
 
 }  // namespace
