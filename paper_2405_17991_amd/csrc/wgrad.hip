@@ -39,9 +39,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // registers with v_perm_b32, which yields CW ready B fragments for CW
 // different columns.  The column a lane/fragment pair stands for is strided
 // (o = o0 + jj*CW + c); MFMA columns need not be adjacent in memory and the
-// epilogue undoes the mapping.  No LDS is involved, so the loads of several
-// future steps can be kept in flight in a register ring (NST stages), which is
-// what a bandwidth-bound kernel needs.
+// epilogue undoes the mapping.  No LDS is involved, so loads can be issued
+// ahead into a register ring (NST stages).  One stage is what is used: a CU
+// sustains a bounded number of outstanding cache-line requests (about 80), which
+// four waves with one 32-token step each already exceed, and deeper rings
+// measured slower on every layer shape.
 //
 // S (small, re-read by every column tile).  Up to three group tiles (DIRECT):
 // lane (jj, q) gathers its eight values S[8q + e][16*tile + jj] with 2-byte
@@ -51,7 +53,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 //
 //   CW   G columns per lane (8 -> 16-byte loads, 4 -> 8-byte)
 //   GT   16-group tiles per block (the block covers 16*GT groups g)
-//   NST  ring depth: 32-token steps in flight per wave
+//   NST  ring depth: 32-token steps loaded ahead per wave
 //   DIRECT  S operand is S[N, M] itself rather than the packed fragments
 // Block = 4 waves; the waves take alternate 32-token steps of the block's token
 // range and are summed through LDS at the end in a fixed order.
