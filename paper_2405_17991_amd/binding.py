@@ -100,10 +100,14 @@ def velora_version() -> int:
 
 
 _ws_cache = {}
+_torch_mod = None
 
 
 def velora_workspace_bytes(op: int, N: int, D: int, O: int, M: int, dtype: int) -> int:
-    key = (op, N, D, O, M, dtype)
+    # the answer depends on the current device's CU count, so the device is part of the key
+    tm = _torch_mod
+    dev = tm.cuda.current_device() if tm is not None and tm.cuda.is_initialized() else -1
+    key = (dev, op, N, D, O, M, dtype)
     need = _ws_cache.get(key)
     if need is None:
         need = int(raw.velora_workspace_bytes(op, N, D, O, M, dtype))
@@ -113,9 +117,6 @@ def velora_workspace_bytes(op: int, N: int, D: int, O: int, M: int, dtype: int) 
 
 
 # ---- torch plumbing ---------------------------------------------------------
-_torch_mod = None
-
-
 def _torch():
     global _torch_mod
     if _torch_mod is None:
