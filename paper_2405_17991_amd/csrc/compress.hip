@@ -27,10 +27,11 @@ template <typename E, int P, int L, int U>
 __global__ __launch_bounds__(256) void compress_vec_kernel(const uint4* __restrict__ X,
                                                           const float* __restrict__ v,
                                                           typename E::type* __restrict__ S,
-                                                          int64_t n_sub) {
+                                                          int64_t n_sub, int vps) {
+    // vps = 16-byte vectors per sub-token, P * (L - 1) < vps <= P * L: when d / kPerVec is not a power of
+    // two the lanes (and vectors) past vps stay idle and contribute zeros
     constexpr int kV = E::kPerVec;
     constexpr int SEG = kWave / P;
-    constexpr int kVecPerSub = P * L;               // 16-byte vectors per sub-token
     const int lane = threadIdx.x & (kWave - 1);
     const int p = lane % P;
     const int seg = lane / P;
@@ -43,7 +44,7 @@ __global__ __launch_bounds__(256) void compress_vec_kernel(const uint4* __restri
 #pragma unroll
     for (int l = 0; l < L; ++l)
 #pragma unroll
-        for (int e = 0; e < kV; ++e) vf[l][e] = v[(l * P + p) * kV + e];
+        for (int e = 0; e < kV; ++e) vf[l][e] = (l * P + p) < vps ? v[(l * P + p) * kV + e] : 0.f;
 
     for (int64_t chunk = wave; chunk < n_chunks; chunk += n_waves) {
         const int64_t k0 = chunk * (SEG * U) + static_cast<int64_t>(seg) * U;
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(256) void compress_vec_kernel(const uint4* __restri
 #pragma unroll
             for (int l = 0; l < L; ++l) {
                 q[u][l] = make_uint4(0u, 0u, 0u, 0u);
-                if (k0 + u < n_sub) q[u][l] = load_stream16(&X[(k0 + u) * kVecPerSub + l * P + p]);
+                if (k0 + u < n_sub && l * P + p < vps) q[u][l] = load_stream16(&X[(k0 + u) * vps + l * P + p]);
             }
         float sum[U];
 #pragma unroll
@@ -198,13 +199,13 @@ int grid_for(int64_t n_wave_items, int waves_per_block, int max_blocks) {
 }
 
 template <typename E, int P, int L, int U>
-hipError_t launch_compress_vec(const void* X, const float* v, void* S, int64_t n_sub, const LaunchCfg& cfg,
+hipError_t launch_compress_vec(const void* X, const float* v, void* S, int64_t n_sub, int vps, const LaunchCfg& cfg,
                                hipStream_t st) {
     constexpr int SEG = kWave / P;
     const int64_t n_chunks = ceil_div(n_sub, static_cast<int64_t>(SEG) * U);
     const int grid = grid_for(n_chunks, kBlock / kWave, cfg.max_blocks);
     hipLaunchKernelGGL((compress_vec_kernel<E, P, L, U>), dim3(grid), dim3(kBlock), 0, st,
-                       static_cast<const uint4*>(X), v, static_cast<typename E::type*>(S), n_sub);
+                       static_cast<const uint4*>(X), v, static_cast<typename E::type*>(S), n_sub, vps);
     return hipGetLastError();
 }
 
@@ -212,18 +213,19 @@ template <typename E>
 hipError_t dispatch_compress_vec(int vec_per_sub, const void* X, const float* v, void* S, int64_t n_sub,
                                  const LaunchCfg& cfg, hipStream_t st, bool* handled) {
     *handled = true;
-    switch (vec_per_sub) {
-        case 1:   return launch_compress_vec<E, 1, 1, 8>(X, v, S, n_sub, cfg, st);
-        case 2:   return launch_compress_vec<E, 2, 1, 8>(X, v, S, n_sub, cfg, st);
-        case 4:   return launch_compress_vec<E, 4, 1, 8>(X, v, S, n_sub, cfg, st);
-        case 8:   return launch_compress_vec<E, 8, 1, 8>(X, v, S, n_sub, cfg, st);
-        case 16:  return launch_compress_vec<E, 16, 1, 8>(X, v, S, n_sub, cfg, st);
-        case 32:  return launch_compress_vec<E, 32, 1, 8>(X, v, S, n_sub, cfg, st);
-        case 64:  return launch_compress_vec<E, 64, 1, 8>(X, v, S, n_sub, cfg, st);
-        case 128: return launch_compress_vec<E, 64, 2, 4>(X, v, S, n_sub, cfg, st);
-        case 256: return launch_compress_vec<E, 64, 4, 2>(X, v, S, n_sub, cfg, st);
-        default:  *handled = false; return hipSuccess;
-    }
+    // lanes per sub-token: the next power of two (at most 64); vectors per lane: 1, 2 or 4
+    const int vps = vec_per_sub;
+    if (vps <= 1) return launch_compress_vec<E, 1, 1, 8>(X, v, S, n_sub, vps, cfg, st);
+    if (vps <= 2) return launch_compress_vec<E, 2, 1, 8>(X, v, S, n_sub, vps, cfg, st);
+    if (vps <= 4) return launch_compress_vec<E, 4, 1, 8>(X, v, S, n_sub, vps, cfg, st);
+    if (vps <= 8) return launch_compress_vec<E, 8, 1, 8>(X, v, S, n_sub, vps, cfg, st);
+    if (vps <= 16) return launch_compress_vec<E, 16, 1, 8>(X, v, S, n_sub, vps, cfg, st);
+    if (vps <= 32) return launch_compress_vec<E, 32, 1, 8>(X, v, S, n_sub, vps, cfg, st);
+    if (vps <= 64) return launch_compress_vec<E, 64, 1, 8>(X, v, S, n_sub, vps, cfg, st);
+    if (vps <= 128) return launch_compress_vec<E, 64, 2, 4>(X, v, S, n_sub, vps, cfg, st);
+    if (vps <= 256) return launch_compress_vec<E, 64, 4, 2>(X, v, S, n_sub, vps, cfg, st);
+    *handled = false;
+    return hipSuccess;
 }
 
 template <typename E>

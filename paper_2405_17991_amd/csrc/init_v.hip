@@ -18,9 +18,9 @@ __global__ __launch_bounds__(256) void colsum_vec_kernel(const uint4* __restrict
                                                         int64_t n_sub, int d) {
     constexpr int kV = E::kPerVec;
     constexpr int SEG = kWave / P;
-    constexpr int kVecPerSub = P * L;
     constexpr int kWavesPerBlock = 256 / kWave;
     __shared__ float lds[kWavesPerBlock][L * kV][kWave + 1];
+    const int vps = d / kV;        // vectors per sub-token, P * (L - 1) < vps <= P * L; lanes past it stay idle
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wib = threadIdx.x / kWave;
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void colsum_vec_kernel(const uint4* __restrict
             for (int l = 0; l < L; ++l) {
                 q[u][l] = make_uint4(0u, 0u, 0u, 0u);
                 const int64_t k = k0 + static_cast<int64_t>(u) * SEG;
-                if (k < n_sub) q[u][l] = load_stream16(&X[k * kVecPerSub + l * P + p]);
+                if (k < n_sub && l * P + p < vps) q[u][l] = load_stream16(&X[k * vps + l * P + p]);
             }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -193,9 +193,9 @@ __global__ __launch_bounds__(256) void compress_colsum_vec_kernel(const uint4* _
                                                                  float* __restrict__ partial, int64_t n_sub, int d) {
     constexpr int kV = E::kPerVec;
     constexpr int SEG = kWave / P;
-    constexpr int kVecPerSub = P * L;
     constexpr int kWavesPerBlock = 256 / kWave;
     __shared__ float lds[kWavesPerBlock][L * kV][kWave + 1];
+    const int vps = d / kV;        // as in compress_vec_kernel: lanes and vectors past vps stay idle
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wib = threadIdx.x / kWave;
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void compress_colsum_vec_kernel(const uint4* _
     for (int l = 0; l < L; ++l)
 #pragma unroll
         for (int e = 0; e < kV; ++e) {
-            vf[l][e] = v[(l * P + p) * kV + e];
+            vf[l][e] = (l * P + p) < vps ? v[(l * P + p) * kV + e] : 0.f;
             acc[l][e] = 0.f;
         }
 
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(256) void compress_colsum_vec_kernel(const uint4* _
 #pragma unroll
             for (int l = 0; l < L; ++l) {
                 q[u][l] = make_uint4(0u, 0u, 0u, 0u);
-                if (k0 + u < n_sub) q[u][l] = load_stream16(&X[(k0 + u) * kVecPerSub + l * P + p]);
+                if (k0 + u < n_sub && l * P + p < vps) q[u][l] = load_stream16(&X[(k0 + u) * vps + l * P + p]);
             }
         float sum[U];
 #pragma unroll
@@ -282,24 +282,23 @@ template <typename E>
 hipError_t dispatch_colsum_vec(int vec_per_sub, const void* X, float* partial, int64_t n_sub, int d, int blocks,
                                hipStream_t st, bool* handled) {
     *handled = true;
-    switch (vec_per_sub) {
-        case 1:   return launch_colsum_vec<E, 1, 1, 8>(X, partial, n_sub, d, blocks, st);
-        case 2:   return launch_colsum_vec<E, 2, 1, 8>(X, partial, n_sub, d, blocks, st);
-        case 4:   return launch_colsum_vec<E, 4, 1, 8>(X, partial, n_sub, d, blocks, st);
-        case 8:   return launch_colsum_vec<E, 8, 1, 8>(X, partial, n_sub, d, blocks, st);
-        case 16:  return launch_colsum_vec<E, 16, 1, 8>(X, partial, n_sub, d, blocks, st);
-        case 32:  return launch_colsum_vec<E, 32, 1, 8>(X, partial, n_sub, d, blocks, st);
-        case 64:  return launch_colsum_vec<E, 64, 1, 8>(X, partial, n_sub, d, blocks, st);
-        case 128: return launch_colsum_vec<E, 64, 2, 4>(X, partial, n_sub, d, blocks, st);
-        case 256: return launch_colsum_vec<E, 64, 4, 2>(X, partial, n_sub, d, blocks, st);
-        default:  *handled = false; return hipSuccess;
-    }
+    const int vps = vec_per_sub;   // lanes per sub-token: the next power of two, at most 64; 1, 2 or 4 vectors per lane
+    if (vps <= 1) return launch_colsum_vec<E, 1, 1, 8>(X, partial, n_sub, d, blocks, st);
+    if (vps <= 2) return launch_colsum_vec<E, 2, 1, 8>(X, partial, n_sub, d, blocks, st);
+    if (vps <= 4) return launch_colsum_vec<E, 4, 1, 8>(X, partial, n_sub, d, blocks, st);
+    if (vps <= 8) return launch_colsum_vec<E, 8, 1, 8>(X, partial, n_sub, d, blocks, st);
+    if (vps <= 16) return launch_colsum_vec<E, 16, 1, 8>(X, partial, n_sub, d, blocks, st);
+    if (vps <= 32) return launch_colsum_vec<E, 32, 1, 8>(X, partial, n_sub, d, blocks, st);
+    if (vps <= 64) return launch_colsum_vec<E, 64, 1, 8>(X, partial, n_sub, d, blocks, st);
+    if (vps <= 128) return launch_colsum_vec<E, 64, 2, 4>(X, partial, n_sub, d, blocks, st);
+    if (vps <= 256) return launch_colsum_vec<E, 64, 4, 2>(X, partial, n_sub, d, blocks, st);
+    *handled = false;
+    return hipSuccess;
 }
 
 bool vec_shape_ok(int64_t d, int per_vec) {
     if (d % per_vec) return false;
-    const int64_t vps = d / per_vec;
-    return vps <= 256 && (vps & (vps - 1)) == 0;
+    return d / per_vec <= 256;
 }
 
 template <typename E>
@@ -331,17 +330,16 @@ hipError_t launch_compress_colsum_vec(const void* X, const float* v, void* S, fl
 template <typename E>
 hipError_t dispatch_compress_colsum(int vec_per_sub, const void* X, const float* v, void* S, float* partial,
                                     int64_t n_sub, int d, int blocks, hipStream_t st) {
-    switch (vec_per_sub) {
-        case 1:   return launch_compress_colsum_vec<E, 1, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
-        case 2:   return launch_compress_colsum_vec<E, 2, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
-        case 4:   return launch_compress_colsum_vec<E, 4, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
-        case 8:   return launch_compress_colsum_vec<E, 8, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
-        case 16:  return launch_compress_colsum_vec<E, 16, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
-        case 32:  return launch_compress_colsum_vec<E, 32, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
-        case 64:  return launch_compress_colsum_vec<E, 64, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
-        case 128: return launch_compress_colsum_vec<E, 64, 2, 4>(X, v, S, partial, n_sub, d, blocks, st);
-        default:  return launch_compress_colsum_vec<E, 64, 4, 2>(X, v, S, partial, n_sub, d, blocks, st);
-    }
+    const int vps = vec_per_sub;   // at most 256: fused_compress_update_ok
+    if (vps <= 1) return launch_compress_colsum_vec<E, 1, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+    if (vps <= 2) return launch_compress_colsum_vec<E, 2, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+    if (vps <= 4) return launch_compress_colsum_vec<E, 4, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+    if (vps <= 8) return launch_compress_colsum_vec<E, 8, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+    if (vps <= 16) return launch_compress_colsum_vec<E, 16, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+    if (vps <= 32) return launch_compress_colsum_vec<E, 32, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+    if (vps <= 64) return launch_compress_colsum_vec<E, 64, 1, 8>(X, v, S, partial, n_sub, d, blocks, st);
+    if (vps <= 128) return launch_compress_colsum_vec<E, 64, 2, 4>(X, v, S, partial, n_sub, d, blocks, st);
+    return launch_compress_colsum_vec<E, 64, 4, 2>(X, v, S, partial, n_sub, d, blocks, st);
 }
 
 struct WsView {

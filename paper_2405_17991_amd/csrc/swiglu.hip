@@ -29,10 +29,10 @@ __global__ __launch_bounds__(256) void swiglu_compress_vec_kernel(const uint4* _
                                                                  const uint4* __restrict__ up,
                                                                  const float* __restrict__ v,
                                                                  uint4* __restrict__ X,
-                                                                 typename E::type* __restrict__ S, int64_t n_sub) {
+                                                                 typename E::type* __restrict__ S, int64_t n_sub,
+                                                                 int vps) {
     constexpr int kV = E::kPerVec;
     constexpr int SEG = kWave / P;
-    constexpr int kVecPerSub = P * L;
     const int lane = threadIdx.x & (kWave - 1);
     const int p = lane % P;
     const int seg = lane / P;
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void swiglu_compress_vec_kernel(const uint4* _
 #pragma unroll
     for (int l = 0; l < L; ++l)
 #pragma unroll
-        for (int e = 0; e < kV; ++e) vf[l][e] = v[(l * P + p) * kV + e];
+        for (int e = 0; e < kV; ++e) vf[l][e] = (l * P + p) < vps ? v[(l * P + p) * kV + e] : 0.f;
 
     for (int64_t chunk = wave; chunk < n_chunks; chunk += n_waves) {
         const int64_t k0 = chunk * (SEG * U) + static_cast<int64_t>(seg) * U;
@@ -55,8 +55,8 @@ __global__ __launch_bounds__(256) void swiglu_compress_vec_kernel(const uint4* _
             for (int l = 0; l < L; ++l) {
                 qg[u][l] = make_uint4(0u, 0u, 0u, 0u);
                 qu[u][l] = make_uint4(0u, 0u, 0u, 0u);
-                if (k0 + u < n_sub) {
-                    const int64_t i = (k0 + u) * kVecPerSub + l * P + p;
+                if (k0 + u < n_sub && l * P + p < vps) {
+                    const int64_t i = (k0 + u) * vps + l * P + p;
                     qg[u][l] = load_stream16(&gate[i]);
                     qu[u][l] = load_stream16(&up[i]);
                 }
@@ -81,10 +81,10 @@ __global__ __launch_bounds__(256) void swiglu_compress_vec_kernel(const uint4* _
                     q = make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]),
                                    pack_bf16x2(x[6], x[7]));
                 }
-                if (k0 + u < n_sub) {
+                if (k0 + u < n_sub && l * P + p < vps) {
                     const u32x4_nt out = {q.x, q.y, q.z, q.w};
                     __builtin_nontemporal_store(
-                        out, reinterpret_cast<u32x4_nt*>(&X[(k0 + u) * kVecPerSub + l * P + p]));
+                        out, reinterpret_cast<u32x4_nt*>(&X[(k0 + u) * vps + l * P + p]));
                 }
                 float f[kV];
                 E::unpack(q, f);
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void swiglu_generic_kernel(const typename E::t
 namespace {
 
 template <typename E, int P, int L, int U>
-hipError_t launch_vec(const void* gate, const void* up, const float* v, void* X, void* S, int64_t n_sub,
+hipError_t launch_vec(const void* gate, const void* up, const float* v, void* X, void* S, int64_t n_sub, int vps,
                       const LaunchCfg& cfg, hipStream_t st) {
     constexpr int SEG = kWave / P;
     const int64_t n_chunks = ceil_div(n_sub, static_cast<int64_t>(SEG) * U);
@@ -127,26 +127,25 @@ hipError_t launch_vec(const void* gate, const void* up, const float* v, void* X,
     if (grid > cfg.max_blocks) grid = cfg.max_blocks;
     hipLaunchKernelGGL((swiglu_compress_vec_kernel<E, P, L, U>), dim3(static_cast<unsigned>(grid)), dim3(256), 0, st,
                        static_cast<const uint4*>(gate), static_cast<const uint4*>(up), v, static_cast<uint4*>(X),
-                       static_cast<typename E::type*>(S), n_sub);
+                       static_cast<typename E::type*>(S), n_sub, vps);
     return hipGetLastError();
 }
 
 template <typename E>
 hipError_t swiglu_any(const void* gate, const void* up, const float* v, void* X, void* S, int64_t n_sub, int64_t d,
                       bool vec_ok, const LaunchCfg& cfg, hipStream_t st) {
-    if (vec_ok && d % E::kPerVec == 0) {
-        switch (static_cast<int>(d / E::kPerVec)) {
-            case 1:   return launch_vec<E, 1, 1, 4>(gate, up, v, X, S, n_sub, cfg, st);
-            case 2:   return launch_vec<E, 2, 1, 4>(gate, up, v, X, S, n_sub, cfg, st);
-            case 4:   return launch_vec<E, 4, 1, 4>(gate, up, v, X, S, n_sub, cfg, st);
-            case 8:   return launch_vec<E, 8, 1, 4>(gate, up, v, X, S, n_sub, cfg, st);
-            case 16:  return launch_vec<E, 16, 1, 4>(gate, up, v, X, S, n_sub, cfg, st);
-            case 32:  return launch_vec<E, 32, 1, 4>(gate, up, v, X, S, n_sub, cfg, st);
-            case 64:  return launch_vec<E, 64, 1, 4>(gate, up, v, X, S, n_sub, cfg, st);
-            case 128: return launch_vec<E, 64, 2, 2>(gate, up, v, X, S, n_sub, cfg, st);
-            case 256: return launch_vec<E, 64, 4, 1>(gate, up, v, X, S, n_sub, cfg, st);
-            default:  break;
-        }
+    if (vec_ok && d % E::kPerVec == 0 && d / E::kPerVec <= 256) {
+        // the same lanes-per-sub-token choice as dispatch_compress_vec, so S matches velora_compress bit for bit
+        const int vps = static_cast<int>(d / E::kPerVec);
+        if (vps <= 1) return launch_vec<E, 1, 1, 4>(gate, up, v, X, S, n_sub, vps, cfg, st);
+        if (vps <= 2) return launch_vec<E, 2, 1, 4>(gate, up, v, X, S, n_sub, vps, cfg, st);
+        if (vps <= 4) return launch_vec<E, 4, 1, 4>(gate, up, v, X, S, n_sub, vps, cfg, st);
+        if (vps <= 8) return launch_vec<E, 8, 1, 4>(gate, up, v, X, S, n_sub, vps, cfg, st);
+        if (vps <= 16) return launch_vec<E, 16, 1, 4>(gate, up, v, X, S, n_sub, vps, cfg, st);
+        if (vps <= 32) return launch_vec<E, 32, 1, 4>(gate, up, v, X, S, n_sub, vps, cfg, st);
+        if (vps <= 64) return launch_vec<E, 64, 1, 4>(gate, up, v, X, S, n_sub, vps, cfg, st);
+        if (vps <= 128) return launch_vec<E, 64, 2, 2>(gate, up, v, X, S, n_sub, vps, cfg, st);
+        return launch_vec<E, 64, 4, 1>(gate, up, v, X, S, n_sub, vps, cfg, st);
     }
     const int64_t n = n_sub * d;
     int64_t grid = ceil_div(n, 256 * 4);

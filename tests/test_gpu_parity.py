@@ -35,6 +35,10 @@ COMPRESS_CASES = [
     (301, 64, 8, wl.BF16), (257, 64, 16, wl.BF16), (130, 96, 32, wl.BF16), (4 * 197, 768, 64, wl.BF16),
     (515, 768, 128, wl.BF16), (203, 1024, 256, wl.BF16), (67, 1536, 512, wl.BF16), (41, 2048, 1024, wl.BF16),
     (23, 4096, 2048, wl.BF16),
+    # 16-byte vectors per sub-token not a power of two: the vectorised kernel with idle lanes
+    (203, 72, 24, wl.BF16), (131, 120, 40, wl.BF16), (97, 2 * 344, 344, wl.BF16), (515, 3 * 344, 344, wl.F32),
+    (67, 2 * 776, 776, wl.BF16), (45, 2 * 1032, 1032, wl.BF16), (29, 2040, 2040, wl.BF16), (33, 3 * 12, 12, wl.F32),
+    (21, 2 * 1020, 1020, wl.F32), (150, 11008, 344, wl.BF16),
     # generic kernel: d not a power of two times the vector width, d = 1, d = D
     (50, 60, 12, wl.BF16), (50, 63, 7, wl.F32), (31, 33, 1, wl.BF16), (17, 100, 100, wl.F32),
     (11, 3000, 3000, wl.BF16), (1, 8, 8, wl.BF16), (1, 1, 1, wl.F32),
@@ -60,7 +64,7 @@ def test_compress_matches_oracle(vl, N, D, d, dtype):
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
-@pytest.mark.parametrize("d", [8, 64, 256, 12])
+@pytest.mark.parametrize("d", [8, 64, 256, 12, 24, 344, 1032])
 def test_compress_gather_is_bit_exact(vl, dtype, d):
     # v = e_j: compress degenerates to a gather, so the indexing (group) is
     # checked with no rounding at all.
@@ -125,6 +129,8 @@ def test_projection_is_idempotent_on_gpu(vl):
     (256, 64, 16, wl.F32), (4 * 197, 768, 64, wl.BF16), (1000, 768, 128, wl.BF16), (555, 1024, 256, wl.BF16),
     (300, 2048, 1024, wl.BF16), (64, 4096, 2048, wl.BF16), (513, 96, 8, wl.F32), (100, 60, 12, wl.BF16),
     (77, 63, 7, wl.F32), (40, 33, 1, wl.F32), (3, 3000, 3000, wl.BF16),
+    (700, 72, 24, wl.BF16), (333, 3 * 344, 344, wl.BF16), (210, 2 * 344, 344, wl.F32), (90, 2 * 1032, 1032, wl.BF16),
+    (64, 2040, 2040, wl.BF16),
 ])
 def test_init_v_matches_oracle(vl, N, D, d, dtype):
     M = D // d
@@ -159,6 +165,7 @@ def test_init_v_degenerate(vl):
 @pytest.mark.parametrize("N,D,d,dtype", [
     (4 * 197, 768, 64, wl.BF16), (600, 1024, 256, wl.BF16), (300, 2048, 1024, wl.BF16), (513, 96, 8, wl.F32),
     (256, 64, 16, wl.F32), (100, 60, 12, wl.BF16), (77, 63, 7, wl.F32),
+    (400, 72, 24, wl.BF16), (333, 3 * 344, 344, wl.BF16), (210, 2 * 344, 344, wl.F32), (90, 2 * 1032, 1032, wl.BF16),
 ])
 def test_update_v_and_fused_compress_update(vl, N, D, d, dtype):
     torch = _torch()

@@ -25,7 +25,7 @@ def _inputs(N, D, dtype, seed):
 
 
 CASES = [(256, 64, 16), (197, 768, 64), (130, 1376, 32), (33, 4096, 1024), (7, 2048, 2048), (64, 96, 8), (50, 60, 12),
-         (1, 8, 8), (300, 24, 24)]
+         (1, 8, 8), (300, 24, 24), (97, 2 * 344, 344), (45, 2 * 1032, 1032), (131, 120, 40)]
 
 
 @pytest.mark.parametrize("N,D,d", CASES)
@@ -54,7 +54,8 @@ def test_against_oracle(vl, N, D, d, dtype):
         assert rel_fro(got, S2_exact) <= TOL_F32 and rel_max(got, S2_exact) <= TOL_F32
 
 
-@pytest.mark.parametrize("N,D,d", [(256, 1024, 256), (197, 768, 64), (33, 4096, 1024), (50, 60, 12)])
+@pytest.mark.parametrize("N,D,d", [(256, 1024, 256), (197, 768, 64), (33, 4096, 1024), (50, 60, 12), (97, 688, 344),
+                                    (45, 2064, 1032), (131, 120, 40)])
 def test_same_bits_as_compress_on_the_stored_activation(vl, N, D, d):
     import torch
     M = D // d

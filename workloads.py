@@ -114,7 +114,8 @@ def _mk(name, cfg, dtype, N, D, O, d, x_dist, g_sigma, tid):
 
 def all_shapes() -> List[Shape]:
     """Every layer shape of the five configurations (including the one cell
-    of configuration 5 whose sub-token size does not divide D)."""
+    of configuration 5 whose sub-token size does not divide D), plus three
+    layers at the paper's own LLaMA-7B sub-token count (cfg = 6)."""
     s: List[Shape] = []
     s.append(_mk("cfg1_tiny", 1, F32, 256, 64, 64, 16, "normal", 0.02, 0))
     s.append(_mk("cfg2_vit_fc1", 2, BF16, 64 * 197, 768, 3072, 64, "chan_scale", 0.02, 0))
@@ -135,6 +136,11 @@ def all_shapes() -> List[Shape]:
     # 1024 does not divide 13824; d = 512 keeps the large-d end of the sweep
     # exercised on the down projection.
     s.append(_mk("cfg5_down_d512", 5, BF16, n5, 13824, 5120, 512, "outlier_chan", 0.005, tid))
+    # Beyond the five configurations: the paper's own setting for LLaMA-7B, 32 sub-tokens
+    # per token ("M = D/32", Sec. 5.2 and its sub-token-size ablation), on configuration 4's layers.
+    s.append(_mk("paper7b_attn_m32", 6, BF16, n4, 4096, 4096, 128, "student_t4", 0.005, 0))
+    s.append(_mk("paper7b_up_m32", 6, BF16, n4, 4096, 11008, 128, "student_t4", 0.005, 1))
+    s.append(_mk("paper7b_down_m32", 6, BF16, n4, 11008, 4096, 344, "student_t4", 0.005, 2))
     return s
 
 
