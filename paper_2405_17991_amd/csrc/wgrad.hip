@@ -242,7 +242,9 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
         } else {
 #pragma unroll
             for (int a = 0; a < GT; ++a) {
-                const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, s_voff[0][0] + a * 1024u, 0, 0);
+                // tiles past the last real one are not in the array: an offset no descriptor covers reads zeros
+                const uint32_t so = tile0 + a < tiles_packed ? s_voff[0][0] + a * 1024u : 0xFFFFFFFFu;
+                const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, so, 0, 0);
                 sg.s[a][0] = x.x; sg.s[a][1] = x.y; sg.s[a][2] = x.z; sg.s[a][3] = x.w;
             }
         }
@@ -333,30 +335,38 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
 // Kernel 1, MFMA path for many group tiles (8, 12 or 16 per block).
 //
 // With that many tiles a wave cannot hold accumulators for all of them, so the
-// four waves split the tiles (GTW each) and all walk every 32-token step of the
-// block's range.  They then need the same G tile (32 tokens x 128 features,
-// 8 KB): each wave fetches a quarter of it from HBM (its lanes' rows 2w, 2w+1
-// of every 8-row group) into a register ring NG steps deep, publishes it in a
-// double-buffered LDS tile, and after one barrier every wave reads the whole
-// tile back in the lane layout of the in-register transpose.  G is thus read
-// once per block, S (packed fragments) once per 128 output features.  A wave
-// only carries 2 KB of G per step, so the G ring is deep (NG = 8); S comes from
-// L2 and needs a shorter ring (NS).  What bounds this kernel is the number of
-// cache-line requests a CU can have outstanding below its L1 (about 64): per
-// step a block asks for 64 lines of G and 32 * GTW lines of S, so at 16 tiles
-// two thirds of the requests are S re-reads served by L2.
-// grid = (o tiles of 128, splits, g chunks of 64*GTW groups)
+// block's NW waves (4 or 8) split the tiles (GTW each) and all walk every
+// 32-token step of the block's range.  They then need the same G tile
+// (32 tokens x 128 features, 8 KB): each wave fetches its share of it from HBM
+// (8 / NW rows of every 8-row group) into a register ring NG steps deep,
+// publishes it in a double-buffered LDS tile, and after one barrier every wave
+// reads the whole tile back in the lane layout of the in-register transpose.
+// G is thus read once per block, S (packed fragments) once per 128 output
+// features.  A wave only carries 1-2 KB of G per step, so the G ring is deep
+// (NG = 8); S comes from L2 and needs a shorter ring (NS).
+// A wave that waits to issue loads (a CU sustains a bounded number of
+// outstanding cache-line requests; per step a block asks for 64 lines of G and
+// 8 lines of S per tile) issues no MFMAs meanwhile, so with one wave per SIMD
+// the two times add up.  At 16 tiles the block therefore has eight waves of two
+// tiles each, two per SIMD (under 256 registers), and one wave's MFMAs fill the
+// other's stalls: measured 57 us against 64 us for four waves of four tiles at
+// N = 16384, O = 5120, M = 216.  At 8 and 12 tiles eight waves measured no
+// faster than four.  Covering 256 features per block (half the S re-reads)
+// measured no faster either.
+// grid = (o tiles of 128, splits, g chunks of NW*GTW tiles)
 // ---------------------------------------------------------------------------
-template <int GTW, int NG, int NS>
-__global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint16_t* __restrict__ G,
+template <int GTW, int NW, int NG, int NS>
+__global__ __launch_bounds__(NW * 64) void wgrad_partial_shared_g_kernel(const uint16_t* __restrict__ G,
                                                                     const void* __restrict__ Spk,
                                                                     float* __restrict__ partial, int64_t N,
                                                                     int64_t O, int64_t M, int64_t Mp,
                                                                     int64_t rows_per_split, int64_t tiles_packed) {
     static_assert(NG % 2 == 0, "the LDS buffer index must be a compile-time function of the ring slot");
     static_assert(NG % NS == 0, "the S ring slot must be a compile-time function of the G ring slot");
+    static_assert(NW == 4 || NW == 8, "a wave fetches 8 / NW rows of every 8-row group");
     constexpr int CW = 8;
     constexpr int OT = 16 * CW;
+    constexpr int RPW = 8 / NW;                        // rows of every 8-row group this wave fetches
     __shared__ uint4 gtile[2][kStep][16];              // [buffer][token][16-byte chunk of 8 features]
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -365,27 +375,34 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
     const int jj = lane & 15;
     const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
     const int split = blockIdx.y;
-    const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * (GTW * kWavesPerBlock) + w * GTW;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * (GTW * NW) + w * GTW;
     const int64_t kb = static_cast<int64_t>(split) * rows_per_split;
     int64_t ke = kb + rows_per_split;
     if (ke > N) ke = N;
     const int rows = static_cast<int>(ke - kb);
     const int n_steps = (rows + kStep - 1) / kStep;
-    const bool col_ok = o0 + jj * CW < O;
 
     const uint32_t row_bytes = static_cast<uint32_t>(O) * 2u;
-    uint32_t voff[2];                                  // this wave's two rows of every 8-row group
+    const bool col_ok = o0 + jj * CW < O;
+    uint32_t voff[RPW];                                // this wave's rows of every 8-row group
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-        voff[i] = col_ok ? static_cast<uint32_t>(q * 8 + 2 * w + i) * row_bytes + static_cast<uint32_t>(jj * CW * 2)
+    for (int i = 0; i < RPW; ++i)
+        voff[i] = col_ok ? static_cast<uint32_t>(q * 8 + RPW * w + i) * row_bytes + static_cast<uint32_t>(jj * CW * 2)
                          : 0xFFFFFFFFu;
     const char* gblock = reinterpret_cast<const char*>(G) + (kb * O + o0) * 2;
     const uint32_t gblock_bytes = static_cast<uint32_t>(rows) * row_bytes - static_cast<uint32_t>(o0 * 2);
     const uint32_t step_bytes = static_cast<uint32_t>(kStep) * row_bytes;
+    // S fragments of this wave's tiles; tiles past the last real one are never fetched (they read as zeros)
     const uint32_t s_step_bytes = static_cast<uint32_t>(tiles_packed) * 1024u;
-    const char* sblock = reinterpret_cast<const char*>(Spk) + ((kb / kStep) * tiles_packed + tile0) * 1024;
-    const uint32_t sblock_bytes = static_cast<uint32_t>(n_steps) * s_step_bytes - static_cast<uint32_t>(tile0) * 1024u;
-    const uint32_t s_voff = static_cast<uint32_t>(lane) * 16u;
+    const bool any_tile = tile0 < tiles_packed;
+    const char* sblock = reinterpret_cast<const char*>(Spk) +
+                         ((kb / kStep) * tiles_packed + (any_tile ? tile0 : 0)) * 1024;
+    const uint32_t sblock_bytes =
+        any_tile ? static_cast<uint32_t>(n_steps) * s_step_bytes - static_cast<uint32_t>(tile0) * 1024u : 0u;
+    uint32_t s_voff[GTW];
+#pragma unroll
+    for (int a = 0; a < GTW; ++a)
+        s_voff[a] = tile0 + a < tiles_packed ? static_cast<uint32_t>(lane) * 16u + a * 1024u : 0xFFFFFFFFu;
 
     f32x4 acc[GTW][CW];
 #pragma unroll
@@ -393,15 +410,15 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
 #pragma unroll
         for (int c = 0; c < CW; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 gr[NG][2];
+    u32x4 gr[NG][RPW];
     u32x4 sr[NS][GTW];
-    auto load_g_step = [&](u32x4 (&dst)[2], int t) {
+    auto load_g_step = [&](u32x4 (&dst)[RPW], int t) {
         const uint32_t off = static_cast<uint32_t>(t) * step_bytes;
         const uint32_t left = t < n_steps ? gblock_bytes - off : 0u;
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char*>(gblock + (t < n_steps ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[i], 0, kStreamAux);
+        for (int i = 0; i < RPW; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[i], 0, kStreamAux);
     };
     auto load_s_step = [&](u32x4 (&dst)[GTW], int t) {
         const uint32_t off = static_cast<uint32_t>(t) * s_step_bytes;
@@ -409,7 +426,7 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char*>(sblock + (left ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
 #pragma unroll
-        for (int a = 0; a < GTW; ++a) dst[a] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, s_voff + a * 1024u, 0, 0);
+        for (int a = 0; a < GTW; ++a) dst[a] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, s_voff[a], 0, 0);
     };
 
 #pragma unroll
@@ -417,15 +434,15 @@ __global__ __launch_bounds__(256) void wgrad_partial_shared_g_kernel(const uint1
 #pragma unroll
     for (int s = 0; s < NS; ++s) load_s_step(sr[s], s);
     // Software pipeline: while the matrix pipe works on step t, the wave
-    // publishes its quarter of step t+1, reads the whole tile t+1 back and
+    // publishes its share of step t+1, reads the whole tile t+1 back and
     // transposes it, so LDS latency and the v_perm work hide under the MFMAs.
     // One barrier per step is enough with two LDS buffers: a wave writes
     // buffer (t+1)&1 only after the barrier of step t-1, which every wave
     // passes with its reads of tile t-1 already in registers.
-    auto publish = [&](const u32x4 (&src)[2], int buf) {
+    auto publish = [&](const u32x4 (&src)[RPW], int buf) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            gtile[buf][q * 8 + 2 * w + i][jj] = make_uint4(src[i].x, src[i].y, src[i].z, src[i].w);
+        for (int i = 0; i < RPW; ++i)
+            gtile[buf][q * 8 + RPW * w + i][jj] = make_uint4(src[i].x, src[i].y, src[i].z, src[i].w);
     };
     auto read_tile = [&](RawRow<4> (&rowsv)[8], int buf) {
 #pragma unroll
@@ -675,44 +692,61 @@ int env_int(const char* name, int fallback) {
 }
 
 struct MfmaChoice {
-    int cw, gt, chunks;   // cw == 0: the MFMA path cannot take this call
+    int cw, gt, nw, chunks;   // cw == 0: the MFMA path cannot take this call
+    bool shared;
 };
 
-// 16-group tiles per block: the smallest supported count that covers M, else
-// chunks of 16 tiles.  Up to 6 tiles the block's waves alternate token steps;
-// 8, 12 and 16 tiles are split between the waves (2, 3, 4 each).  Depends on M
-// only, so the workspace query can use it.
-void tiles_for(int64_t M, int* gt, int64_t* chunks) {
+// How a block covers the group axis.  Depends on M only, so the workspace query
+// can use it.
+//   gt      16-group tiles per block: the smallest supported count that covers M,
+//           else chunks of 16 tiles
+//   shared  the block's nw waves split the tiles (gt / nw each) and share every G
+//           tile through LDS; otherwise each of four waves holds all gt tiles and
+//           the waves alternate token steps
+struct Tiling {
+    int gt, nw;
+    bool shared;
+    int64_t chunks;
+};
+
+Tiling tiling_for(int64_t M) {
     static const int kSupported[] = {1, 2, 3, 4, 5, 6, 8, 12, 16};
     const int64_t need = ceil_div(M, 16);
+    Tiling t{16, 8, true, ceil_div(need, 16)};
     if (need <= 16) {
         for (int g : kSupported)
-            if (g >= need) { *gt = g; *chunks = 1; return; }
+            if (g >= need) { t.gt = g; t.chunks = 1; break; }
+        t.shared = t.gt >= 8;
+        t.nw = t.gt == 16 ? 8 : 4;
     }
-    *gt = 16;
-    *chunks = ceil_div(need, 16);
+    // tuning aid: gt * 10 + waves per block (0 = the per-wave kernel)
+    const int forced = env_int("VELORA_WGRAD_TILING", 0);
+    if (forced > 0 && need <= forced / 10) {
+        t.gt = forced / 10; t.nw = forced % 10; t.shared = t.nw != 0; t.chunks = 1;
+    }
+    return t;
 }
 
 // S operand: the [N, M] array itself (direct gather, at most three group tiles:
 // beyond that the 8 two-byte loads per tile and step cost more registers and
 // issue slots than the packing pre-pass does time) or the packed fragment array.
-bool direct_s(int gt) { return gt <= 3; }
+bool direct_s(const Tiling& t) { return !t.shared && t.gt <= 3; }
 
 MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan) {
-    MfmaChoice ch{0, 0, 0};
-    int gt; int64_t chunks;
-    tiles_for(M, &gt, &chunks);
+    MfmaChoice ch{0, 0, 4, 0, false};
+    const Tiling tl = tiling_for(M);
     // byte offsets inside a block's token range are 32-bit
     if (static_cast<double>(plan.rows_per_split) * static_cast<double>(O) * 2.0 >= 2147483648.0) return ch;
     if (static_cast<double>(plan.rows_per_split / kStep + 1) * static_cast<double>(plan.tiles_packed) * 1024.0 >=
         2147483648.0)
         return ch;
-    if (chunks > 65535) return ch;
+    if (tl.chunks > 65535) return ch;
     if (static_cast<double>(plan.rows_per_split) * static_cast<double>(M) * 2.0 >= 2147483648.0) return ch;
     int cw = 8;
     while (cw >= 4 && (O % cw != 0 || g_align < 2 * cw)) cw >>= 1;
     if (cw < 4) return ch;
-    ch.cw = cw; ch.gt = gt; ch.chunks = static_cast<int>(chunks);
+    ch.cw = cw; ch.gt = tl.gt; ch.nw = tl.nw; ch.chunks = static_cast<int>(tl.chunks);
+    ch.shared = tl.shared && cw == 8;     // 8-byte G loads: the per-wave kernel with the same tiles
     return ch;
 }
 
@@ -731,31 +765,33 @@ hipError_t launch_mfma(const void* G, const void* s_operand, float* partial, int
     if (ch.cw == CW && ch.gt == GT)           \
         return launch_mfma<CW, GT, NST, DIRECT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
 
-template <int GTW, int NG, int NS>
+template <int GTW, int NW, int NG, int NS>
 hipError_t launch_shared_g(const void* G, const void* s_operand, float* partial, int64_t N, int64_t O, int64_t M,
                            const WgradPlan& plan, int chunks, hipStream_t st) {
     dim3 grid(static_cast<unsigned>(ceil_div(O, 128)), static_cast<unsigned>(plan.splits),
               static_cast<unsigned>(chunks));
-    hipLaunchKernelGGL((wgrad_partial_shared_g_kernel<GTW, NG, NS>), grid, dim3(256), 0, st,
+    hipLaunchKernelGGL((wgrad_partial_shared_g_kernel<GTW, NW, NG, NS>), grid, dim3(NW * 64), 0, st,
                        static_cast<const uint16_t*>(G), s_operand, partial, N, O, M, plan.Mp, plan.rows_per_split,
                        plan.tiles_packed);
     return hipGetLastError();
 }
 
-#define VELORA_SHARED_G_CASE(TILES, GTW, NG, NS) \
-    if (ch.cw == 8 && ch.gt == TILES)            \
-        return launch_shared_g<GTW, NG, NS>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
+#define VELORA_SHARED_G_CASE(TILES, NW, NG, NS)                  \
+    if (ch.shared && ch.gt == TILES && ch.nw == NW)              \
+        return launch_shared_g<TILES / NW, NW, NG, NS>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
 
 hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_operand, float* partial, int64_t N,
                          int64_t O, int64_t M, const WgradPlan& plan, hipStream_t st, bool* handled) {
     *handled = true;
+    VELORA_SHARED_G_CASE(8, 4, 8, 4) VELORA_SHARED_G_CASE(12, 4, 8, 4) VELORA_SHARED_G_CASE(16, 4, 8, 4)
+    VELORA_SHARED_G_CASE(8, 8, 8, 4) VELORA_SHARED_G_CASE(16, 8, 8, 4)
+    if (ch.shared) { *handled = false; return hipSuccess; }
     // Ring depth 1 everywhere it was measured (2-4 were 1-5 us slower on every layer
     // shape): a CU sustains a fixed number of outstanding cache-line requests, which
     // four waves with one 32-token step each already exceed, and deeper rings only
     // cost registers.
     VELORA_MFMA_CASE(8, 1, 1, true) VELORA_MFMA_CASE(8, 2, 1, true) VELORA_MFMA_CASE(8, 3, 1, true)
     VELORA_MFMA_CASE(8, 4, 1, false) VELORA_MFMA_CASE(8, 5, 1, false) VELORA_MFMA_CASE(8, 6, 1, false)
-    VELORA_SHARED_G_CASE(8, 2, 8, 4) VELORA_SHARED_G_CASE(12, 3, 8, 4) VELORA_SHARED_G_CASE(16, 4, 8, 4)
     VELORA_MFMA_CASE(4, 1, 1, true) VELORA_MFMA_CASE(4, 2, 1, true) VELORA_MFMA_CASE(4, 3, 1, true)
     VELORA_MFMA_CASE(4, 4, 1, false) VELORA_MFMA_CASE(4, 5, 1, false) VELORA_MFMA_CASE(4, 6, 1, false)
     VELORA_MFMA_CASE(4, 8, 1, false) VELORA_MFMA_CASE(4, 12, 1, false) VELORA_MFMA_CASE(4, 16, 1, false)
@@ -816,10 +852,10 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     WgradPlan p;
     p.Mp = ceil_div(M, 4) * 4;
     const int64_t in_b = is_bf16 ? 2 : 4;
-    int gt = 1;
-    int64_t chunks = 1;
-    if (is_bf16) tiles_for(M, &gt, &chunks);
-    const int64_t o_tiles = ceil_div(O, 128) * chunks;
+    Tiling tl{1, 4, false, 1};
+    if (is_bf16) tl = tiling_for(M);
+    const int gt = tl.gt;
+    const int64_t o_tiles = ceil_div(O, 128) * tl.chunks;
     // Each split writes a partial tile that the second kernel reads back.
     const double per_split = static_cast<double>(O) * p.Mp * 8.0;
     const int64_t min_rows = is_bf16 ? 256 : 32;   // the plain-FMA kernel is latency-bound per token
@@ -870,8 +906,8 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     p.partial_bytes = (p.partial_bytes + 255) / 256 * 256;
     p.tiles_packed = 0;
     p.packed_bytes = 0;
-    if (is_bf16 && !direct_s(gt)) {
-        p.tiles_packed = gt * chunks;
+    if (is_bf16 && !direct_s(tl)) {
+        p.tiles_packed = ceil_div(M, 16);          // real tiles only: blocks never fetch the padding
         p.packed_bytes = static_cast<size_t>(ceil_div(N, kStep)) * static_cast<size_t>(p.tiles_packed) * 1024;
     }
     p.ws_bytes = p.partial_bytes + p.packed_bytes;
@@ -890,7 +926,7 @@ hipError_t launch_partials(const void* G, const void* S, int64_t N, int64_t O, i
         const MfmaChoice ch = choose_mfma(O, M, g_align, plan);
         if (ch.cw != 0) {
             const void* s_operand = S;
-            if (!direct_s(ch.gt)) {
+            if (plan.tiles_packed > 0) {
                 uint4* packed = reinterpret_cast<uint4*>(static_cast<char*>(ws) + plan.partial_bytes);
                 const int64_t total = ceil_div(N, kStep) * plan.tiles_packed * 64;
                 if (phases & 1)
