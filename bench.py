@@ -207,6 +207,25 @@ def _swiglu_record(vl, torch, sh, v, dev, launches):
             "frac": round(nbytes / us * 1e-3 / HBM_PEAK_GBPS, 4)}
 
 
+def _linear_record(vl, torch, sh, v, dev, launches):
+    """The layer's forward with compress inside the GEMM (not part of `value`):
+    Y = X W^T as a bf16 MFMA kernel that also forms S from its tiles of X.  Next
+    to it, for scale only, the vendor GEMM followed by velora_compress."""
+    launches = max(5, min(launches, 40))
+    X = torch.randn((sh.N, sh.D), device=dev).to(torch.bfloat16)
+    W = (torch.randn((sh.O, sh.D), device=dev) * sh.D ** -0.5).to(torch.bfloat16)
+    Y = torch.empty((sh.N, sh.O), device=dev, dtype=torch.bfloat16)
+    S = torch.empty((sh.N, sh.M), device=dev, dtype=torch.bfloat16)
+    us = _event_avg_us(torch, lambda i: vl.velora_linear_compress(X, W, v, sh.M, Y=Y, S=S), launches)
+    Wt = W.t()
+    ref = _event_avg_us(torch, lambda i: (torch.matmul(X, Wt, out=Y), vl.velora_compress(X, v, sh.M, S=S)), launches)
+    flops = 2.0 * sh.N * sh.O * sh.D + 2.0 * sh.N * sh.D
+    return {"kernel": "linear_compress_mfma_kernel", "bound": "mfma", "avg_us": round(us, 1), "algorithmic_flops": flops,
+            "achieved": round(flops / us * 1e-6, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(flops / us * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "vendor_gemm_plus_compress_us": round(ref, 1)}
+
+
 def _rmsnorm_record(vl, torch, wl, dev, launches):
     """Producer-side fusion for the attention projections' input (LLaMA-7B-like:
     N=16384, D=4096, d=256): X = RMSNorm(H) written and compressed in one pass."""
@@ -425,6 +444,8 @@ def main():
         out["swiglu_compress"] = _swiglu_record(vl, torch, sh, v, dev, args.steps)
         torch.cuda.empty_cache()
         out["rmsnorm_compress"] = _rmsnorm_record(vl, torch, wl, dev, args.steps)
+        torch.cuda.empty_cache()
+        out["linear_compress"] = _linear_record(vl, torch, sh, v, dev, args.steps)
     torch.cuda.empty_cache()
 
     # ---------------- every layer shape of the five configurations

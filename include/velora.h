@@ -152,6 +152,26 @@ velora_status velora_swiglu_compress(const void* gate, const void* up, const flo
                                      int64_t M, velora_dtype dt, void* X, void* S, velora_stream stream);
 
 /*
+ * The forward of the layer with the compression taken from the same pass (Sec. 3.2
+ * and Algorithm 1, forward: the output is the dense product, next to it
+ * compress(group(input), v) is what is kept for backward):
+ *     Y[n, o] = sum_c X[n, c] * W[o, c]         (W in the nn.Linear layout [O, D])
+ *     S[n, g] = sum_{j<d} X[n, g*d + j] * v[j]
+ * Products of the stored inputs accumulated in float32, one RNE rounding when Y
+ * and S are stored in dtype dt.  For bf16 inputs with 16-byte aligned X, W, Y,
+ * D a multiple of 64 and O a multiple of 4 this is one MFMA kernel; when d is
+ * also a multiple of 64 (and at most 2048) S comes out of that kernel, from
+ * the tiles of X it has loaded, so X is read once for both results; there v
+ * enters as the sum of two bf16 numbers (relative error 2^-17, far below the
+ * rounding of S).  Every other case runs a plain FMA kernel for Y and the
+ * compress kernel for S.
+ *   X [N, D], W [O, D] device, dtype dt (read only);  v [d] device float32 (read only)
+ *   Y [N, O], S [N, M] device, dtype dt (written).  O <= 65535 * 64.
+ */
+velora_status velora_linear_compress(const void* X, const void* W, const float* v, int64_t N, int64_t D, int64_t O,
+                                     int64_t M, velora_dtype dt, void* Y, void* S, velora_stream stream);
+
+/*
  * The other producer: the attention projections of an LLaMA block (the paper
  * compresses the value projection's input, Sec. 4) read X = RMSNorm(H),
  *     X[n, j] = H[n, j] / sqrt(mean_j H[n, j]^2 + eps) * gamma[j].

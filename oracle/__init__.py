@@ -223,6 +223,28 @@ def linear(X: np.ndarray, W: np.ndarray, threads: int = 0) -> np.ndarray:
     return Y
 
 
+def _store(x: np.ndarray, dt: int) -> np.ndarray:
+    """float64 -> storage dtype: float32, or bfloat16 bits by round-to-nearest-even of the float32 value."""
+    f = x.astype(np.float32)
+    if dt != DT_BF16:
+        return f
+    b = f.view(np.uint32)
+    return ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def linear_compress(X: np.ndarray, W: np.ndarray, v: np.ndarray, M: int,
+                    threads: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """Algorithm 1's forward as one call: the dense product Y = X @ W^T (W stored
+    [O, D]; "forward compute is preserved") and, next to it, Sec. 3.2's compress of
+    the same X, which is what the layer keeps for backward.  Both from their
+    definitions in float64, then stored in the inputs' dtype.
+    -> (Y_exact float64[N, O], Y_store storage[N, O], S_exact float64[N, M], S_store storage[N, M])
+    """
+    Y_exact = linear(X, W, threads=threads)
+    S_exact, S_store = compress(X, v, M, threads=threads)
+    return Y_exact, _store(Y_exact, _dt(_c(X))), S_exact, S_store
+
+
 def adamw_step_factor(T: np.ndarray, v: np.ndarray, W: np.ndarray, exp_avg: np.ndarray, exp_avg_sq: np.ndarray,
                       lr: float, beta1: float, beta2: float, eps: float, weight_decay: float, step: int,
                       grad_scale: float = 1.0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:

@@ -31,7 +31,7 @@ EXPORTS = [
     "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
     "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_factor",
     "velora_expand_factor", "velora_update_v", "velora_compress_update", "velora_adamw_step_factor",
-    "velora_swiglu_compress", "velora_rmsnorm_compress",
+    "velora_swiglu_compress", "velora_rmsnorm_compress", "velora_linear_compress",
 ]
 
 
@@ -73,6 +73,8 @@ def _load() -> ctypes.CDLL:
     L.velora_expand_factor.restype = ci
     L.velora_swiglu_compress.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, vp]
     L.velora_swiglu_compress.restype = ci
+    L.velora_linear_compress.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, vp]
+    L.velora_linear_compress.restype = ci
     L.velora_rmsnorm_compress.argtypes = [vp, vp, ctypes.c_float, vp, i64, i64, i64, ci, vp, vp, vp]
     L.velora_rmsnorm_compress.restype = ci
     cf = ctypes.c_float
@@ -219,6 +221,32 @@ def velora_swiglu_compress(gate, up, v, M: int, X=None, S=None):
                                     S.data_ptr(), _stream())
     _raise(st, "velora_swiglu_compress")
     return X, S
+
+
+def velora_linear_compress(X, W, v, M: int, Y=None, S=None):
+    """Y = X @ W^T (W is [O, D]) and S = compress(X, v) from one pass over X.  -> (Y, S)"""
+    torch = _torch()
+    _check(X, "X", 2)
+    _check(W, "W", 2)
+    _check(v, "v", 1)
+    if W.dtype != X.dtype or W.shape[1] != X.shape[1]:
+        raise ValueError("W must be [O, D] in X's dtype")
+    if v.dtype != torch.float32:
+        raise TypeError("v must be float32")
+    N, D = X.shape
+    O = W.shape[0]
+    if Y is None:
+        Y = torch.empty((N, O), dtype=X.dtype, device=X.device)
+    if S is None:
+        S = torch.empty((N, max(M, 1)), dtype=X.dtype, device=X.device)
+    _check(Y, "Y", 2)
+    _check(S, "S", 2)
+    if tuple(Y.shape) != (N, O) or Y.dtype != X.dtype or tuple(S.shape) != (N, M) or S.dtype != X.dtype:
+        raise ValueError("Y must be [N, O] and S [N, M] in X's dtype")
+    st = raw.velora_linear_compress(X.data_ptr(), W.data_ptr(), v.data_ptr(), N, D, O, M, _dt(X), Y.data_ptr(),
+                                    S.data_ptr(), _stream())
+    _raise(st, "velora_linear_compress")
+    return Y, S
 
 
 def velora_rmsnorm_compress(H, gamma, eps: float, v, M: int, X=None, S=None):

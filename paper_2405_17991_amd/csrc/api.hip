@@ -193,6 +193,22 @@ velora_status velora_swiglu_compress(const void* gate, const void* up, const flo
                                                      static_cast<hipStream_t>(stream)));
 }
 
+velora_status velora_linear_compress(const void* X, const void* W, const float* v, int64_t N, int64_t D, int64_t O,
+                                     int64_t M, velora_dtype dt, void* Y, void* S, velora_stream stream) {
+    if (!X || !W || !v || !Y || !S) return VELORA_ERR_NULL;
+    if (!dtype_ok(dt)) return VELORA_ERR_DTYPE;
+    if (!shape_ok(N, D, M) || !size_ok(N, D) || D / M > INT32_MAX / 8 || O <= 0 || O > INT64_C(65535) * 64 ||
+        !size_ok(N, O) || !size_ok(O, D))
+        return VELORA_ERR_SHAPE;
+    const int eb = elem_bytes(dt);
+    if (ptr_align(X) < eb || ptr_align(W) < eb || ptr_align(Y) < eb || ptr_align(S) < eb || ptr_align(v) < 4)
+        return VELORA_ERR_ALIGN;
+    const LaunchCfg cfg = current_cfg();
+    const bool align16 = ptr_align(X) >= 16 && ptr_align(W) >= 16 && ptr_align(Y) >= 16;
+    return hip_status(velora::launch_linear_compress(X, W, v, Y, S, N, D, O, M, dt == VELORA_BF16, align16,
+                                                     ptr_align(X) >= 16, cfg, static_cast<hipStream_t>(stream)));
+}
+
 velora_status velora_rmsnorm_compress(const void* H, const float* gamma, float eps, const float* v, int64_t N,
                                       int64_t D, int64_t M, velora_dtype dt, void* X, void* S,
                                       velora_stream stream) {

@@ -27,6 +27,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 // 16-byte load with the streaming (non-temporal) hint: the data is read once.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));   // one MFMA A or B operand (eight k-consecutive bf16)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_stream16(const uint4* p) {
     const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     return make_uint4(q.x, q.y, q.z, q.w);

@@ -33,6 +33,15 @@ hipError_t launch_rmsnorm_compress(const void* H, const float* gamma, const floa
                                    int64_t D, int64_t M, float eps, bool is_bf16, bool vec_ok, const LaunchCfg& cfg,
                                    hipStream_t st);
 
+// ---- linear.hip ----
+// Y[N, O] = X[N, D] * W[O, D]^T stored in the inputs' dtype and S = compress(X, v).  bf16 inputs with 16-byte
+// aligned X, W and Y, D % 64 == 0 and O % 4 == 0 take the MFMA kernel (S inside it when d % 64 == 0 and
+// d <= 2048, else by the compress kernel); everything else a plain FMA kernel plus the compress kernel.
+// s_vec_ok: X is 16-byte aligned (for the compress kernel).  Requires O <= 65535 * 64.
+hipError_t launch_linear_compress(const void* X, const void* W, const float* v, void* Y, void* S, int64_t N, int64_t D,
+                                  int64_t O, int64_t M, bool is_bf16, bool align16, bool s_vec_ok, const LaunchCfg& cfg,
+                                  hipStream_t st);
+
 // ---- init_v.hip ----
 // Workspace layout: [int32 flag | pad to 256 B | mean[d] f64 | slices[8][d] f64 | float partial[rows][d]].
 struct InitVPlan {

@@ -19,8 +19,6 @@
 
 namespace velora {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------
 // Kernel 1, MFMA path (bf16 inputs).
@@ -93,7 +91,6 @@ struct RawRow {
     uint32_t w[NDW];
 };
 
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // CW consecutive bf16 through a buffer descriptor (wave-uniform base in SGPRs,
 // 32-bit per-lane byte offset).  A raw buffer load whose offset is not below

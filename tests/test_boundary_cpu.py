@@ -137,6 +137,19 @@ def test_swiglu_compress_argument_errors(vl):
     assert f(P, P, P + 2, 8, 16, 4, vl.F32, P, P, None) == 4
 
 
+def test_linear_compress_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    f = raw.velora_linear_compress
+    assert f(None, P, P, 8, 16, 4, 4, vl.BF16, P, P, None) == 1
+    assert f(P, P, P, 8, 16, 4, 4, vl.BF16, P, None, None) == 1
+    assert f(P, P, P, 8, 16, 4, 4, 9, P, P, None) == 3
+    assert f(P, P, P, 8, 16, 4, 5, vl.BF16, P, P, None) == 2                    # M does not divide D
+    assert f(P, P, P, 8, 16, 0, 4, vl.BF16, P, P, None) == 2                    # O < 1
+    assert f(P, P, P, 8, 16, 65535 * 64 + 1, 4, vl.BF16, P, P, None) == 2       # O beyond the grid limit
+    assert f(P, P + 1, P, 8, 16, 4, 4, vl.BF16, P, P, None) == 4
+    assert f(P, P, P + 2, 8, 16, 4, 4, vl.F32, P, P, None) == 4
+
+
 def test_rmsnorm_compress_argument_errors(vl):
     from paper_2405_17991_amd.binding import raw
     f = raw.velora_rmsnorm_compress

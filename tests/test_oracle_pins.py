@@ -454,6 +454,39 @@ class TestLinear:
         np.testing.assert_allclose(Y, wl.to_f64(X, dtype) @ wl.to_f64(W, dtype).T, rtol=1e-13, atol=1e-15)
 
 
+class TestLinearCompress:
+    """Algorithm 1's forward as one call: pinned to the library matmul, to a triple loop on a tiny case,
+    and to the already pinned compress."""
+
+    def test_triple_loop_and_library(self):
+        X = _rand((5, 12), 3, wl.BF16); W = _rand((4, 12), 4, wl.BF16)
+        v = wl.random_unit_v(6, 1)
+        Y, Ys, S, Ss = oracle.linear_compress(X, W, v, 2)
+        Xf, Wf = wl.to_f64(X, wl.BF16), wl.to_f64(W, wl.BF16)
+        want = np.zeros((5, 4))
+        for n in range(5):
+            for o in range(4):
+                for c in range(12):
+                    want[n, o] += Xf[n, c] * Wf[o, c]
+        np.testing.assert_allclose(Y, want, rtol=1e-14, atol=1e-300)
+        np.testing.assert_allclose(Y, Xf @ Wf.T, rtol=1e-13, atol=1e-15)
+        assert Ys.dtype == np.uint16 and (Ys == wl.f32_to_bf16_bits(Y.astype(np.float32))).all()
+        S2, Ss2 = oracle.compress(X, v, 2)
+        assert (S == S2).all() and (Ss == Ss2).all()
+        # S[n, g] from the definition, by hand
+        np.testing.assert_allclose(S[2, 1], float(Xf[2, 6:12] @ v.astype(np.float64)), rtol=1e-14)
+
+    def test_identity_and_transposition(self):
+        # W = I gives Y = X; a single 1 at W[o, c] copies column c of X into column o of Y (pins the [O, D] layout)
+        X = _rand((7, 8), 5)
+        v = wl.random_unit_v(4, 2)
+        Y, Ys, _, _ = oracle.linear_compress(X, np.eye(8, dtype=np.float32), v, 2)
+        assert (Y == X.astype(np.float64)).all() and (Ys == X).all()
+        W = np.zeros((3, 8), dtype=np.float32); W[2, 5] = 1.0
+        Y, _, _, _ = oracle.linear_compress(X, W, v, 2)
+        assert (Y[:, 2] == X[:, 5]).all() and (Y[:, :2] == 0).all()
+
+
 # ------------------------------------------------------------------ AdamW on the factored gradient
 class TestAdamWFactor:
     """The fused optimiser step of the factored gradient, pinned to the library
