@@ -220,10 +220,20 @@ def _linear_record(vl, torch, sh, v, dev, launches):
     Wt = W.t()
     ref = _event_avg_us(torch, lambda i: (torch.matmul(X, Wt, out=Y), vl.velora_compress(X, v, sh.M, S=S)), launches)
     flops = 2.0 * sh.N * sh.O * sh.D + 2.0 * sh.N * sh.D
-    return {"kernel": "linear_compress_mfma_kernel", "bound": "mfma", "avg_us": round(us, 1), "algorithmic_flops": flops,
-            "achieved": round(flops / us * 1e-6, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(flops / us * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "vendor_gemm_plus_compress_us": round(ref, 1)}
+    rec = {"kernel": "linear_mfma_kernel<fused S>", "bound": "mfma", "avg_us": round(us, 1), "algorithmic_flops": flops,
+           "achieved": round(flops / us * 1e-6, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+           "frac": round(flops / us * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+           "vendor_gemm_plus_compress_us": round(ref, 1)}
+    # the input gradient of the same layer: dX = G W, W read in its own [O, D] layout
+    G = (torch.randn((sh.N, sh.O), device=dev) * 0.05).to(torch.bfloat16)
+    dX = torch.empty((sh.N, sh.D), device=dev, dtype=torch.bfloat16)
+    us2 = _event_avg_us(torch, lambda i: vl.velora_grad_input(G, W, dX=dX), launches)
+    ref2 = _event_avg_us(torch, lambda i: torch.matmul(G, W, out=dX), launches)
+    fl2 = 2.0 * sh.N * sh.O * sh.D
+    rec["grad_input"] = {"kernel": "linear_mfma_kernel<W as stored>", "avg_us": round(us2, 1),
+                         "achieved": round(fl2 / us2 * 1e-6, 1), "unit": "TFLOP/s",
+                         "frac": round(fl2 / us2 * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4), "vendor_gemm_us": round(ref2, 1)}
+    return rec
 
 
 def _rmsnorm_record(vl, torch, wl, dev, launches):

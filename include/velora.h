@@ -172,6 +172,20 @@ velora_status velora_linear_compress(const void* X, const void* W, const float* 
                                      int64_t M, velora_dtype dt, void* Y, void* S, velora_stream stream);
 
 /*
+ * The other half of the layer's backward (Algorithm 1, backward:
+ * grad_input = grad_output @ weight; it needs neither the input nor S):
+ *     dX[n, c] = sum_o G[n, o] * W[o, c]
+ * Products of the stored inputs accumulated in float32, one RNE rounding when dX
+ * is stored in dtype dt.  bf16 with 16-byte aligned pointers, O a multiple of 64
+ * and D a multiple of 8 runs the MFMA kernel of velora_linear_compress with W
+ * read in its own [O, D] layout (transposed in registers); every other case a
+ * plain FMA kernel.
+ *   G [N, O], W [O, D] device, dtype dt (read only);  dX [N, D] device, dtype dt (written).  D <= 65535 * 64.
+ */
+velora_status velora_grad_input(const void* G, const void* W, int64_t N, int64_t O, int64_t D, velora_dtype dt,
+                                void* dX, velora_stream stream);
+
+/*
  * The other producer: the attention projections of an LLaMA block (the paper
  * compresses the value projection's input, Sec. 4) read X = RMSNorm(H),
  *     X[n, j] = H[n, j] / sqrt(mean_j H[n, j]^2 + eps) * gamma[j].

@@ -245,6 +245,21 @@ def linear_compress(X: np.ndarray, W: np.ndarray, v: np.ndarray, M: int,
     return Y_exact, _store(Y_exact, _dt(_c(X))), S_exact, S_store
 
 
+def grad_input(G: np.ndarray, W: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Algorithm 1, backward: grad_input = grad_output @ weight, dX[n, c] = sum_o G[n, o] * W[o, c]
+    with W stored [O, D]; float64 (numpy's matmul on the widened inputs), then stored in the inputs' dtype.
+    -> (dX_exact float64[N, D], dX_store storage[N, D])"""
+    G, W = _c(G), _c(W)
+    assert G.shape[1] == W.shape[0] and _dt(G) == _dt(W)
+    if _dt(G) == DT_BF16:
+        g = (G.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        w = (W.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    else:
+        g, w = G.astype(np.float64), W.astype(np.float64)
+    dX = g @ w
+    return dX, _store(dX, _dt(G))
+
+
 def adamw_step_factor(T: np.ndarray, v: np.ndarray, W: np.ndarray, exp_avg: np.ndarray, exp_avg_sq: np.ndarray,
                       lr: float, beta1: float, beta2: float, eps: float, weight_decay: float, step: int,
                       grad_scale: float = 1.0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:

@@ -27,19 +27,28 @@ from . import binding as _b
 
 
 class VeLoRALinearFunction(torch.autograd.Function):
-    """``forward(input[..., D], weight[O, D], v[d], M) -> out[..., O]``."""
+    """``forward(input[..., D], weight[O, D], v[d], M, own_gemm=False) -> out[..., O]``.
+
+    ``own_gemm``: run the two dense products in this package's kernels as well
+    (``velora_linear_compress`` forms the output and S from one pass over the
+    input; ``velora_grad_input`` the input gradient) instead of the vendor GEMM.
+    """
 
     @staticmethod
-    def forward(ctx, input, weight, v, M):
+    def forward(ctx, input, weight, v, M, own_gemm=False):
         D = input.shape[-1]
         x2 = input.reshape(-1, D)
         if not x2.is_contiguous():
             x2 = x2.contiguous()
-        out = torch.matmul(x2, weight.t())
-        S = _b.velora_compress(x2, v, M)          # the only activation kept for backward
+        if own_gemm:
+            out, S = _b.velora_linear_compress(x2, weight.detach().contiguous(), v, M)
+        else:
+            out = torch.matmul(x2, weight.t())
+            S = _b.velora_compress(x2, v, M)      # the only activation kept for backward
         ctx.save_for_backward(S, weight, v)
         ctx.in_shape = input.shape
         ctx.needs_in = ctx.needs_input_grad[0]
+        ctx.own_gemm = own_gemm
         return out.reshape(*input.shape[:-1], weight.shape[0])
 
     @staticmethod
@@ -51,11 +60,14 @@ class VeLoRALinearFunction(torch.autograd.Function):
             g2 = g2.contiguous()
         grad_input = None
         if ctx.needs_in:
-            grad_input = torch.matmul(g2, weight).reshape(ctx.in_shape)
+            if ctx.own_gemm:
+                grad_input = _b.velora_grad_input(g2, weight.detach().contiguous()).reshape(ctx.in_shape)
+            else:
+                grad_input = torch.matmul(g2, weight).reshape(ctx.in_shape)
         grad_weight = None
         if ctx.needs_input_grad[1]:
             grad_weight = _b.velora_weight_grad(g2, S, v, D, dw_dtype=weight.dtype)
-        return grad_input, grad_weight, None, None
+        return grad_input, grad_weight, None, None, None
 
 
 class VeLoRALinear(torch.nn.Module):
@@ -66,10 +78,12 @@ class VeLoRALinear(torch.nn.Module):
     training mode, then fixed and saved with the module's state.
     """
 
-    def __init__(self, in_features: int, out_features: int, sub_token_size: int, device=None, dtype=None):
+    def __init__(self, in_features: int, out_features: int, sub_token_size: int, device=None, dtype=None,
+                 own_gemm: bool = False):
         super().__init__()
         if in_features % sub_token_size:
             raise ValueError("sub_token_size must divide in_features")
+        self.own_gemm = own_gemm
         self.in_features, self.out_features, self.d = in_features, out_features, sub_token_size
         self.M = in_features // sub_token_size
         w = torch.empty((out_features, in_features), device=device, dtype=dtype)
@@ -87,7 +101,7 @@ class VeLoRALinear(torch.nn.Module):
     def forward(self, input: torch.Tensor) -> torch.Tensor:
         if not bool(self.v_ready):
             self.init_v(input.detach())
-        return VeLoRALinearFunction.apply(input, self.weight, self.v, self.M)
+        return VeLoRALinearFunction.apply(input, self.weight, self.v, self.M, self.own_gemm)
 
 
 def saved_activation_bytes(N: int, D: int, d: int, elem_bytes: int = 2) -> dict:

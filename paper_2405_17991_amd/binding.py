@@ -31,7 +31,7 @@ EXPORTS = [
     "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
     "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_factor",
     "velora_expand_factor", "velora_update_v", "velora_compress_update", "velora_adamw_step_factor",
-    "velora_swiglu_compress", "velora_rmsnorm_compress", "velora_linear_compress",
+    "velora_swiglu_compress", "velora_rmsnorm_compress", "velora_linear_compress", "velora_grad_input",
 ]
 
 
@@ -75,6 +75,8 @@ def _load() -> ctypes.CDLL:
     L.velora_swiglu_compress.restype = ci
     L.velora_linear_compress.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, vp]
     L.velora_linear_compress.restype = ci
+    L.velora_grad_input.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp]
+    L.velora_grad_input.restype = ci
     L.velora_rmsnorm_compress.argtypes = [vp, vp, ctypes.c_float, vp, i64, i64, i64, ci, vp, vp, vp]
     L.velora_rmsnorm_compress.restype = ci
     cf = ctypes.c_float
@@ -247,6 +249,25 @@ def velora_linear_compress(X, W, v, M: int, Y=None, S=None):
                                     S.data_ptr(), _stream())
     _raise(st, "velora_linear_compress")
     return Y, S
+
+
+def velora_grad_input(G, W, dX=None):
+    """dX = G @ W (G is [N, O], W is [O, D]): the input gradient of the layer.  -> dX [N, D]"""
+    torch = _torch()
+    _check(G, "G", 2)
+    _check(W, "W", 2)
+    if W.dtype != G.dtype or W.shape[0] != G.shape[1]:
+        raise ValueError("W must be [O, D] in G's dtype")
+    N, O = G.shape
+    D = W.shape[1]
+    if dX is None:
+        dX = torch.empty((N, D), dtype=G.dtype, device=G.device)
+    _check(dX, "dX", 2)
+    if tuple(dX.shape) != (N, D) or dX.dtype != G.dtype:
+        raise ValueError("dX must be [N, D] in G's dtype")
+    st = raw.velora_grad_input(G.data_ptr(), W.data_ptr(), N, O, D, _dt(G), dX.data_ptr(), _stream())
+    _raise(st, "velora_grad_input")
+    return dX
 
 
 def velora_rmsnorm_compress(H, gamma, eps: float, v, M: int, X=None, S=None):

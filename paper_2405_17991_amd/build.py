@@ -38,13 +38,44 @@ def _stale(target: str, deps: List[str]) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+# Kernels whose loops count outstanding vector-memory operations by hand (s_waitcnt vmcnt(n)): a register
+# spill inside them would add scratch loads and stores to that count and break the waits, so the build
+# fails if the compiler reports any spill or scratch use for them.
+NO_SPILL = {"linear.hip": "linear_mfma_kernel"}
+
+
+def _check_no_spill(src: str, remarks: str) -> None:
+    name, bad = None, []
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif name and NO_SPILL[src] in name:
+            for key in ("VGPRs Spill:", "SGPRs Spill:", "ScratchSize [bytes/lane]:"):
+                if key in line and int(line.split(key)[1].split()[0]) != 0:
+                    bad.append(f"{name}: {key} {line.split(key)[1].split()[0]}")
+    if bad:
+        raise RuntimeError(f"{src}: kernels with hand-counted waits must not spill:\n" + "\n".join(bad))
+
+
 def _compile(src: str, force: bool) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
     if force or _stale(obj, [path] + HEADERS):
         cmd = [HIPCC] + FLAGS + ["-c", path, "-o", obj]
+        if src in NO_SPILL:
+            cmd.append("-Rpass-analysis=kernel-resource-usage")
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if src in NO_SPILL and r.returncode == 0:
+            _check_no_spill(src, r.stdout)
+        kept, skip = [], 0
+        for l in r.stdout.splitlines():        # drop the resource remarks with their two source-context lines
+            if "-Rpass-analysis=kernel-resource-usage" in l:
+                skip = 2
+            elif skip:
+                skip -= 1
+            elif "packed-fp32-ops" not in l:
+                kept.append(l)
+        out = "\n".join(kept)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed for {src}:\n{out}")
         if out.strip():

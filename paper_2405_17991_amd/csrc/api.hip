@@ -209,6 +209,19 @@ velora_status velora_linear_compress(const void* X, const void* W, const float* 
                                                      ptr_align(X) >= 16, cfg, static_cast<hipStream_t>(stream)));
 }
 
+velora_status velora_grad_input(const void* G, const void* W, int64_t N, int64_t O, int64_t D, velora_dtype dt,
+                                void* dX, velora_stream stream) {
+    if (!G || !W || !dX) return VELORA_ERR_NULL;
+    if (!dtype_ok(dt)) return VELORA_ERR_DTYPE;
+    if (N <= 0 || O <= 0 || D <= 0 || D > INT64_C(65535) * 64 || !size_ok(N, O) || !size_ok(N, D) || !size_ok(O, D))
+        return VELORA_ERR_SHAPE;
+    const int eb = elem_bytes(dt);
+    if (ptr_align(G) < eb || ptr_align(W) < eb || ptr_align(dX) < eb) return VELORA_ERR_ALIGN;
+    const bool align16 = ptr_align(G) >= 16 && ptr_align(W) >= 16 && ptr_align(dX) >= 16;
+    return hip_status(velora::launch_grad_input(G, W, dX, N, O, D, dt == VELORA_BF16, align16,
+                                                static_cast<hipStream_t>(stream)));
+}
+
 velora_status velora_rmsnorm_compress(const void* H, const float* gamma, float eps, const float* v, int64_t N,
                                       int64_t D, int64_t M, velora_dtype dt, void* X, void* S,
                                       velora_stream stream) {

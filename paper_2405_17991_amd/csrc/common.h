@@ -85,4 +85,27 @@ __device__ __forceinline__ float group_sum_rt(float x, int P) {
 
 __host__ __device__ constexpr int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Eight rows of an 8 x (2*NDW) block of 16-bit values, one row per register group, and its in-register
+// transpose: the eight k-consecutive values of column c as one MFMA operand.
+template <int NDW>
+struct RawRow {
+    uint32_t w[NDW];
+};
+
+
+// Column c of an 8-row block -> one MFMA fragment (rows 2i, 2i+1 share dword i).
+template <int NDW>
+__device__ __forceinline__ bf16x8 column_fragment(const RawRow<NDW> (&rows)[8], int c) {
+    uint32_t f[4];
+    const int dw = c >> 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t a = rows[2 * i].w[dw], b = rows[2 * i + 1].w[dw];
+        // v_perm_b32: selector bytes 0-3 pick from the second operand, 4-7 from the first
+        f[i] = (c & 1) ? __builtin_amdgcn_perm(b, a, 0x07060302u) : __builtin_amdgcn_perm(b, a, 0x05040100u);
+    }
+    uint4 q = make_uint4(f[0], f[1], f[2], f[3]);
+    return __builtin_bit_cast(bf16x8, q);
+}
+
 }  // namespace velora

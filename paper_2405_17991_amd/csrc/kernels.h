@@ -42,6 +42,11 @@ hipError_t launch_linear_compress(const void* X, const void* W, const float* v, 
                                   int64_t O, int64_t M, bool is_bf16, bool align16, bool s_vec_ok, const LaunchCfg& cfg,
                                   hipStream_t st);
 
+// dX[N, D] = G[N, O] * W[O, D] stored in the inputs' dtype.  bf16 with 16-byte aligned G, W and dX, O % 64 == 0 and
+// D % 8 == 0 takes the MFMA kernel, everything else the plain FMA kernel.  Requires D <= 65535 * 64.
+hipError_t launch_grad_input(const void* G, const void* W, void* dX, int64_t N, int64_t O, int64_t D, bool is_bf16,
+                             bool align16, hipStream_t st);
+
 // ---- init_v.hip ----
 // Workspace layout: [int32 flag | pad to 256 B | mean[d] f64 | slices[8][d] f64 | float partial[rows][d]].
 struct InitVPlan {

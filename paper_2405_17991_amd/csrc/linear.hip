@@ -56,34 +56,56 @@ __device__ __forceinline__ lds_ptr to_lds(char* p) { return (lds_ptr)p; }
 
 }  // namespace
 
-// One block's tile.  DO_S: this block also forms S for its 256 tokens.
-template <bool DO_S>
-__device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restrict__ X, const uint16_t* __restrict__ W,
-                                            const float* __restrict__ v, uint16_t* __restrict__ Y,
-                                            uint16_t* __restrict__ S, int N, int O, int D, int d, int64_t n0,
+// One block's tile of  Out[R, C] = A[R, K] * B,  A k-contiguous (X, or grad_output).
+//   NN = false: B = W[C, K], k-contiguous (the forward: Out = X W^T)
+//   NN = true:  B = W[K, C], c-contiguous (the backward: grad_input = grad_output W).  The W stream passes
+//               through registers anyway, so a thread fetches an 8 k x 8 column block (eight 16-byte row
+//               pieces), transposes it in registers (column_fragment) and writes eight ready operands into
+//               the k-contiguous LDS layout of the forward; everything after that is the same code.
+//   DO_S: this block also forms S for its 256 rows (forward only).
+template <bool DO_S, bool NN>
+__device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                                            const float* __restrict__ v, uint16_t* __restrict__ Out,
+                                            uint16_t* __restrict__ S, int R, int C, int K, int d, int64_t n0,
                                             int64_t o0) {
+    static_assert(!(DO_S && NN), "S belongs to the forward");
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int wm = w >> 1, wn = w & 1;
     const int q = lane >> 4, jj = lane & 15;
-    // Range-checked descriptors over this block's rows: rows past N (or O) read as zeros.
-    const int rows_x = N - n0 < kBM ? static_cast<int>(N - n0) : kBM;
-    const int rows_w = O - o0 < kBN ? static_cast<int>(O - o0) : kBN;
+    // Range-checked descriptors over this block's rows: rows past R (or C) read as zeros.
+    const int rows_x = R - n0 < kBM ? static_cast<int>(R - n0) : kBM;
+    const int rows_w = C - o0 < kBN ? static_cast<int>(C - o0) : kBN;
     __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t*>(X + n0 * D), 0, static_cast<int>(static_cast<int64_t>(rows_x) * D * 2), 0x00020000);
-    __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t*>(W + o0 * D), 0, static_cast<int>(static_cast<int64_t>(rows_w) * D * 2), 0x00020000);
-    // One wave instruction moves 1 KB = 8 rows x 128 B; wave w owns rows 64w .. 64w+63 of both tiles.
-    // lane -> row-in-8 = lane / 8, stored chunk = lane % 8, loaded chunk = stored ^ ((row >> 1) & 7).
+        const_cast<uint16_t*>(A + n0 * K), 0, static_cast<int>(static_cast<int64_t>(rows_x) * K * 2), 0x00020000);
+    // One wave instruction moves 1 KB; wave w owns a quarter of each tile.
+    // k-contiguous tiles: 8 rows x 128 B per instruction; lane -> row-in-8 = lane / 8, stored chunk = lane % 8,
+    // loaded chunk = stored ^ ((row >> 1) & 7).
     uint32_t gvoff[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int row = w * 64 + i * 8 + (lane >> 3);
         const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-        gvoff[i] = static_cast<uint32_t>(row) * static_cast<uint32_t>(D) * 2u + static_cast<uint32_t>(chunk) * 16u;
+        gvoff[i] = static_cast<uint32_t>(row) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
     }
-    const int nk = D / kBK;
+    // c-contiguous W tile (NN): thread -> k group tid % 8 (rows 8kg .. 8kg+7), column chunk tid / 8 (8 columns);
+    // a chunk past the last column gets an offset no descriptor covers
+    const int kg = tid & 7, chunk_w = tid >> 3;
+    const uint32_t wvoff_nn = o0 + chunk_w * 8 < C ? static_cast<uint32_t>(kg * 8) * static_cast<uint32_t>(C) * 2u +
+                                                         static_cast<uint32_t>(chunk_w) * 16u
+                                                   : 0xFFFFFFFFu;
+    const int nk = K / kBK;
     // steps past the end re-fetch the last k block into the (free) stage: the counted waits stay uniform
+    auto w_rsrc = [&](int tc) -> __amdgpu_buffer_rsrc_t {
+        if constexpr (NN) {   // the 64 k rows of step tc, from column o0 to the end of the last row
+            return __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint16_t*>(W + static_cast<int64_t>(tc) * kBK * C + o0), 0,
+                static_cast<int>((static_cast<int64_t>(kBK) * C - o0) * 2), 0x00020000);
+        } else {
+            return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(W + o0 * K), 0,
+                                                     static_cast<int>(static_cast<int64_t>(rows_w) * K * 2), 0x00020000);
+        }
+    };
     auto dma_x = [&](int t) {
         char* st = lds + (t & 1) * kStage;
         const int koff = (t < nk ? t : nk - 1) * kBK * 2;
@@ -91,25 +113,42 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         for (int i = 0; i < 8; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, to_lds(st + (w * 64 + i * 8) * kRowB), 16, gvoff[i], koff, 0, 0);
     };
-    auto dma_w = [&](int t) {
-        char* st = lds + (t & 1) * kStage;
-        const int koff = (t < nk ? t : nk - 1) * kBK * 2;
+    auto dma_w = [&](int t) {                     // NT only
+        char* st = lds + (t & 1) * kStage + kBM * kRowB + w * (kBN * kRowB / 4);
+        const int tc = t < nk ? t : nk - 1;
+        const __amdgpu_buffer_rsrc_t rw = w_rsrc(tc);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, to_lds(st + (kBM + w * 64 + i * 8) * kRowB), 16, gvoff[i], koff,
-                                                     0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, to_lds(st + i * 1024), 16, gvoff[i], tc * kBK * 2, 0, 0);
     };
     u32x4 wreg[8];
     auto regload_w = [&](int t) {
-        const int koff = (t < nk ? t : nk - 1) * kBK * 2;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) wreg[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, gvoff[i], koff, 0);
-    };
-    auto store_w = [&](int t) {
-        char* st = lds + (t & 1) * kStage;
+        const int tc = t < nk ? t : nk - 1;
+        const __amdgpu_buffer_rsrc_t rw = w_rsrc(tc);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<u32x4*>(st + (kBM + w * 64 + i * 8) * kRowB + lane * 16) = wreg[i];
+            wreg[i] = NN ? __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff_nn, i * C * 2, 0)      // row 8kg + i
+                         : __builtin_amdgcn_raw_buffer_load_b128(rw, gvoff[i], tc * kBK * 2, 0);
+    };
+    auto store_w = [&](int t) {
+        if constexpr (NN) {
+            // column 8*chunk + c of the 8 x 8 block -> k chunk kg of LDS row 8*chunk + c (swizzled as above)
+            char* st = lds + (t & 1) * kStage + kBM * kRowB;
+            RawRow<4> rows[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                rows[r].w[0] = wreg[r].x; rows[r].w[1] = wreg[r].y; rows[r].w[2] = wreg[r].z; rows[r].w[3] = wreg[r].w;
+            }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const int n = chunk_w * 8 + c;
+                *reinterpret_cast<bf16x8*>(st + n * kRowB + ((kg ^ ((n >> 1) & 7)) * 16)) = column_fragment(rows, c);
+            }
+        } else {
+            char* st = lds + (t & 1) * kStage + kBM * kRowB + w * (kBN * kRowB / 4);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(st + i * 1024 + lane * 16) = wreg[i];
+        }
     };
     // fragment of rows base + 16b + jj, chunk 4*kk + q; (row >> 1) & 7 == (jj >> 1) & 7 because base is a multiple of 16
     uint32_t foff[2];
@@ -174,11 +213,11 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     };
     // lane (jj, q = 0) holds rows 0..3 of the result for token jj: S = row 0 + row 1
     auto flush_s = [&](int g) {
-        const int M = D / d;
+        const int M = K / d;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const int64_t n = n0 + wm * 128 + (wn * 4 + b) * 16 + jj;
-            if (q == 0 && n < N) S[n * M + g] = f32_to_bf16(acc_s[b][0] + acc_s[b][1]);
+            if (q == 0 && n < R) S[n * M + g] = f32_to_bf16(acc_s[b][0] + acc_s[b][1]);
             acc_s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
@@ -187,10 +226,20 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     constexpr int kWaitVm8Lgkm0 = 0x0078;         // s_waitcnt vmcnt(8) lgkmcnt(0)
     bf16x8 fxA[8], fwA[8], fxB[8], fwB[8];
     bf16x8 vfA = {}, vfB = {};
-    dma_x(0); dma_w(0);
-    dma_x(1); dma_w(1);
+    dma_x(0);
+    dma_x(1);
+    if constexpr (NN) {
+        regload_w(0);
+        store_w(0);
+        regload_w(1);
+        store_w(1);
+    } else {
+        dma_w(0);
+        dma_w(1);
+    }
     regload_w(2);
-    __builtin_amdgcn_s_waitcnt(kWaitVm8);        // the four direct loads have landed; W(2) may still be in flight
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWaitVm8);        // everything before W(2) has landed; W(2) may still be in flight
     __syncthreads();                              // (also publishes vtab)
     fread(fxA, fwA, 0, 0);
     if constexpr (DO_S) vfA = v_fragment(0, 0);
@@ -201,7 +250,7 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         mma(fxA, fwA);
         if constexpr (DO_S) mma_s(fxA, vfA);
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(kWaitVm8Lgkm0);   // X(t+1) landed; fragments B and this wave's W(t+1) stores done
+        __builtin_amdgcn_s_waitcnt(kWaitVm8Lgkm0);   // A(t+1) landed; fragments B and this wave's W(t+1) stores done
         __syncthreads();                          // stage t&1 is free, stage (t+1)&1 is complete
         dma_x(t + 2);
         if (t + 1 < nk) {
@@ -215,7 +264,7 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
             if (((t + 1) * kBK) % d == 0) flush_s((t * kBK) / d);
         }
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(kWaitVm8);    // W(t+2) is in registers; X(t+2) may still be in flight
+        __builtin_amdgcn_s_waitcnt(kWaitVm8);    // W(t+2) is in registers; A(t+2) may still be in flight
         store_w(t + 2);                           // stage t&1: free since this step's barrier
         regload_w(t + 3);
         __builtin_amdgcn_sched_barrier(0);
@@ -228,21 +277,20 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
             const int64_t n = n0 + wm * 128 + b * 16 + jj, o = o0 + wn * 128 + a * 16 + q * 4;
-            if (n < N && o < O) {   // O % 4 == 0: a lane's four outputs are all inside or all outside
+            if (n < R && o < C) {   // C % 4 == 0: a lane's four outputs are all inside or all outside
                 const u32x2 out = {pack_bf16x2(acc[a][b][0], acc[a][b][1]), pack_bf16x2(acc[a][b][2], acc[a][b][3])};
-                *reinterpret_cast<u32x2*>(Y + n * O + o) = out;
+                *reinterpret_cast<u32x2*>(Out + n * C + o) = out;
             }
         }
 }
 
-template <bool FUSE>
-__global__ __launch_bounds__(256) void linear_compress_mfma_kernel(const uint16_t* __restrict__ X,
-                                                                  const uint16_t* __restrict__ W,
-                                                                  const float* __restrict__ v,
-                                                                  uint16_t* __restrict__ Y, uint16_t* __restrict__ S,
-                                                                  int N, int O, int D, int d) {
+// Out[R, C] = A[R, K] * W^T (NN = false, W[C, K]) or A * W (NN = true, W[K, C]); FUSE: S = compress(A, v) as well.
+template <bool FUSE, bool NN>
+__global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                                                         const float* __restrict__ v, uint16_t* __restrict__ Out,
+                                                         uint16_t* __restrict__ S, int R, int C, int K, int d) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const int To = (O + kBN - 1) / kBN, Tn = (N + kBM - 1) / kBM, T = To * Tn;
+    const int To = (C + kBN - 1) / kBN, Tn = (R + kBM - 1) / kBM, T = To * Tn;
     const int per_xcd = (T + 7) / 8;
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
     const int vid = xcd * per_xcd + idx;
@@ -254,27 +302,37 @@ __global__ __launch_bounds__(256) void linear_compress_mfma_kernel(const uint16_
         tn = xcd * (per_xcd / To) + band * 4 + within / 8;
     }
     const int64_t n0 = static_cast<int64_t>(tn) * kBM, o0 = static_cast<int64_t>(to) * kBN;
-    if (FUSE && to == 0) linear_tile<true>(lds, X, W, v, Y, S, N, O, D, d, n0, o0);
-    else linear_tile<false>(lds, X, W, v, Y, S, N, O, D, d, n0, o0);
+    if constexpr (FUSE) {
+        if (to == 0) {
+            linear_tile<true, false>(lds, A, W, v, Out, S, R, C, K, d, n0, o0);
+            return;
+        }
+    }
+    linear_tile<false, NN>(lds, A, W, v, Out, S, R, C, K, d, n0, o0);
 }
 
 // Any dtype, size and alignment: 64 x 64 output tile per block, 16-k slices through LDS, a 4 x 4 patch
 // per thread, float32 FMA.  Not tuned; it exists so that every shape has a result.
-template <typename E>
-__global__ __launch_bounds__(256) void linear_generic_kernel(const typename E::type* __restrict__ X,
+// Out[R, C] = A[R, K] * W^T (W[C, K]) or, NN, A * W (W[K, C]).
+template <typename E, bool NN>
+__global__ __launch_bounds__(256) void linear_generic_kernel(const typename E::type* __restrict__ A,
                                                             const typename E::type* __restrict__ W,
-                                                            typename E::type* __restrict__ Y, int64_t N, int64_t O,
-                                                            int64_t D) {
+                                                            typename E::type* __restrict__ Out, int64_t R, int64_t C,
+                                                            int64_t K) {
     __shared__ float xs[16][64 + 1], ws[16][64 + 1];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     const int64_t n0 = static_cast<int64_t>(blockIdx.x) * 64, o0 = static_cast<int64_t>(blockIdx.y) * 64;
     float acc[4][4] = {};
-    for (int64_t k0 = 0; k0 < D; k0 += 16) {
+    for (int64_t k0 = 0; k0 < K; k0 += 16) {
         for (int i = threadIdx.x; i < 64 * 16; i += 256) {
             const int r = i >> 4, k = i & 15;
-            const bool kin = k0 + k < D;
-            xs[k][r] = (kin && n0 + r < N) ? E::load(X, (n0 + r) * D + k0 + k) : 0.f;
-            ws[k][r] = (kin && o0 + r < O) ? E::load(W, (o0 + r) * D + k0 + k) : 0.f;
+            xs[k][r] = (k0 + k < K && n0 + r < R) ? E::load(A, (n0 + r) * K + k0 + k) : 0.f;
+            if constexpr (NN) {
+                const int kw = i >> 6, c = i & 63;          // consecutive threads along the contiguous axis
+                ws[kw][c] = (k0 + kw < K && o0 + c < C) ? E::load(W, (k0 + kw) * C + o0 + c) : 0.f;
+            } else {
+                ws[k][r] = (k0 + k < K && o0 + r < C) ? E::load(W, (o0 + r) * K + k0 + k) : 0.f;
+            }
         }
         __syncthreads();
 #pragma unroll
@@ -294,59 +352,69 @@ __global__ __launch_bounds__(256) void linear_generic_kernel(const typename E::t
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t n = n0 + ty * 4 + i, o = o0 + tx * 4 + j;
-            if (n < N && o < O) E::store(Y, n * O + o, acc[i][j]);
+            if (n < R && o < C) E::store(Out, n * C + o, acc[i][j]);
         }
 }
 
-bool linear_mfma_ok(int64_t N, int64_t D, int64_t O, bool is_bf16, bool align16) {
-    // 32-bit tile counts and byte offsets inside a 256-row tile; 8-byte Y stores
-    return is_bf16 && align16 && D % kBK == 0 && O % 4 == 0 && D <= (1 << 21) && N < (int64_t{1} << 31) - kBM &&
-           O < (int64_t{1} << 31) - kBN && ((N + kBM - 1) / kBM) * ((O + kBN - 1) / kBN) < (int64_t{1} << 28);
+namespace {
+
+// R rows, C output columns, K reduction length.  32-bit tile counts and byte offsets inside a tile.
+bool mfma_shape_ok(int64_t R, int64_t C, int64_t K, int c_multiple) {
+    return K % kBK == 0 && C % c_multiple == 0 && K <= (1 << 21) && C <= (1 << 21) && R < (int64_t{1} << 31) - kBM &&
+           ((R + kBM - 1) / kBM) * ((C + kBN - 1) / kBN) < (int64_t{1} << 28);
 }
 
-bool linear_fused_s_ok(int64_t d) { return d % kBK == 0 && d <= kMaxFusedD; }
+template <bool FUSE, bool NN>
+hipError_t launch_mfma(const void* A, const void* W, const float* v, void* Out, void* S, int64_t R, int64_t C,
+                       int64_t K, int64_t d, hipStream_t st) {
+    const int64_t tiles = ((R + kBM - 1) / kBM) * ((C + kBN - 1) / kBN);
+    const unsigned grid = static_cast<unsigned>((tiles + 7) / 8 * 8);
+    const size_t lds_bytes = 2 * static_cast<size_t>(kStage) + (FUSE ? 2 * static_cast<size_t>(d) * 2 : 0);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&linear_mfma_kernel<FUSE, NN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((linear_mfma_kernel<FUSE, NN>), dim3(grid), dim3(256), lds_bytes, st,
+                       static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(W), v, static_cast<uint16_t*>(Out),
+                       static_cast<uint16_t*>(S), static_cast<int>(R), static_cast<int>(C), static_cast<int>(K),
+                       static_cast<int>(d));
+    return hipGetLastError();
+}
+
+template <bool NN>
+hipError_t launch_generic(const void* A, const void* W, void* Out, int64_t R, int64_t C, int64_t K, bool is_bf16,
+                          hipStream_t st) {
+    const dim3 grid(static_cast<unsigned>((R + 63) / 64), static_cast<unsigned>((C + 63) / 64));   // C <= 65535 * 64: caller
+    if (is_bf16)
+        hipLaunchKernelGGL((linear_generic_kernel<Bf16Elem, NN>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(A),
+                           static_cast<const uint16_t*>(W), static_cast<uint16_t*>(Out), R, C, K);
+    else
+        hipLaunchKernelGGL((linear_generic_kernel<F32Elem, NN>), grid, dim3(256), 0, st, static_cast<const float*>(A),
+                           static_cast<const float*>(W), static_cast<float*>(Out), R, C, K);
+    return hipGetLastError();
+}
+
+}  // namespace
 
 hipError_t launch_linear_compress(const void* X, const void* W, const float* v, void* Y, void* S, int64_t N, int64_t D,
                                   int64_t O, int64_t M, bool is_bf16, bool align16, bool s_vec_ok, const LaunchCfg& cfg,
                                   hipStream_t st) {
     const int64_t d = D / M;
-    if (linear_mfma_ok(N, D, O, is_bf16, align16)) {
-        const bool fuse = linear_fused_s_ok(d);
-        const int64_t tiles = ((N + kBM - 1) / kBM) * ((O + kBN - 1) / kBN);
-        const unsigned grid = static_cast<unsigned>((tiles + 7) / 8 * 8);
-        const size_t lds_bytes = 2 * static_cast<size_t>(kStage) + (fuse ? 2 * static_cast<size_t>(d) * 2 : 0);
-        hipError_t e;
-        if (fuse) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&linear_compress_mfma_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(linear_compress_mfma_kernel<true>, dim3(grid), dim3(256), lds_bytes, st,
-                               static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(W), v,
-                               static_cast<uint16_t*>(Y), static_cast<uint16_t*>(S), static_cast<int>(N),
-                               static_cast<int>(O), static_cast<int>(D), static_cast<int>(d));
-            return hipGetLastError();
-        }
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&linear_compress_mfma_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(linear_compress_mfma_kernel<false>, dim3(grid), dim3(256), lds_bytes, st,
-                           static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(W), v,
-                           static_cast<uint16_t*>(Y), static_cast<uint16_t*>(S), static_cast<int>(N),
-                           static_cast<int>(O), static_cast<int>(D), static_cast<int>(d));
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        return launch_compress(X, v, S, N * M, d, true, s_vec_ok, cfg, st);
+    hipError_t e;
+    if (is_bf16 && align16 && mfma_shape_ok(N, O, D, 4)) {
+        if (d % kBK == 0 && d <= kMaxFusedD) return launch_mfma<true, false>(X, W, v, Y, S, N, O, D, d, st);
+        e = launch_mfma<false, false>(X, W, v, Y, S, N, O, D, d, st);
+    } else {
+        e = launch_generic<false>(X, W, Y, N, O, D, is_bf16, st);
     }
-    const dim3 grid(static_cast<unsigned>((N + 63) / 64), static_cast<unsigned>((O + 63) / 64));   // O <= 65535 * 64: caller
-    if (is_bf16)
-        hipLaunchKernelGGL(linear_generic_kernel<Bf16Elem>, grid, dim3(256), 0, st, static_cast<const uint16_t*>(X),
-                           static_cast<const uint16_t*>(W), static_cast<uint16_t*>(Y), N, O, D);
-    else
-        hipLaunchKernelGGL(linear_generic_kernel<F32Elem>, grid, dim3(256), 0, st, static_cast<const float*>(X),
-                           static_cast<const float*>(W), static_cast<float*>(Y), N, O, D);
-    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_compress(X, v, S, N * M, d, is_bf16, s_vec_ok, cfg, st);
+}
+
+hipError_t launch_grad_input(const void* G, const void* W, void* dX, int64_t N, int64_t O, int64_t D, bool is_bf16,
+                             bool align16, hipStream_t st) {
+    if (is_bf16 && align16 && mfma_shape_ok(N, D, O, 8))
+        return launch_mfma<false, true>(G, W, nullptr, dX, nullptr, N, D, O, 0, st);
+    return launch_generic<true>(G, W, dX, N, D, O, is_bf16, st);
 }
 
 }  // namespace velora

@@ -86,12 +86,6 @@ __global__ __launch_bounds__(256) void wgrad_pack_s_kernel(const uint16_t* __res
 // (the data is read exactly once)
 constexpr int kStreamAux = 2;
 
-template <int NDW>
-struct RawRow {
-    uint32_t w[NDW];
-};
-
-
 // CW consecutive bf16 through a buffer descriptor (wave-uniform base in SGPRs,
 // 32-bit per-lane byte offset).  A raw buffer load whose offset is not below
 // the descriptor's size returns zero without touching memory; the kernel uses
@@ -108,21 +102,6 @@ __device__ __forceinline__ RawRow<CW / 2> load_g(__amdgpu_buffer_rsrc_t rsrc, ui
         r.w[0] = q.x; r.w[1] = q.y;
     }
     return r;
-}
-
-// Column c of an 8-row block -> one MFMA fragment (rows 2i, 2i+1 share dword i).
-template <int NDW>
-__device__ __forceinline__ bf16x8 column_fragment(const RawRow<NDW> (&rows)[8], int c) {
-    uint32_t f[4];
-    const int dw = c >> 1;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t a = rows[2 * i].w[dw], b = rows[2 * i + 1].w[dw];
-        // v_perm_b32: selector bytes 0-3 pick from the second operand, 4-7 from the first
-        f[i] = (c & 1) ? __builtin_amdgcn_perm(b, a, 0x07060302u) : __builtin_amdgcn_perm(b, a, 0x05040100u);
-    }
-    uint4 q = make_uint4(f[0], f[1], f[2], f[3]);
-    return __builtin_bit_cast(bf16x8, q);
 }
 
 // One 32-token step in flight.  S is either a ready fragment per tile (packed

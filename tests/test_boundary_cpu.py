@@ -150,6 +150,18 @@ def test_linear_compress_argument_errors(vl):
     assert f(P, P, P + 2, 8, 16, 4, 4, vl.F32, P, P, None) == 4
 
 
+def test_grad_input_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    f = raw.velora_grad_input
+    assert f(None, P, 8, 4, 16, vl.BF16, P, None) == 1
+    assert f(P, P, 8, 4, 16, vl.BF16, None, None) == 1
+    assert f(P, P, 8, 4, 16, 9, P, None) == 3
+    assert f(P, P, 0, 4, 16, vl.BF16, P, None) == 2
+    assert f(P, P, 8, 4, 65535 * 64 + 1, vl.BF16, P, None) == 2
+    assert f(P, P + 1, 8, 4, 16, vl.BF16, P, None) == 4
+    assert f(P, P, 8, 4, 16, vl.F32, P + 2, None) == 4
+
+
 def test_rmsnorm_compress_argument_errors(vl):
     from paper_2405_17991_amd.binding import raw
     f = raw.velora_rmsnorm_compress

@@ -57,6 +57,30 @@ def test_layer_forward_backward(mods, dtype, B, T, D, O, d):
     assert torch.equal(layer.v, before)
 
 
+def test_layer_with_the_package_s_own_gemms(mods):
+    # the same layer with both dense products in this package's kernels: same forward and gradients as the
+    # vendor-GEMM variant up to the rounding of bf16 outputs
+    torch, va = mods
+    torch.manual_seed(1)
+    B, T, D, O, d = 3, 100, 256, 264, 64
+    a = va.VeLoRALinear(D, O, d, device="cuda", dtype=torch.bfloat16)
+    b = va.VeLoRALinear(D, O, d, device="cuda", dtype=torch.bfloat16, own_gemm=True)
+    b.load_state_dict(a.state_dict())
+    x = (torch.randn(B, T, D, device="cuda") + 0.5).to(torch.bfloat16)
+    g = (torch.randn(B, T, O, device="cuda") * 0.05).to(torch.bfloat16)
+    xa = x.clone().requires_grad_(True)
+    xb = x.clone().requires_grad_(True)
+    ya = a(xa); ya.backward(g)
+    yb = b(xb); yb.backward(g)
+    torch.cuda.synchronize()
+    assert torch.equal(a.v, b.v)
+
+    def rel(p, q):
+        return ((p.float() - q.float()).norm() / q.float().norm()).item()
+
+    assert rel(yb, ya) <= 4e-3 and rel(xb.grad, xa.grad) <= 4e-3 and rel(b.weight.grad, a.weight.grad) <= 4e-3
+
+
 def test_saved_activation_shrinks_by_d(mods):
     torch, va = mods
     N, D, O, d = 2048, 1024, 512, 64

@@ -131,3 +131,64 @@ def test_full_size_sampled(vl):
     S2 = vl.velora_compress(Xd, to_dev(v, wl.F32), sh.M)
     torch.cuda.synchronize()
     assert rel_fro(to_host_f64(Sd), to_host_f64(S2)) <= 2e-3
+
+
+# ------------------------------------------------------------------ grad_input = grad_output @ weight
+def _check_grad_input(vl, N, O, D, dtype, seed=0):
+    import torch
+    G = wl.random_tensor(N, O, dtype, 900 + seed + N + O, 41, 0.05)
+    W = wl.random_tensor(O, D, dtype, 901 + seed + D, 42, O ** -0.5)
+    dX_exact, dX_store = oracle.grad_input(G, W)
+    dXd = vl.velora_grad_input(to_dev(G, dtype), to_dev(W, dtype))
+    torch.cuda.synchronize()
+    assert tuple(dXd.shape) == (N, D)
+    got = to_host_f64(dXd)
+    if dtype == wl.F32:
+        assert rel_fro(got, dX_exact) <= TOL_F32 and rel_max(got, dX_exact) <= TOL_F32
+    else:
+        assert rel_fro(got, dX_exact) <= TOL_BF16 and rel_fro(got, dX_exact) <= TOL_BF16_STORE
+        assert_bf16_store_matches(to_host_bits(dXd), dX_exact, dX_store, "dX")
+
+
+# MFMA kernel: O % 64 == 0 (the reduction), D % 8 == 0; ragged token and column tiles, one and several k steps
+@pytest.mark.parametrize("N,O,D", [(300, 128, 264), (512, 256, 512), (256, 64, 256), (700, 192, 104), (1, 64, 8),
+                                   (131, 2048, 72), (1030, 320, 1032), (2304, 128, 2048)])
+def test_grad_input_bf16_mfma(vl, N, O, D):
+    _check_grad_input(vl, N, O, D, wl.BF16)
+
+
+@pytest.mark.parametrize("N,O,D", [(100, 96, 50), (64, 37, 128), (33, 9, 60), (5, 3, 8), (70, 128, 36)])
+def test_grad_input_bf16_generic(vl, N, O, D):
+    _check_grad_input(vl, N, O, D, wl.BF16)
+
+
+@pytest.mark.parametrize("N,O,D", [(256, 64, 64), (77, 19, 63), (130, 70, 128), (1, 1, 1)])
+def test_grad_input_f32(vl, N, O, D):
+    _check_grad_input(vl, N, O, D, wl.F32)
+
+
+def test_grad_input_selects_weight_rows(vl):
+    # G = one-hot rows: dX[n, :] = W[o(n), :] bit for bit (pins the [O, D] layout of W and the transposition)
+    import torch
+    N, O, D = 300, 128, 264
+    W = wl.random_tensor(O, D, wl.BF16, 13)
+    pick = (np.arange(N) * 7 + 3) % O
+    G32 = np.zeros((N, O), dtype=np.float32)
+    G32[np.arange(N), pick] = 1.0
+    dXd = vl.velora_grad_input(to_dev(wl.to_storage(G32, wl.BF16), wl.BF16), to_dev(W, wl.BF16))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_bits(dXd), W[pick])
+
+
+def test_grad_input_full_size_sampled(vl):
+    import torch
+    sh = wl.shape_by_name("cfg4_down")
+    torch.manual_seed(1)
+    Gd = (torch.randn((sh.N, sh.O), device="cuda") * 0.05).to(torch.bfloat16)
+    Wd = (torch.randn((sh.O, sh.D), device="cuda") * sh.O ** -0.5).to(torch.bfloat16)
+    dXd = vl.velora_grad_input(Gd, Wd)
+    torch.cuda.synchronize()
+    rows = np.array([0, 255, 256, 4097, 8191, 12345, sh.N - 257, sh.N - 1])
+    idx = torch.from_numpy(rows).cuda()
+    dX_exact, dX_store = oracle.grad_input(to_host_bits(Gd[idx]), to_host_bits(Wd))
+    assert_bf16_store_matches(to_host_bits(dXd[idx]), dX_exact, dX_store, "dX rows")

@@ -487,6 +487,29 @@ class TestLinearCompress:
         assert (Y[:, 2] == X[:, 5]).all() and (Y[:, :2] == 0).all()
 
 
+class TestGradInput:
+    def test_triple_loop_layout_and_adjointness(self):
+        G = _rand((5, 4), 6, wl.BF16); W = _rand((4, 12), 7, wl.BF16)
+        dX, dXs = oracle.grad_input(G, W)
+        Gf, Wf = wl.to_f64(G, wl.BF16), wl.to_f64(W, wl.BF16)
+        want = np.zeros((5, 12))
+        for n in range(5):
+            for c in range(12):
+                for o in range(4):
+                    want[n, c] += Gf[n, o] * Wf[o, c]
+        np.testing.assert_allclose(dX, want, rtol=1e-14, atol=1e-300)
+        assert dXs.dtype == np.uint16 and (dXs == wl.f32_to_bf16_bits(dX.astype(np.float32))).all()
+        # adjoint of the forward: <G, X W^T> = <G W, X> for any X (the defining property of grad_input)
+        X = _rand((5, 12), 8, wl.BF16)
+        Y = oracle.linear(X, W)
+        np.testing.assert_allclose((Gf * Y).sum(), (dX * wl.to_f64(X, wl.BF16)).sum(), rtol=1e-12)
+        # a one-hot grad_output row selects a row of W
+        G1 = np.zeros((2, 4), dtype=np.float32); G1[0, 2] = 1.0; G1[1, 0] = 1.0
+        W32 = _rand((4, 12), 9)
+        d1, _ = oracle.grad_input(G1, W32)
+        assert (d1[0] == W32[2]).all() and (d1[1] == W32[0]).all()
+
+
 # ------------------------------------------------------------------ AdamW on the factored gradient
 class TestAdamWFactor:
     """The fused optimiser step of the factored gradient, pinned to the library
