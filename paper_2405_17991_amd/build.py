@@ -39,8 +39,9 @@ def _stale(target: str, deps: List[str]) -> bool:
 
 
 # Kernels whose loops count outstanding vector-memory operations by hand (s_waitcnt vmcnt(n)): a register
-# spill inside them would add scratch loads and stores to that count and break the waits, so the build
-# fails if the compiler reports any spill or scratch use for them.
+# spill inside them would add scratch loads and stores to that count, which makes every wait cover more
+# than it needs and serialises the load streams, so the build fails if the compiler reports any spill or
+# scratch use for them.
 NO_SPILL = {"linear.hip": "linear_mfma_kernel"}
 
 
@@ -54,7 +55,7 @@ def _check_no_spill(src: str, remarks: str) -> None:
                 if key in line and int(line.split(key)[1].split()[0]) != 0:
                     bad.append(f"{name}: {key} {line.split(key)[1].split()[0]}")
     if bad:
-        raise RuntimeError(f"{src}: kernels with hand-counted waits must not spill:\n" + "\n".join(bad))
+        raise RuntimeError(f"{src}: kernels with hand-counted waits are built without spills:\n" + "\n".join(bad))
 
 
 def _compile(src: str, force: bool) -> str:

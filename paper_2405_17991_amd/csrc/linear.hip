@@ -11,19 +11,26 @@
 // writes and the fragment reads (16 rows x one chunk) bank-conflict free.
 // Two LDS stages (2 x 64 KB).  What bounds the loop is the number of cache-line
 // requests a CU can have outstanding (~70 x 128 B at ~500 cycles from L2), so
-// the request queue must never drain at a wait point.  Two interleaved streams:
-//   X tiles: global -> LDS directly (buffer_load ... lds), issued at the middle
-//            of step t for step t+2, awaited at the middle of step t+1;
-//   W tiles: global -> registers, issued at the end of step t for step t+3,
-//            awaited at the end of step t+1 and written to LDS there.
+// the request queue must never drain at a wait point and loads must not arrive in
+// bursts (a wave that cannot issue a load issues no MFMA either).  Two streams,
+// one load instruction after every eight MFMAs:
+//   W tiles: global -> registers during the first half of step t (for step
+//            t+2), awaited at the end of step t and written to LDS there;
+//   A tiles: global -> LDS directly (buffer_load ... lds) during the second half
+//            of step t (for step t+2), awaited at the middle of step t+1.
 // At each wait the other stream's batch is still in flight (s_waitcnt vmcnt(8),
 // vector-memory operations complete in order).  Fragments are double-buffered in
 // registers: the LDS reads for the next 32-k half run under the 64 MFMAs of the
-// current one.  No other vector-memory load may sit inside the loop, or the
-// counted waits would be off; v is therefore staged in LDS before the loop.
+// current one.  The counted waits stay correct if further vector-memory
+// operations are issued inside the loop (each wait only needs eight younger
+// loads behind the batch it waits for, and loads complete in order), but every
+// such operation makes a wait cover more than it needs and costs overlap: v is
+// therefore staged in LDS before the loop, and the build rejects register
+// spills in this kernel.
 // Block order: consecutive block ids land on different XCDs (one L2 each), so
-// XCD x takes a contiguous run of tiles, 32 blocks running together covering
-// 4 token tiles x 8 output tiles where the tile counts allow it.
+// XCD x takes a contiguous run of tile ids, and ids are laid out in groups of
+// four token tiles (output tiles outer): the 32 blocks an XCD runs together
+// cover about 4 token tiles x 8 output tiles.
 //
 // Compression inside the GEMM.  Blocks of the first output tile also form
 // S[n, g] = <X[n, g*d : (g+1)*d], v>.  v is split into two bf16 parts,
@@ -187,12 +194,32 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc_s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto mma = [&](const bf16x8 (&fx)[8], const bf16x8 (&fw)[8]) {
+    // 64 MFMAs with one load instruction after every eight: a load then finds room in the CU's request queue
+    // instead of arriving in a burst that blocks the wave (and with it the MFMA issue)
+    auto mma_w = [&](const bf16x8 (&fx)[8], const bf16x8 (&fw)[8], int t) {      // + W(t) -> registers
+        const int tc = t < nk ? t : nk - 1;
+        const __amdgpu_buffer_rsrc_t rw = w_rsrc(tc);
 #pragma unroll
-        for (int a = 0; a < 8; ++a)
+        for (int a = 0; a < 8; ++a) {
 #pragma unroll
             for (int b = 0; b < 8; ++b)
                 acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[a], fx[b], acc[a][b], 0, 0, 0);
+            wreg[a] = NN ? __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff_nn, a * C * 2, 0)      // row 8kg + a
+                         : __builtin_amdgcn_raw_buffer_load_b128(rw, gvoff[a], tc * kBK * 2, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto mma_x = [&](const bf16x8 (&fx)[8], const bf16x8 (&fw)[8], int t) {      // + A(t) -> its LDS stage
+        char* st = lds + (t & 1) * kStage;
+        const int koff = (t < nk ? t : nk - 1) * kBK * 2;
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+#pragma unroll
+            for (int b = 0; b < 8; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[a], fx[b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, to_lds(st + (w * 64 + a * 8) * kRowB), 16, gvoff[a], koff, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
     // A operand with v: row 0 = hi, row 1 = lo, rows 2..15 zero; k = 8q .. 8q+7 of this 32-k half
     auto v_fragment = [&](int t, int kk) -> bf16x8 {
@@ -237,9 +264,8 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         dma_w(0);
         dma_w(1);
     }
-    regload_w(2);
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(kWaitVm8);        // everything before W(2) has landed; W(2) may still be in flight
+    __builtin_amdgcn_s_waitcnt(0);                // the first two steps' tiles have landed
     __syncthreads();                              // (also publishes vtab)
     fread(fxA, fwA, 0, 0);
     if constexpr (DO_S) vfA = v_fragment(0, 0);
@@ -247,18 +273,17 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         fread(fxB, fwB, t, 1);
         if constexpr (DO_S) vfB = v_fragment(t, 1);
         __builtin_amdgcn_sched_barrier(0);
-        mma(fxA, fwA);
+        mma_w(fxA, fwA, t + 2);                   // first half: W(t+2) on its way to registers
         if constexpr (DO_S) mma_s(fxA, vfA);
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(kWaitVm8Lgkm0);   // A(t+1) landed; fragments B and this wave's W(t+1) stores done
         __syncthreads();                          // stage t&1 is free, stage (t+1)&1 is complete
-        dma_x(t + 2);
         if (t + 1 < nk) {
             fread(fxA, fwA, t + 1, 0);
             if constexpr (DO_S) vfA = v_fragment(t + 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-        mma(fxB, fwB);
+        mma_x(fxB, fwB, t + 2);                   // second half: A(t+2) on its way into stage t&1
         if constexpr (DO_S) {
             mma_s(fxB, vfB);
             if (((t + 1) * kBK) % d == 0) flush_s((t * kBK) / d);
@@ -266,7 +291,6 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(kWaitVm8);    // W(t+2) is in registers; A(t+2) may still be in flight
         store_w(t + 2);                           // stage t&1: free since this step's barrier
-        regload_w(t + 3);
         __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_s_waitcnt(0);                // nothing of this block is in flight when its LDS is released
@@ -295,12 +319,13 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t* __rest
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
     const int vid = xcd * per_xcd + idx;
     if (idx >= per_xcd || vid >= T) return;       // whole block, before any barrier
-    int tn = vid / To, to = vid % To;
-    if (To % 8 == 0 && per_xcd % (4 * To) == 0) {
-        const int band = idx / (4 * To), r = idx % (4 * To), panel = r / 32, within = r % 32;
-        to = panel * 8 + within % 8;
-        tn = xcd * (per_xcd / To) + band * 4 + within / 8;
-    }
+    // grouped order: four token tiles at a time, output tiles outer, so 32 consecutive ids (what one XCD runs
+    // together) touch about 4 + 8 distinct operand tiles per k step instead of 1 + 32
+    constexpr int kGroup = 4;
+    const int in_group = kGroup * To;
+    const int first_tn = (vid / in_group) * kGroup;
+    const int group_rows = Tn - first_tn < kGroup ? Tn - first_tn : kGroup;
+    const int tn = first_tn + (vid % in_group) % group_rows, to = (vid % in_group) / group_rows;
     const int64_t n0 = static_cast<int64_t>(tn) * kBM, o0 = static_cast<int64_t>(to) * kBN;
     if constexpr (FUSE) {
         if (to == 0) {
