@@ -46,6 +46,7 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace velora {
@@ -395,9 +396,17 @@ hipError_t launch_mfma(const void* A, const void* W, const float* v, void* Out, 
     const int64_t tiles = ((R + kBM - 1) / kBM) * ((C + kBN - 1) / kBN);
     const unsigned grid = static_cast<unsigned>((tiles + 7) / 8 * 8);
     const size_t lds_bytes = 2 * static_cast<size_t>(kStage) + (FUSE ? 2 * static_cast<size_t>(d) * 2 : 0);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&linear_mfma_kernel<FUSE, NN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel and device (the call is not free)
+    static std::atomic<bool> allowed[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64 || !allowed[dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&linear_mfma_kernel<FUSE, NN>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStage + 4 * kMaxFusedD);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) allowed[dev].store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL((linear_mfma_kernel<FUSE, NN>), dim3(grid), dim3(256), lds_bytes, st,
                        static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(W), v, static_cast<uint16_t*>(Out),
                        static_cast<uint16_t*>(S), static_cast<int>(R), static_cast<int>(C), static_cast<int>(K),
