@@ -122,3 +122,48 @@ def test_other_entry_points_replay_from_a_graph(vl):
         for name, got, ref in zip(("X1", "S1", "X2", "S2", "S3", "state", "v_next", "W", "m", "u"),
                                   (X1, S1, X2, S2, S3, state, v_next, W, m, u), refs[i]):
             assert torch.equal(got, ref), f"replay {rep}: {name} differs from the eager result"
+
+
+def test_gemm_entry_points_replay_from_a_graph(vl):
+    """velora_linear_compress and velora_grad_input are capturable as well (their one-off per-device set-up
+    happens on the warm-up call before the capture)."""
+    import torch
+    N, D, O, d = 520, 256, 264, 64
+    M = D // d
+    Xs = [to_dev(wl.random_tensor(N, D, wl.BF16, seed=s, stream=51), wl.BF16) for s in (1, 2)]
+    Gs = [to_dev(wl.random_tensor(N, O, wl.BF16, seed=s, stream=52, sigma=0.05), wl.BF16) for s in (1, 2)]
+    W = to_dev(wl.random_tensor(O, D, wl.BF16, seed=3, stream=53, sigma=D ** -0.5), wl.BF16)
+    v = to_dev(wl.random_unit_v(d, seed=4), wl.F32)
+    X, G = Xs[0].clone(), Gs[0].clone()
+    Y = torch.empty((N, O), dtype=torch.bfloat16, device="cuda"); S = torch.empty((N, M), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((N, D), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        vl.velora_linear_compress(X, W, v, M, Y=Y, S=S)
+        vl.velora_grad_input(G, W, dX=dX)
+
+    refs = []
+    for x_, g_ in zip(Xs, Gs):
+        X.copy_(x_); G.copy_(g_)
+        step()
+        torch.cuda.synchronize()
+        refs.append([t.clone() for t in (Y, S, dX)])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        i = rep % 2
+        X.copy_(Xs[i]); G.copy_(Gs[i])
+        for t in (Y, S, dX):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, ref in zip(("Y", "S", "dX"), (Y, S, dX), refs[i]):
+            assert torch.equal(got, ref), f"replay {rep}: {name} differs from the eager result"
