@@ -62,3 +62,43 @@ def test_random_shape(vl, N, O, D, d, dtype):
         assert np.abs(to_host_f64(Xhat) - ref).max() <= 2.0 ** -23 * max(np.abs(ref).max(), 1e-30)
     else:
         assert (np.abs(to_host_f64(Xhat) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-30).all()
+
+
+def _gemm_shapes(n, seed):
+    # multiples that reach the MFMA kernel (D % 64 == 0 and O % 4 == 0 forward, O % 64 == 0 and D % 8 == 0
+    # backward) mixed with ones that do not
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([8, 16, 32, 64, 64, 128, 192, 256]))
+        M = int(rng.integers(1, max(2, 1100 // d)))
+        D = M * d
+        N = int(rng.integers(1, 900))
+        O = int(rng.integers(1, 12)) * int(rng.choice([1, 4, 8, 64, 64]))
+        dtype = wl.BF16 if rng.random() < 0.8 else wl.F32
+        out.append((N, O, D, d, dtype))
+    return out
+
+
+@pytest.mark.parametrize("N,O,D,d,dtype", _gemm_shapes(30, 77))
+def test_random_shape_dense_products(vl, N, O, D, d, dtype):
+    """velora_linear_compress and velora_grad_input on seeded random shapes."""
+    import torch
+    M = D // d
+    seed = N * 7919 + O * 104729 + D
+    X = wl.random_tensor(N, D, dtype, seed=seed, stream=6)
+    W = wl.random_tensor(O, D, dtype, seed=seed, stream=8, sigma=D ** -0.5)
+    G = wl.random_tensor(N, O, dtype, seed=seed, stream=7, sigma=0.05)
+    v = wl.random_unit_v(d, seed=seed)
+    Yd, Sd = vl.velora_linear_compress(to_dev(X, dtype), to_dev(W, dtype), to_dev(v, wl.F32), M)
+    dXd = vl.velora_grad_input(to_dev(G, dtype), to_dev(W, dtype))
+    torch.cuda.synchronize()
+    Y_exact, Y_store, S_exact, S_store = oracle.linear_compress(X, W, v, M)
+    dX_exact, dX_store = oracle.grad_input(G, W)
+    if dtype == wl.F32:
+        for got, want in ((Yd, Y_exact), (Sd, S_exact), (dXd, dX_exact)):
+            assert rel_fro(to_host_f64(got), want) <= TOL_F32 and rel_max(to_host_f64(got), want) <= TOL_F32
+    else:
+        assert_bf16_store_matches(to_host_bits(Yd), Y_exact, Y_store, "Y")
+        assert_bf16_store_matches(to_host_bits(Sd), S_exact, S_store, "S")
+        assert_bf16_store_matches(to_host_bits(dXd), dX_exact, dX_store, "dX")
