@@ -88,6 +88,72 @@ __global__ __launch_bounds__(256) void rmsnorm_compress_row_kernel(const uint4* 
     }
 }
 
+// The same with the row kept in registers between the two passes: NV 16-byte vectors per lane (a row is
+// exactly 64 * NV vectors), lane l holding vectors l, l + 64, ...  The lane's slice of gamma stays in
+// registers for the whole kernel (it would otherwise be re-read, at twice the row's bytes, for every row), and
+// LDS is not used at all.  64 % P == 0, so every vector of a lane has the same position p in its sub-token.
+template <typename E, int P, int NV>
+__global__ __launch_bounds__(256) void rmsnorm_compress_reg_kernel(const uint4* __restrict__ H,
+                                                                  const float* __restrict__ gamma,
+                                                                  const float* __restrict__ v,
+                                                                  uint4* __restrict__ X,
+                                                                  typename E::type* __restrict__ S, int64_t N, int M,
+                                                                  float inv_D, float eps) {
+    constexpr int kV = E::kPerVec;
+    constexpr int kVecPerRow = kWave * NV;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+    const int p = lane % P;
+    float vf[kV], gf[NV][kV];
+#pragma unroll
+    for (int e = 0; e < kV; ++e) vf[e] = v[p * kV + e];
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+#pragma unroll
+        for (int e = 0; e < kV; ++e) gf[j][e] = gamma[(j * kWave + lane) * kV + e];
+
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * 4;
+    for (int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + w; row < N; row += n_waves) {
+        const uint4* src = H + row * kVecPerRow;
+        uint4 q[NV];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) q[j] = load_stream16(&src[j * kWave + lane]);
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float f[kV];
+            E::unpack(q[j], f);
+#pragma unroll
+            for (int e = 0; e < kV; ++e) ss = fmaf(f[e], f[e], ss);
+        }
+        ss = group_sum<kWave>(ss);
+        const float rinv = 1.f / sqrtf(ss * inv_D + eps);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float f[kV], x[kV];
+            E::unpack(q[j], f);
+#pragma unroll
+            for (int e = 0; e < kV; ++e) x[e] = f[e] * rinv * gf[j][e];
+            uint4 o;
+            if constexpr (kV == 4) {
+                o = make_uint4(__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3]));
+            } else {
+                o = make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]),
+                               pack_bf16x2(x[6], x[7]));
+            }
+            const u32x4_rn out = {o.x, o.y, o.z, o.w};
+            __builtin_nontemporal_store(out, reinterpret_cast<u32x4_rn*>(&X[row * kVecPerRow + j * kWave + lane]));
+            float sv[kV];
+            E::unpack(o, sv);                                      // the stored values
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < kV; ++e) acc = fmaf(sv[e], vf[e], acc);
+            acc = group_sum<P>(acc);
+            if (p == 0) E::store(S, row * M + (j * kWave + lane) / P, acc);
+        }
+    }
+}
+
 // Any shape: one block per row, X only; compress follows as its own launch.
 template <typename E>
 __global__ __launch_bounds__(256) void rmsnorm_generic_kernel(const typename E::type* __restrict__ H,
@@ -115,10 +181,30 @@ __global__ __launch_bounds__(256) void rmsnorm_generic_kernel(const typename E::
 
 namespace {
 
+template <typename E, int P, int NV>
+hipError_t launch_reg(const void* H, const float* gamma, const float* v, void* X, void* S, int64_t N, int64_t D,
+                      int64_t M, float eps, const LaunchCfg& cfg, hipStream_t st) {
+    int64_t grid = ceil_div(N, 4);
+    if (grid > cfg.max_blocks) grid = cfg.max_blocks;
+    hipLaunchKernelGGL((rmsnorm_compress_reg_kernel<E, P, NV>), dim3(static_cast<unsigned>(grid)), dim3(256), 0, st,
+                       static_cast<const uint4*>(H), gamma, v, static_cast<uint4*>(X),
+                       static_cast<typename E::type*>(S), N, static_cast<int>(M),
+                       static_cast<float>(1.0 / static_cast<double>(D)), eps);
+    return hipGetLastError();
+}
+
 template <typename E, int P>
 hipError_t launch_row(const void* H, const float* gamma, const float* v, void* X, void* S, int64_t N, int64_t D,
                       int64_t M, float eps, const LaunchCfg& cfg, hipStream_t st) {
     const int vec_per_row = static_cast<int>(D / E::kPerVec);
+    // rows of exactly 64, 128, 256, 512 (or 1024, bf16) vectors stay in registers
+    switch (vec_per_row) {
+        case 64:  return launch_reg<E, P, 1>(H, gamma, v, X, S, N, D, M, eps, cfg, st);
+        case 128: return launch_reg<E, P, 2>(H, gamma, v, X, S, N, D, M, eps, cfg, st);
+        case 256: return launch_reg<E, P, 4>(H, gamma, v, X, S, N, D, M, eps, cfg, st);
+        case 512: return launch_reg<E, P, 8>(H, gamma, v, X, S, N, D, M, eps, cfg, st);
+        default:  break;
+    }
     const size_t lds = static_cast<size_t>(4) * vec_per_row * sizeof(uint4);
     int64_t grid = ceil_div(N, 4);
     if (grid > cfg.max_blocks) grid = cfg.max_blocks;
