@@ -83,3 +83,38 @@ def test_more_than_2_31_elements(vl):
     dW2 = vl.velora_expand_factor(T, vd, D)
     torch.cuda.synchronize()
     assert rel_fro(dW2.cpu().numpy().astype(np.float64), dW.cpu().numpy().astype(np.float64)) <= 2e-6
+
+
+def test_dense_products_past_2_31_elements(vl):
+    """velora_linear_compress and velora_grad_input with X (and dX) beyond 2^31 elements: the row
+    offsets of the last token tiles do not fit 32 bits.  Rows on both sides of the 2^31 boundary
+    and the last rows are checked against the oracle's per-row products."""
+    import torch
+    from gpu_helpers import assert_bf16_store_matches
+    Ox = 264
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    X = torch.empty((N, D), device="cuda", dtype=torch.bfloat16)
+    step = 1 << 18
+    for r0 in range(0, N, step):
+        r1 = min(N, r0 + step)
+        X[r0:r1] = torch.randn((r1 - r0, D), generator=g, device="cuda").to(torch.bfloat16)
+    W = (torch.randn((Ox, D), generator=g, device="cuda") * D ** -0.5).to(torch.bfloat16)
+    v = wl.random_unit_v(D // M, seed=5)
+    vd = torch.from_numpy(v).cuda()
+    Y, S = vl.velora_linear_compress(X, W, vd, M)
+    torch.cuda.synchronize()
+    rows = np.array([0, 255, 256, (2**31) // D - 1, (2**31) // D, (2**31) // D + 1, N - 78, N - 77, N - 1])
+    idx = torch.from_numpy(rows).cuda()
+    Y_exact, Y_store, S_exact, S_store = oracle.linear_compress(to_host_bits(X[idx]), to_host_bits(W), v, M)
+    assert_bf16_store_matches(to_host_bits(Y[idx]), Y_exact, Y_store, "Y rows")
+    assert_bf16_store_matches(to_host_bits(S[idx]), S_exact, S_store, "S rows")
+    del Y, S
+    # dX[N, D] = G[N, Ox] W[Ox, D]: the output is the array past 2^31 elements here (Ox % 64 != 0 would leave
+    # the MFMA path, so the reduction length is cut to 256)
+    Gx = (torch.randn((N, 256), generator=g, device="cuda") * 0.05).to(torch.bfloat16)
+    W2 = W[:256].contiguous()
+    dX = vl.velora_grad_input(Gx, W2)
+    torch.cuda.synchronize()
+    dX_exact, dX_store = oracle.grad_input(to_host_bits(Gx[idx]), to_host_bits(W2))
+    assert_bf16_store_matches(to_host_bits(dX[idx]), dX_exact, dX_store, "dX rows")
