@@ -236,6 +236,57 @@ def _linear_record(vl, torch, sh, v, dev, launches):
     return rec
 
 
+def _mlp_block_record(torch, dev):
+    """A whole LLaMA-7B-like gated MLP block (hidden 4096, intermediate 11008, 16384 tokens, bf16), forward +
+    backward through autograd: the plain block against the same block with VeLoRA on its three projections
+    (paper Sec. 4: what the method costs in time and what it frees in memory).  Memory = what stays allocated
+    between the end of the forward and the start of the backward, beyond weights, input and output.
+    Not part of `value`."""
+    from paper_2405_17991_amd import autograd as va
+    N, H, F, d_h, d_f = 16384, 4096, 11008, 256, 256
+    torch.manual_seed(0)
+    blk = va.VeLoRALlamaMLP(H, F, d_h, d_f, device=dev, dtype=torch.bfloat16)
+    h0 = torch.randn((N, H), device=dev).to(torch.bfloat16)
+    blk.init_v(h0)
+    gout = (torch.randn((N, H), device=dev) * 0.05).to(torch.bfloat16)
+
+    def plain(h):
+        gate = torch.nn.functional.linear(h, blk.w_gate)
+        up = torch.nn.functional.linear(h, blk.w_up)
+        return torch.nn.functional.linear(torch.nn.functional.silu(gate) * up, blk.w_down)
+
+    def run(fn, reps=6):
+        held, times = 0, []
+        for r in range(reps + 2):
+            for p in blk.parameters():
+                p.grad = None
+            h = h0.clone().requires_grad_(True)
+            torch.cuda.synchronize()
+            base = torch.cuda.memory_allocated()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            y = fn(h)
+            torch.cuda.synchronize()
+            held = torch.cuda.memory_allocated() - base - y.numel() * y.element_size()
+            y.backward(gout)
+            e1.record()
+            torch.cuda.synchronize()
+            if r >= 2:
+                times.append(e0.elapsed_time(e1))
+            del y, h
+        return sum(times) / len(times), held
+
+    t_plain, m_plain = run(plain)
+    t_velora, m_velora = run(blk)
+    return {"workload": "LLaMA-7B-like MLP block, N=16384, 4096 -> 11008 -> 4096, d=256, bf16, forward + backward",
+            "plain_ms": round(t_plain, 3), "velora_ms": round(t_velora, 3),
+            "time_ratio": round(t_velora / t_plain, 4),
+            "plain_saved_MB": round(m_plain / 1e6, 1), "velora_saved_MB": round(m_velora / 1e6, 1),
+            "note": "the three dense products and their input gradients run in the vendor GEMM in both columns; "
+                    "the VeLoRA column keeps gate and up (the activation's own backward needs them) but neither "
+                    "the block input nor the down projection's input"}
+
+
 def _rmsnorm_record(vl, torch, wl, dev, launches):
     """Producer-side fusion for the attention projections' input (LLaMA-7B-like:
     N=16384, D=4096, d=256): X = RMSNorm(H) written and compressed in one pass."""
@@ -456,6 +507,8 @@ def main():
         out["rmsnorm_compress"] = _rmsnorm_record(vl, torch, wl, dev, args.steps)
         torch.cuda.empty_cache()
         out["linear_compress"] = _linear_record(vl, torch, sh, v, dev, args.steps)
+        torch.cuda.empty_cache()
+        out["mlp_block"] = _mlp_block_record(torch, dev)
     torch.cuda.empty_cache()
 
     # ---------------- every layer shape of the five configurations
