@@ -16,6 +16,8 @@ shrinks from ``N*D`` to ``N*M = N*D/d`` elements (Sec. 3.2).
 ``VeLoRALlamaMLP`` applies the same rule to a whole gated MLP block: the block
 input is compressed once for the gate and up projections, and the down
 projection's input is compressed by the kernel that produces it.
+``VeLoRANormLinears`` does it for the input side of an attention block: RMSNorm
+and compress in one kernel, one S for the q, k and v projections.
 """
 from __future__ import annotations
 
@@ -211,3 +213,76 @@ class VeLoRALlamaMLP(torch.nn.Module):
             self.init_v(h.detach())
         gate, up = _SharedInputLinearsFunction.apply(h, self.w_gate, self.w_up, self.v_h, self.M_h)
         return _SwiGLUDownFunction.apply(gate, up, self.w_down, self.v_f, self.M_f)
+
+
+class _NormLinearsFunction(torch.autograd.Function):
+    """RMSNorm followed by several bias-free linears on the normalised input (an attention block's
+    q, k, v projections; the paper's LLaMA runs compress the value projection's input, Sec. 4).
+    ``velora_rmsnorm_compress`` writes the normalised input X and S = compress(X, v) in one pass;
+    X feeds the dense products and is then dropped, S is kept once for all the weight gradients,
+    and h stays because the normalisation's own backward needs it (as it does without VeLoRA)."""
+
+    @staticmethod
+    def forward(ctx, h, gamma, v, M, eps, *weights):
+        H = h.shape[-1]
+        h2 = h.reshape(-1, H)
+        if not h2.is_contiguous():
+            h2 = h2.contiguous()
+        X, S = _b.velora_rmsnorm_compress(h2, gamma, eps, v, M)
+        outs = tuple(torch.matmul(X, w.t()).reshape(*h.shape[:-1], w.shape[0]) for w in weights)
+        del X
+        ctx.save_for_backward(h2, gamma, S, v, *weights)
+        ctx.in_shape, ctx.eps = h.shape, eps
+        return outs
+
+    @staticmethod
+    def backward(ctx, *grads):
+        h2, gamma, S, v, *weights = ctx.saved_tensors
+        H = h2.shape[1]
+        gs = [g.reshape(-1, w.shape[0]).contiguous() for g, w in zip(grads, weights)]
+        grad_ws = [(_b.velora_weight_grad(g, S, v, H, dw_dtype=w.dtype) if ctx.needs_input_grad[5 + i] else None)
+                   for i, (g, w) in enumerate(zip(gs, weights))]
+        grad_h = grad_gamma = None
+        if ctx.needs_input_grad[0] or ctx.needs_input_grad[1]:
+            dX = torch.matmul(gs[0], weights[0]).float()
+            for g, w in zip(gs[1:], weights[1:]):
+                dX += torch.matmul(g, w).float()
+            hf = h2.float()
+            rinv = torch.rsqrt(hf.pow(2).mean(dim=-1, keepdim=True) + ctx.eps)
+            xhat = hf * rinv
+            if ctx.needs_input_grad[1]:
+                grad_gamma = (dX * xhat).sum(dim=0)
+            if ctx.needs_input_grad[0]:
+                dxg = dX * gamma
+                grad_h = (rinv * (dxg - xhat * (dxg * xhat).mean(dim=-1, keepdim=True))).to(h2.dtype).reshape(ctx.in_shape)
+        return (grad_h, grad_gamma, None, None, None, *grad_ws)
+
+
+class VeLoRANormLinears(torch.nn.Module):
+    """``RMSNorm(h) -> [linear_i]``: the input side of a LLaMA attention block (q, k, v) with VeLoRA on the
+    projections.  ``out_features`` lists the projections' widths; one ``v`` and one ``S`` serve all of them."""
+
+    def __init__(self, hidden: int, out_features, sub_token_size: int, eps: float = 1e-5, device=None, dtype=None):
+        super().__init__()
+        if hidden % sub_token_size:
+            raise ValueError("sub_token_size must divide the hidden width")
+        self.hidden, self.M, self.eps = hidden, hidden // sub_token_size, eps
+        self.gamma = torch.nn.Parameter(torch.ones(hidden, device=device, dtype=torch.float32))
+        self.weights = torch.nn.ParameterList(
+            [torch.nn.Parameter(torch.nn.init.normal_(torch.empty((o, hidden), device=device, dtype=dtype),
+                                                      std=hidden ** -0.5)) for o in out_features])
+        self.register_buffer("v", torch.zeros(sub_token_size, device=device, dtype=torch.float32))
+        self.register_buffer("v_ready", torch.zeros((), device=device, dtype=torch.bool))
+
+    @torch.no_grad()
+    def init_v(self, h: torch.Tensor) -> None:
+        """v from the first batch's normalised input (Sec. 3.3)."""
+        hf = h.reshape(-1, self.hidden).float()
+        x = (hf * torch.rsqrt(hf.pow(2).mean(dim=-1, keepdim=True) + self.eps) * self.gamma).to(h.dtype)
+        _b.velora_init_v(x.contiguous(), self.M, v=self.v, allow_degenerate=True)
+        self.v_ready.fill_(True)
+
+    def forward(self, h: torch.Tensor):
+        if not bool(self.v_ready):
+            self.init_v(h.detach())
+        return _NormLinearsFunction.apply(h, self.gamma, self.v, self.M, self.eps, *self.weights)

@@ -209,3 +209,64 @@ def test_llama_mlp_block_keeps_scalars_instead_of_inputs(mods):
     # gate and up (for the activation's backward) plus one scalar per sub-token of h and of the product;
     # neither h (N*H) nor the product (N*F) is kept
     assert sum(seen.values()) == 2 * N * F * 2 + N * (H // d_h) * 2 + N * (F // d_f) * 2
+
+
+def test_norm_qkv_block_matches_the_same_rule_in_plain_torch(mods):
+    torch, va = mods
+    torch.manual_seed(5)
+    N, H, d = 384, 512, 64
+    blk = va.VeLoRANormLinears(H, (H, 256, 256), d, device="cuda", dtype=torch.bfloat16)
+    with torch.no_grad():
+        blk.gamma.copy_(torch.linspace(0.5, 1.5, H, device="cuda"))
+    h = (torch.randn(N, H, device="cuda") + 0.3).to(torch.bfloat16).requires_grad_(True)
+    gouts = [(torch.randn(N, o, device="cuda") * 0.05).to(torch.bfloat16) for o in (H, 256, 256)]
+    outs = blk(h)
+    torch.autograd.backward(outs, gouts)
+    torch.cuda.synchronize()
+    # the same rule with plain torch ops: dense forward, weight gradients from reconstruct(compress(X))
+    hf = h.detach().float()
+    rinv = torch.rsqrt(hf.pow(2).mean(-1, keepdim=True) + blk.eps)
+    X = (hf * rinv * blk.gamma.detach()).to(torch.bfloat16)
+    z = X.float().reshape(N, H // d, d)
+    s = (z @ blk.v).to(torch.bfloat16).float()
+    Xp = (s.unsqueeze(-1) * blk.v).reshape(N, H)
+
+    def rel(a, b):
+        return ((a.float() - b.float()).norm() / b.float().norm()).item()
+
+    dX = torch.zeros(N, H, device="cuda")
+    for o, w, g in zip(outs, blk.weights, gouts):
+        assert rel(o, X @ w.detach().t()) <= 1e-2
+        assert rel(w.grad, g.float().t() @ Xp) <= 2e-2
+        dX += g.float() @ w.detach().float()
+    xhat = hf * rinv
+    dxg = dX * blk.gamma.detach()
+    want_h = rinv * (dxg - xhat * (dxg * xhat).mean(-1, keepdim=True))
+    assert rel(h.grad, want_h) <= 2e-2
+    assert rel(blk.gamma.grad, (dX * xhat).sum(0)) <= 2e-2
+    # and against autograd through torch's own rms_norm for the parts VeLoRA does not change
+    h2 = h.detach().clone().requires_grad_(True)
+    g2 = blk.gamma.detach().clone().requires_grad_(True)
+    Xr = torch.nn.functional.rms_norm(h2.float(), (H,), g2, blk.eps).to(torch.bfloat16)
+    torch.autograd.backward([Xr @ w.detach().t() for w in blk.weights], gouts)
+    assert rel(h.grad, h2.grad) <= 2e-2 and rel(blk.gamma.grad, g2.grad) <= 2e-2
+
+
+def test_norm_qkv_block_keeps_scalars_instead_of_the_normalised_input(mods):
+    torch, va = mods
+    N, H, d = 2048, 1024, 128
+    blk = va.VeLoRANormLinears(H, (H, H, H), d, device="cuda", dtype=torch.bfloat16)
+    blk.init_v(torch.randn(N, H, device="cuda", dtype=torch.bfloat16))
+    params = {p.data_ptr() for p in blk.parameters()} | {blk.v.data_ptr()}
+    seen = {}
+
+    def pack(t):
+        if t.data_ptr() not in params:
+            seen[t.data_ptr()] = t.numel() * t.element_size()
+        return t
+
+    h = torch.randn(N, H, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    with torch.autograd.graph.saved_tensors_hooks(pack, lambda t: t):
+        blk(h)
+    # h itself (for the normalisation's backward) and one scalar per sub-token; the normalised input is not kept
+    assert sum(seen.values()) == N * H * 2 + N * (H // d) * 2
