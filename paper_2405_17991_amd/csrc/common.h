@@ -38,7 +38,10 @@ __device__ __forceinline__ uint4 load_stream16(const uint4* p) {
 // ---- element traits for the two storage dtypes ------------------------------
 struct F32Elem {
     using type = float;
+    using vec = uint4;
     static constexpr int kPerVec = 4;  // elements in one 16-byte vector
+    __device__ static __forceinline__ vec load_stream(const vec* p) { return load_stream16(p); }
+    __device__ static __forceinline__ vec zero_vec() { return make_uint4(0u, 0u, 0u, 0u); }
     __device__ static __forceinline__ float load(const void* p, int64_t i) { return static_cast<const float*>(p)[i]; }
     __device__ static __forceinline__ void store(void* p, int64_t i, float x) { static_cast<float*>(p)[i] = x; }
     __device__ static __forceinline__ void unpack(const uint4& q, float* f) {
@@ -48,12 +51,31 @@ struct F32Elem {
 };
 struct Bf16Elem {
     using type = uint16_t;
+    using vec = uint4;
     static constexpr int kPerVec = 8;
+    __device__ static __forceinline__ vec load_stream(const vec* p) { return load_stream16(p); }
+    __device__ static __forceinline__ vec zero_vec() { return make_uint4(0u, 0u, 0u, 0u); }
     __device__ static __forceinline__ float load(const void* p, int64_t i) { return bf16_to_f32(static_cast<const uint16_t*>(p)[i]); }
     __device__ static __forceinline__ void store(void* p, int64_t i, float x) { static_cast<uint16_t*>(p)[i] = f32_to_bf16(x); }
     __device__ static __forceinline__ void unpack(const uint4& q, float* f) {
         f[0] = bf16_lo(q.x); f[1] = bf16_hi(q.x); f[2] = bf16_lo(q.y); f[3] = bf16_hi(q.y);
         f[4] = bf16_lo(q.z); f[5] = bf16_hi(q.z); f[6] = bf16_lo(q.w); f[7] = bf16_hi(q.w);
+    }
+};
+
+// bfloat16 in 8-byte vectors of four: for sub-token sizes that are a multiple of 4 but not of 8
+struct Bf16Half {
+    using type = uint16_t;
+    using vec = uint2;
+    static constexpr int kPerVec = 4;
+    __device__ static __forceinline__ vec load_stream(const vec* p) {
+        const u32x2 q = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+        return make_uint2(q.x, q.y);
+    }
+    __device__ static __forceinline__ vec zero_vec() { return make_uint2(0u, 0u); }
+    __device__ static __forceinline__ void store(void* p, int64_t i, float x) { static_cast<uint16_t*>(p)[i] = f32_to_bf16(x); }
+    __device__ static __forceinline__ void unpack(const uint2& q, float* f) {
+        f[0] = bf16_lo(q.x); f[1] = bf16_hi(q.x); f[2] = bf16_lo(q.y); f[3] = bf16_hi(q.y);
     }
 };
 

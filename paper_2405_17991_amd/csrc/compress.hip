@@ -10,6 +10,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace velora {
 
 // ---------------------------------------------------------------------------
@@ -24,11 +26,11 @@ namespace velora {
 // stores form one contiguous run of S.
 // ---------------------------------------------------------------------------
 template <typename E, int P, int L, int U>
-__global__ __launch_bounds__(256) void compress_vec_kernel(const uint4* __restrict__ X,
+__global__ __launch_bounds__(256) void compress_vec_kernel(const typename E::vec* __restrict__ X,
                                                           const float* __restrict__ v,
                                                           typename E::type* __restrict__ S,
                                                           int64_t n_sub, int vps) {
-    // vps = 16-byte vectors per sub-token, P * (L - 1) < vps <= P * L: when d / kPerVec is not a power of
+    // vps = vectors (16 bytes; 8 for Bf16Half) per sub-token, P * (L - 1) < vps <= P * L: when d / kPerVec is not a power of
     // two the lanes (and vectors) past vps stay idle and contribute zeros
     constexpr int kV = E::kPerVec;
     constexpr int SEG = kWave / P;
@@ -48,13 +50,13 @@ __global__ __launch_bounds__(256) void compress_vec_kernel(const uint4* __restri
 
     for (int64_t chunk = wave; chunk < n_chunks; chunk += n_waves) {
         const int64_t k0 = chunk * (SEG * U) + static_cast<int64_t>(seg) * U;
-        uint4 q[U][L];
+        typename E::vec q[U][L];
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int l = 0; l < L; ++l) {
-                q[u][l] = make_uint4(0u, 0u, 0u, 0u);
-                if (k0 + u < n_sub && l * P + p < vps) q[u][l] = load_stream16(&X[(k0 + u) * vps + l * P + p]);
+                q[u][l] = E::zero_vec();
+                if (k0 + u < n_sub && l * P + p < vps) q[u][l] = E::load_stream(&X[(k0 + u) * vps + l * P + p]);
             }
         float sum[U];
 #pragma unroll
@@ -205,7 +207,7 @@ hipError_t launch_compress_vec(const void* X, const float* v, void* S, int64_t n
     const int64_t n_chunks = ceil_div(n_sub, static_cast<int64_t>(SEG) * U);
     const int grid = grid_for(n_chunks, kBlock / kWave, cfg.max_blocks);
     hipLaunchKernelGGL((compress_vec_kernel<E, P, L, U>), dim3(grid), dim3(kBlock), 0, st,
-                       static_cast<const uint4*>(X), v, static_cast<typename E::type*>(S), n_sub, vps);
+                       static_cast<const typename E::vec*>(X), v, static_cast<typename E::type*>(S), n_sub, vps);
     return hipGetLastError();
 }
 
@@ -235,6 +237,14 @@ hipError_t compress_any(const void* X, const float* v, void* S, int64_t n_sub, i
         bool handled = false;
         hipError_t e = dispatch_compress_vec<E>(static_cast<int>(d / E::kPerVec), X, v, S, n_sub, cfg, st, &handled);
         if (handled) return e;
+    }
+    if constexpr (std::is_same<E, Bf16Elem>::value) {
+        // a multiple of 4 but not of 8 (the 11008-wide layer at 64 sub-tokens per token: d = 172): 8-byte vectors
+        if (d % 4 == 0 && (reinterpret_cast<uintptr_t>(X) & 7) == 0) {
+            bool handled = false;
+            hipError_t e = dispatch_compress_vec<Bf16Half>(static_cast<int>(d / 4), X, v, S, n_sub, cfg, st, &handled);
+            if (handled) return e;
+        }
     }
     int P = 1;
     while (P < kWave && P < d) P <<= 1;

@@ -39,6 +39,9 @@ COMPRESS_CASES = [
     (203, 72, 24, wl.BF16), (131, 120, 40, wl.BF16), (97, 2 * 344, 344, wl.BF16), (515, 3 * 344, 344, wl.F32),
     (67, 2 * 776, 776, wl.BF16), (45, 2 * 1032, 1032, wl.BF16), (29, 2040, 2040, wl.BF16), (33, 3 * 12, 12, wl.F32),
     (21, 2 * 1020, 1020, wl.F32), (150, 11008, 344, wl.BF16),
+    # bf16 sub-token sizes that are a multiple of 4 but not of 8: 8-byte vectors
+    (97, 2 * 172, 172, wl.BF16), (150, 11008, 172, wl.BF16), (203, 5 * 4, 4, wl.BF16), (131, 3 * 20, 20, wl.BF16),
+    (45, 2 * 1028, 1028, wl.BF16), (64, 11008, 1376, wl.BF16), (64, 11008, 688, wl.BF16),
     # generic kernel: d not a power of two times the vector width, d = 1, d = D
     (50, 60, 12, wl.BF16), (50, 63, 7, wl.F32), (31, 33, 1, wl.BF16), (17, 100, 100, wl.F32),
     (11, 3000, 3000, wl.BF16), (1, 8, 8, wl.BF16), (1, 1, 1, wl.F32),
@@ -64,7 +67,7 @@ def test_compress_matches_oracle(vl, N, D, d, dtype):
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
-@pytest.mark.parametrize("d", [8, 64, 256, 12, 24, 344, 1032])
+@pytest.mark.parametrize("d", [8, 64, 256, 12, 24, 344, 1032, 172, 20])
 def test_compress_gather_is_bit_exact(vl, dtype, d):
     # v = e_j: compress degenerates to a gather, so the indexing (group) is
     # checked with no rounding at all.

@@ -141,6 +141,10 @@ def all_shapes() -> List[Shape]:
     s.append(_mk("paper7b_attn_m32", 6, BF16, n4, 4096, 4096, 128, "student_t4", 0.005, 0))
     s.append(_mk("paper7b_up_m32", 6, BF16, n4, 4096, 11008, 128, "student_t4", 0.005, 1))
     s.append(_mk("paper7b_down_m32", 6, BF16, n4, 11008, 4096, 344, "student_t4", 0.005, 2))
+    # the other sub-token counts of the paper's ablation (8, 16, 64 per token) on the same 11008-wide input
+    s.append(_mk("paper7b_down_m8", 6, BF16, n4, 11008, 4096, 1376, "student_t4", 0.005, 3))
+    s.append(_mk("paper7b_down_m16", 6, BF16, n4, 11008, 4096, 688, "student_t4", 0.005, 4))
+    s.append(_mk("paper7b_down_m64", 6, BF16, n4, 11008, 4096, 172, "student_t4", 0.005, 5))
     return s
 
 
