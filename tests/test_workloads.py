@@ -64,3 +64,16 @@ def test_distributions():
 def test_random_unit_v():
     v = wl.random_unit_v(256, 3)
     assert v.dtype == np.float32 and abs(np.linalg.norm(v.astype(np.float64)) - 1) < 1e-6
+
+
+def test_two_bfloat16_parts_carry_a_float32_to_17_bits():
+    """The GEMM that forms S inside its own tiles (velora_linear_compress) feeds v to the matrix
+    pipes as hi + lo, two bfloat16 numbers: hi = bf16(v), lo = bf16(v - hi).  The stated bound
+    |v - hi - lo| <= 2^-17 |v| is arithmetic, checked here with the generators' own rounding."""
+    rng = np.random.default_rng(11)
+    v = np.concatenate([rng.standard_normal(20000), rng.standard_normal(2000) * 1e-6,
+                        np.array([1.0, -1.0, 0.0, 1.0 + 2.0 ** -8, 3.0 - 2.0 ** -7])]).astype(np.float32)
+    hi = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(v))
+    lo = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits((v - hi).astype(np.float32)))
+    err = np.abs(v.astype(np.float64) - hi.astype(np.float64) - lo.astype(np.float64))
+    assert (err <= 2.0 ** -17 * np.abs(v.astype(np.float64))).all()
