@@ -9,9 +9,9 @@
 // already an MFMA fragment; LDS rows are 128 bytes, eight 16-byte chunks, chunk
 // c of row r stored at position c ^ ((r >> 1) & 7), which makes both the linear
 // writes and the fragment reads (16 rows x one chunk) bank-conflict free.
-// Two LDS stages (2 x 64 KB).  What bounds the loop is the number of cache-line
-// requests a CU can have outstanding (~70 x 128 B at ~500 cycles from L2), so
-// the request queue must never drain at a wait point and loads must not arrive in
+// Two LDS stages (2 x 64 KB).  A step needs 512 cache lines per block and a CU
+// keeps about 70 requests of 128 B outstanding (300-500 cycles from L2), so the
+// request queue must never drain at a wait point and loads must not arrive in
 // bursts (a wave that cannot issue a load issues no MFMA either).  Two streams,
 // one load instruction after every eight MFMAs:
 //   W tiles: global -> registers during the first half of step t (for step
