@@ -192,3 +192,27 @@ def test_grad_input_full_size_sampled(vl):
     idx = torch.from_numpy(rows).cuda()
     dX_exact, dX_store = oracle.grad_input(to_host_bits(Gd[idx]), to_host_bits(Wd))
     assert_bf16_store_matches(to_host_bits(dXd[idx]), dX_exact, dX_store, "dX rows")
+
+
+@pytest.mark.parametrize("name", ["cfg2_vit_fc1", "cfg3_up", "cfg4_up", "cfg5_down_d256", "paper7b_down_m32", "cfg5_up_d64"])
+def test_dense_products_at_other_full_sizes_sampled(vl, name):
+    """Forward (with S) and input gradient at the real layer sizes of the other configurations; the oracle
+    computes sampled token rows one by one (tile edges, first and last rows)."""
+    import torch
+    sh = wl.shape_by_name(name)
+    torch.manual_seed(sh.N % 97)
+    Xd = torch.randn((sh.N, sh.D), device="cuda").to(torch.bfloat16)
+    Wd = (torch.randn((sh.O, sh.D), device="cuda") * sh.D ** -0.5).to(torch.bfloat16)
+    Gd = (torch.randn((sh.N, sh.O), device="cuda") * 0.05).to(torch.bfloat16)
+    v = wl.random_unit_v(sh.d, 3)
+    Yd, Sd = vl.velora_linear_compress(Xd, Wd, to_dev(v, wl.F32), sh.M)
+    dXd = vl.velora_grad_input(Gd, Wd)
+    torch.cuda.synchronize()
+    rows = np.array(sorted({0, 1, 255, 256, 257, sh.N // 2 + 3, sh.N - (sh.N % 256 or 256) - 1, sh.N - 2, sh.N - 1}))
+    idx = torch.from_numpy(rows).cuda()
+    W = to_host_bits(Wd)
+    Y_exact, Y_store, S_exact, S_store = oracle.linear_compress(to_host_bits(Xd[idx]), W, v, sh.M)
+    assert_bf16_store_matches(to_host_bits(Yd[idx]), Y_exact, Y_store, "Y rows")
+    assert_bf16_store_matches(to_host_bits(Sd[idx]), S_exact, S_store, "S rows")
+    dX_exact, dX_store = oracle.grad_input(to_host_bits(Gd[idx]), W)
+    assert_bf16_store_matches(to_host_bits(dXd[idx]), dX_exact, dX_store, "dX rows")
