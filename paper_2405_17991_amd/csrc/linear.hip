@@ -12,21 +12,28 @@
 // Two LDS stages (2 x 64 KB).  A step needs 512 cache lines per block and a CU
 // keeps about 70 requests of 128 B outstanding (300-500 cycles from L2), so the
 // request queue must never drain at a wait point and loads must not arrive in
-// bursts (a wave that cannot issue a load issues no MFMA either).  Two streams,
-// one load instruction after every eight MFMAs:
-//   W tiles: global -> registers during the first half of step t (for step
-//            t+2), awaited at the end of step t and written to LDS there;
+// bursts (a wave that cannot issue a load issues no MFMA either).  A step is two
+// halves of 64 MFMAs (eight rows of eight); after every row come two LDS reads
+// of the next half's fragments (fragments are double-buffered in registers) and
+// one instruction of each load stream:
+//   W tiles: pass through registers.  First half of step t: piece i of W(t+1)
+//            goes from registers to its LDS stage, then a load refills the
+//            register with W(t+2) (a full step in flight);
 //   A tiles: global -> LDS directly (buffer_load ... lds) during the second half
 //            of step t (for step t+2), awaited at the middle of step t+1.
-// At each wait the other stream's batch is still in flight (s_waitcnt vmcnt(8),
-// vector-memory operations complete in order).  Fragments are double-buffered in
-// registers: the LDS reads for the next 32-k half run under the 64 MFMAs of the
-// current one.  The counted waits stay correct if further vector-memory
-// operations are issued inside the loop (each wait only needs eight younger
-// loads behind the batch it waits for, and loads complete in order), but every
-// such operation makes a wait cover more than it needs and costs overlap: v is
-// therefore staged in LDS before the loop, and the build rejects register
-// spills in this kernel.
+// One barrier per step, between the halves: before it every wave has finished
+// reading stage t&1 (its fragments for the second half are in registers) and
+// has A(t+1) and W(t+1) in stage (t+1)&1 (s_waitcnt vmcnt(8): the eight younger
+// loads are W(t+2); vector-memory operations complete in order).
+// The MFMAs are inline assembly with the accumulators tied to AGPRs.  With the
+// builtin, the register allocator starts to move accumulators between the two
+// register files as soon as other instructions sit between the MFMAs (hundreds
+// of copies per step, or spills); tied to AGPRs the 256 accumulators stay put
+// and the loop is exactly the sequence written here.  The counted wait stays
+// correct if the compiler adds vector-memory operations (a spill) inside the
+// loop, since it only needs eight younger loads behind the batch it waits for,
+// but each such operation costs overlap: v is therefore staged in LDS before
+// the loop, and the build rejects register spills in this kernel.
 // Block order: consecutive block ids land on different XCDs (one L2 each), so
 // XCD x takes a contiguous run of tile ids, and ids are laid out in groups of
 // four token tiles (output tiles outer): the 32 blocks an XCD runs together
@@ -129,33 +136,26 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         for (int i = 0; i < 8; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, to_lds(st + i * 1024), 16, gvoff[i], tc * kBK * 2, 0, 0);
     };
-    u32x4 wreg[8];
-    auto regload_w = [&](int t) {
-        const int tc = t < nk ? t : nk - 1;
-        const __amdgpu_buffer_rsrc_t rw = w_rsrc(tc);
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            wreg[i] = NN ? __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff_nn, i * C * 2, 0)      // row 8kg + i
-                         : __builtin_amdgcn_raw_buffer_load_b128(rw, gvoff[i], tc * kBK * 2, 0);
+    // The W stream passes through registers.
+    u32x4 wregP[8], wregQ[8];
+    auto load_w_piece = [&](u32x4& r, int i, const __amdgpu_buffer_rsrc_t& rw, int tc) {
+        r = NN ? __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff_nn, i * C * 2, 0)        // row 8kg + i
+               : __builtin_amdgcn_raw_buffer_load_b128(rw, gvoff[i], tc * kBK * 2, 0);
     };
-    auto store_w = [&](int t) {
+    auto store_w_piece = [&](const u32x4 (&wr)[8], int i, int t) {
         if constexpr (NN) {
-            // column 8*chunk + c of the 8 x 8 block -> k chunk kg of LDS row 8*chunk + c (swizzled as above)
+            // column 8*chunk + i of the 8 x 8 block -> k chunk kg of LDS row 8*chunk + i (swizzled as above)
             char* st = lds + (t & 1) * kStage + kBM * kRowB;
             RawRow<4> rows[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                rows[r].w[0] = wreg[r].x; rows[r].w[1] = wreg[r].y; rows[r].w[2] = wreg[r].z; rows[r].w[3] = wreg[r].w;
+                rows[r].w[0] = wr[r].x; rows[r].w[1] = wr[r].y; rows[r].w[2] = wr[r].z; rows[r].w[3] = wr[r].w;
             }
-#pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const int n = chunk_w * 8 + c;
-                *reinterpret_cast<bf16x8*>(st + n * kRowB + ((kg ^ ((n >> 1) & 7)) * 16)) = column_fragment(rows, c);
-            }
+            const int n = chunk_w * 8 + i;
+            *reinterpret_cast<bf16x8*>(st + n * kRowB + ((kg ^ ((n >> 1) & 7)) * 16)) = column_fragment(rows, i);
         } else {
             char* st = lds + (t & 1) * kStage + kBM * kRowB + w * (kBN * kRowB / 4);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(st + i * 1024 + lane * 16) = wreg[i];
+            *reinterpret_cast<u32x4*>(st + i * 1024 + lane * 16) = wr[i];
         }
     };
     // fragment of rows base + 16b + jj, chunk 4*kk + q; (row >> 1) & 7 == (jj >> 1) & 7 because base is a multiple of 16
@@ -163,14 +163,11 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
         foff[kk] = static_cast<uint32_t>(jj) * kRowB + static_cast<uint32_t>(((kk * 4 + q) ^ ((jj >> 1) & 7)) * 16);
-    auto fread = [&](bf16x8 (&fx)[8], bf16x8 (&fw)[8], int t, int kk) {
-        const char* st = lds + (t & 1) * kStage;
-#pragma unroll
-        for (int b = 0; b < 8; ++b)
-            fx[b] = *reinterpret_cast<const bf16x8*>(st + (wm * 128 + b * 16) * kRowB + foff[kk]);
-#pragma unroll
-        for (int a = 0; a < 8; ++a)
-            fw[a] = *reinterpret_cast<const bf16x8*>(st + (kBM + wn * 128 + a * 16) * kRowB + foff[kk]);
+    auto fread_x = [&](int b, int t, int kk) -> bf16x8 {
+        return *reinterpret_cast<const bf16x8*>(lds + (t & 1) * kStage + (wm * 128 + b * 16) * kRowB + foff[kk]);
+    };
+    auto fread_w = [&](int a, int t, int kk) -> bf16x8 {
+        return *reinterpret_cast<const bf16x8*>(lds + (t & 1) * kStage + (kBM + wn * 128 + a * 16) * kRowB + foff[kk]);
     };
 
     // v = hi + lo as bf16, staged behind the two stages: vtab[0][j] = hi, vtab[1][j] = lo
@@ -195,33 +192,6 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc_s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // 64 MFMAs with one load instruction after every eight: a load then finds room in the CU's request queue
-    // instead of arriving in a burst that blocks the wave (and with it the MFMA issue)
-    auto mma_w = [&](const bf16x8 (&fx)[8], const bf16x8 (&fw)[8], int t) {      // + W(t) -> registers
-        const int tc = t < nk ? t : nk - 1;
-        const __amdgpu_buffer_rsrc_t rw = w_rsrc(tc);
-#pragma unroll
-        for (int a = 0; a < 8; ++a) {
-#pragma unroll
-            for (int b = 0; b < 8; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[a], fx[b], acc[a][b], 0, 0, 0);
-            wreg[a] = NN ? __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff_nn, a * C * 2, 0)      // row 8kg + a
-                         : __builtin_amdgcn_raw_buffer_load_b128(rw, gvoff[a], tc * kBK * 2, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    auto mma_x = [&](const bf16x8 (&fx)[8], const bf16x8 (&fw)[8], int t) {      // + A(t) -> its LDS stage
-        char* st = lds + (t & 1) * kStage;
-        const int koff = (t < nk ? t : nk - 1) * kBK * 2;
-#pragma unroll
-        for (int a = 0; a < 8; ++a) {
-#pragma unroll
-            for (int b = 0; b < 8; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[a], fx[b], acc[a][b], 0, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, to_lds(st + (w * 64 + a * 8) * kRowB), 16, gvoff[a], koff, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
     // A operand with v: row 0 = hi, row 1 = lo, rows 2..15 zero; k = 8q .. 8q+7 of this 32-k half
     auto v_fragment = [&](int t, int kk) -> bf16x8 {
         const int vk = (t * kBK + kk * 32) % d + q * 8;
@@ -229,16 +199,29 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         const u32x4 zero = {0u, 0u, 0u, 0u};
         return __builtin_bit_cast(bf16x8, jj < 2 ? raw : zero);
     };
+    // Four more MFMAs per half with accumulators in ordinary VGPRs (the AGPRs are full), written like the main
+    // ones (see below).  The compiler does not know that this statement holds MFMAs, and it may put register
+    // copies or the select of v_fragment right next to it, so the statement brings its own wait states: a few
+    // before the first MFMA (operands just written by vector instructions) and 20 after the last (its result
+    // may be read by a vector instruction; 19 is the most this chip asks for).  The matrix pipe works through
+    // the four MFMAs meanwhile.
+#define VELORA_S_MFMAS(X0, X1, X2, X3)                                                                          \
+    asm volatile("s_nop 3\n\t"                                                                                \
+                 "v_mfma_f32_16x16x32_bf16 %0, %4, %5, %0\n\t"                                                \
+                 "v_mfma_f32_16x16x32_bf16 %1, %4, %6, %1\n\t"                                                \
+                 "v_mfma_f32_16x16x32_bf16 %2, %4, %7, %2\n\t"                                                \
+                 "v_mfma_f32_16x16x32_bf16 %3, %4, %8, %3\n\t"                                                \
+                 "s_nop 15\n\ts_nop 3"                                                                        \
+                 : "+v"(acc_s[0]), "+v"(acc_s[1]), "+v"(acc_s[2]), "+v"(acc_s[3])                               \
+                 : "v"(vf), "v"(X0), "v"(X1), "v"(X2), "v"(X3))
     auto mma_s = [&](const bf16x8 (&fx)[8], const bf16x8& vf) {
         if (wn == 0) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b) acc_s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, fx[b], acc_s[b], 0, 0, 0);
+            VELORA_S_MFMAS(fx[0], fx[1], fx[2], fx[3]);
         } else {
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc_s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, fx[b + 4], acc_s[b], 0, 0, 0);
+            VELORA_S_MFMAS(fx[4], fx[5], fx[6], fx[7]);
         }
     };
+#undef VELORA_S_MFMAS
     // lane (jj, q = 0) holds rows 0..3 of the result for token jj: S = row 0 + row 1
     auto flush_s = [&](int g) {
         const int M = K / d;
@@ -248,53 +231,115 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
             if (q == 0 && n < R) S[n * M + g] = f32_to_bf16(acc_s[b][0] + acc_s[b][1]);
             acc_s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
+        asm volatile("s_nop 7" ::: "memory");
     };
 
-    constexpr int kWaitVm8 = 0x0F78;              // s_waitcnt vmcnt(8), other counters unconstrained
+    // Half a step: 64 MFMAs in eight rows (one W fragment against the eight token fragments).  After every row
+    // come two LDS reads of the next half's fragments (token fragments first: row 0 of the next half needs all
+    // eight; then the W fragments in row order) and this half's share of the two load streams:
+    //   first half  (SECOND = false): one piece of the W tile held in registers (step tw) goes to its LDS stage,
+    //                                 and one load refills the other register set (step tl)
+    //   second half (SECOND = true):  one direct-to-LDS load of the A tile of step tl
+    // The MFMAs are written as inline assembly with the accumulators tied to AGPRs: with the builtin, the
+    // register allocator moves accumulators between the two register files as soon as loads are placed
+    // between the MFMAs.  The compiler does not know these statements are MFMAs, so it places no wait states
+    // for them; none are needed here: an accumulator is touched again 64 MFMAs later at the earliest, the
+    // operands come from LDS reads (s_waitcnt, which the compiler does place), and the epilogue waits below.
+    auto half = [&](auto second, const bf16x8 (&fx)[8], const bf16x8 (&fw)[8], bf16x8 (&nx)[8], bf16x8 (&nw)[8],
+                    bf16x8& nvf, int tf, int kf, int tl, const u32x4 (&wst)[8], u32x4 (&wld)[8]) {
+        constexpr bool SECOND = decltype(second)::value;
+        const int tc = tl < nk ? tl : nk - 1;     // steps past the end re-fetch the last k block (never used)
+        const __amdgpu_buffer_rsrc_t rw = w_rsrc(tc);
+        char* sx = lds + (tl & 1) * kStage;
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+#pragma unroll
+            for (int b = 0; b < 8; ++b)
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fw[a]), "v"(fx[b]));
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int i = a * 2 + h;
+                if (i < 8) nx[i] = fread_x(i, tf, kf);
+                else nw[i - 8] = fread_w(i - 8, tf, kf);
+            }
+            if constexpr (DO_S) {
+                if (a == 7) nvf = v_fragment(tf, kf);
+            }
+            if constexpr (SECOND) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, to_lds(sx + (w * 64 + a * 8) * kRowB), 16, gvoff[a],
+                                                         tc * kBK * 2, 0, 0);
+            } else {
+                store_w_piece(wst, a, tl - 1);
+                load_w_piece(wld[a], a, rw, tc);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
     constexpr int kWaitVm8Lgkm0 = 0x0078;         // s_waitcnt vmcnt(8) lgkmcnt(0)
     bf16x8 fxA[8], fwA[8], fxB[8], fwB[8];
     bf16x8 vfA = {}, vfB = {};
-    dma_x(0);
-    dma_x(1);
-    if constexpr (NN) {
-        regload_w(0);
-        store_w(0);
-        regload_w(1);
-        store_w(1);
-    } else {
-        dma_w(0);
-        dma_w(1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0);                // the first two steps' tiles have landed
-    __syncthreads();                              // (also publishes vtab)
-    fread(fxA, fwA, 0, 0);
-    if constexpr (DO_S) vfA = v_fragment(0, 0);
-    for (int t = 0; t < nk; ++t) {
-        fread(fxB, fwB, t, 1);
-        if constexpr (DO_S) vfB = v_fragment(t, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_w(fxA, fwA, t + 2);                   // first half: W(t+2) on its way to registers
+    // One step.  On entry: stage t&1 complete, fragments (t, kk0) in set A, W(t+1) in wst (or on its way).
+    auto step = [&](int t, const u32x4 (&wst)[8], u32x4 (&wld)[8]) {
         if constexpr (DO_S) mma_s(fxA, vfA);
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(kWaitVm8Lgkm0);   // A(t+1) landed; fragments B and this wave's W(t+1) stores done
+        // MFMAs (t, kk0); reads (t, kk1); W(t+1) -> stage (t+1)&1 (free since the previous barrier); W(t+2) -> registers
+        half(std::false_type{}, fxA, fwA, fxB, fwB, vfB, t, 1, t + 2, wst, wld);
+        __builtin_amdgcn_s_waitcnt(kWaitVm8Lgkm0);   // A(t+1) landed (the eight younger loads are W(t+2)); this wave's
+                                                     // LDS reads and its W(t+1) writes are done
         __syncthreads();                          // stage t&1 is free, stage (t+1)&1 is complete
-        if (t + 1 < nk) {
-            fread(fxA, fwA, t + 1, 0);
-            if constexpr (DO_S) vfA = v_fragment(t + 1, 0);
-        }
+        if constexpr (DO_S) mma_s(fxB, vfB);
         __builtin_amdgcn_sched_barrier(0);
-        mma_x(fxB, fwB, t + 2);                   // second half: A(t+2) on its way into stage t&1
+        // MFMAs (t, kk1); reads (t+1, kk0) (past the end: a stage nobody uses); A(t+2) -> stage t&1
+        half(std::true_type{}, fxB, fwB, fxA, fwA, vfA, t + 1, 0, t + 2, wst, wld);
         if constexpr (DO_S) {
-            mma_s(fxB, vfB);
             if (((t + 1) * kBK) % d == 0) flush_s((t * kBK) / d);
         }
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(kWaitVm8);    // W(t+2) is in registers; A(t+2) may still be in flight
-        store_w(t + 2);                           // stage t&1: free since this step's barrier
-        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    dma_x(0);
+    if constexpr (NN) {
+        const __amdgpu_buffer_rsrc_t rw0 = w_rsrc(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_w_piece(wregQ[i], i, rw0, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) store_w_piece(wregQ, i, 0);
+    } else {
+        dma_w(0);
+    }
+    dma_x(1);
+    {
+        const int tc = nk > 1 ? 1 : 0;
+        const __amdgpu_buffer_rsrc_t rw1 = w_rsrc(tc);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_w_piece(wregP[i], i, rw1, tc);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0);                // the first tiles have landed, W(1) is in registers
+    __syncthreads();                              // (also publishes vtab)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) fxA[b] = fread_x(b, 0, 0);
+#pragma unroll
+    for (int a = 0; a < 8; ++a) fwA[a] = fread_w(a, 0, 0);
+    if constexpr (DO_S) vfA = v_fragment(0, 0);
+    __builtin_amdgcn_s_waitcnt(0);                // the loop starts with nothing pending, as every later step does
+    __builtin_amdgcn_sched_barrier(0);
+    for (int t = 0; t < nk; ++t) {
+        if constexpr (NN) {
+            // the transposing store of piece i reads all eight registers of the tile, so the refill goes to a
+            // second set that becomes the first at the end of the step (it landed long before: it was
+            // requested in the first half)
+            step(t, wregP, wregQ);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) wregP[i] = wregQ[i];
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+            step(t, wregP, wregP);                // piece i is stored, then refilled
+        }
     }
     __builtin_amdgcn_s_waitcnt(0);                // nothing of this block is in flight when its LDS is released
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have written the accumulators read below
 
     // D[i = output 4q + r][j = token jj] per tile: four consecutive outputs of one token per lane
 #pragma unroll
