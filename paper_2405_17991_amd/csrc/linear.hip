@@ -341,17 +341,48 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     __builtin_amdgcn_s_waitcnt(0);                // nothing of this block is in flight when its LDS is released
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have written the accumulators read below
 
-    // D[i = output 4q + r][j = token jj] per tile: four consecutive outputs of one token per lane
+    // D[i = output 4q + r][j = token jj] per tile: four consecutive outputs of one token per lane.
+    if (C % 8 == 0) {
+        // Through LDS, so that the tile leaves in 16-byte stores that fill whole 128-byte pieces of a row
+        // (8-byte stores in 32-byte runs cost 1.3-1.7 times the bytes at the memory): in two passes of 64
+        // outputs the wave writes its 128 tokens x 64 outputs into its own region (rows 144 bytes apart,
+        // which spreads the 16 tokens of a tile over the banks), reads 16-byte pieces back, eight lanes per
+        // row, and stores them.  LDS serves a wave's operations in order, so the region needs no barrier
+        // of its own; the one below is for the stages it overlays.
+        __syncthreads();                          // every wave has read its last fragments
+        char* ep = lds + w * (128 * 144);
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
+        for (int p = 0; p < 2; ++p) {
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const int64_t n = n0 + wm * 128 + b * 16 + jj, o = o0 + wn * 128 + a * 16 + q * 4;
-            if (n < R && o < C) {   // C % 4 == 0: a lane's four outputs are all inside or all outside
-                const u32x2 out = {pack_bf16x2(acc[a][b][0], acc[a][b][1]), pack_bf16x2(acc[a][b][2], acc[a][b][3])};
-                *reinterpret_cast<u32x2*>(Out + n * C + o) = out;
+            for (int a4 = 0; a4 < 4; ++a4)
+#pragma unroll
+                for (int b = 0; b < 8; ++b) {
+                    const f32x4& c = acc[p * 4 + a4][b];
+                    const u32x2 out = {pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3])};
+                    *reinterpret_cast<u32x2*>(ep + (b * 16 + jj) * 144 + a4 * 32 + q * 8) = out;
+                }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = i * 8 + (lane >> 3), chunk = lane & 7;
+                const u32x4 piece = *reinterpret_cast<const u32x4*>(ep + row * 144 + chunk * 16);
+                const int64_t n = n0 + wm * 128 + row, o = o0 + wn * 128 + p * 64 + chunk * 8;
+                if (n < R && o < C) *reinterpret_cast<u32x4*>(Out + n * C + o) = piece;   // eight outputs: all inside or all outside
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
+    } else {
+#pragma unroll
+        for (int a = 0; a < 8; ++a)
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const int64_t n = n0 + wm * 128 + b * 16 + jj, o = o0 + wn * 128 + a * 16 + q * 4;
+                if (n < R && o < C) {   // C % 4 == 0: a lane's four outputs are all inside or all outside
+                    const u32x2 out = {pack_bf16x2(acc[a][b][0], acc[a][b][1]), pack_bf16x2(acc[a][b][2], acc[a][b][3])};
+                    *reinterpret_cast<u32x2*>(Out + n * C + o) = out;
+                }
+            }
+    }
 }
 
 // Out[R, C] = A[R, K] * W^T (NN = false, W[C, K]) or A * W (NN = true, W[K, C]); FUSE: S = compress(A, v) as well.
