@@ -39,13 +39,15 @@
 // four token tiles (output tiles outer): the 32 blocks an XCD runs together
 // cover about 4 token tiles x 8 output tiles.
 //
-// Compression inside the GEMM.  Blocks of the first output tile also form
-// S[n, g] = <X[n, g*d : (g+1)*d], v>.  v is split into two bf16 parts,
-// v = hi + lo (|v - hi - lo| <= 2^-17 |v|), which become rows 0 and 1 of an
-// otherwise zero 16-row A operand; one extra MFMA per token tile and 32-k half
-// multiplies it with the X fragments that are in registers anyway, accumulating
-// in float32, and rows 0 + 1 of the result are the dot.  d must be a multiple
-// of 64 (a k-step then lies inside one sub-token) and at most 2048.
+// Compression inside the GEMM.  The blocks of a token tile share out
+// S[n, g] = <X[n, g*d : (g+1)*d], v>: the block of output tile `to` takes the
+// sub-tokens g with g % To == to (To output tiles), so the extra work is spread
+// evenly.  v is split into two bf16 parts, v = hi + lo (|v - hi - lo| <=
+// 2^-17 |v|), which become rows 0 and 1 of an otherwise zero 16-row A operand;
+// one extra MFMA per token tile and 32-k half multiplies it with the X
+// fragments that are in registers anyway, accumulating in float32, and rows
+// 0 + 1 of the result are the dot.  d must be a multiple of 64 (a k-step then
+// lies inside one sub-token) and at most 2048.
 //
 // Everything the MFMA kernel cannot take (float32, d or D not a multiple of 64,
 // unaligned pointers) goes to a plain tiled FMA kernel plus the stand-alone
@@ -77,7 +79,7 @@ __device__ __forceinline__ lds_ptr to_lds(char* p) { return (lds_ptr)p; }
 //               through registers anyway, so a thread fetches an 8 k x 8 column block (eight 16-byte row
 //               pieces), transposes it in registers (column_fragment) and writes eight ready operands into
 //               the k-contiguous LDS layout of the forward; everything after that is the same code.
-//   DO_S: this block also forms S for its 256 rows (forward only).
+//   DO_S: this block also forms its share of S for its 256 rows (forward only).
 template <bool DO_S, bool NN>
 __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                                             const float* __restrict__ v, uint16_t* __restrict__ Out,
@@ -193,8 +195,8 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     for (int b = 0; b < 4; ++b) acc_s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // A operand with v: row 0 = hi, row 1 = lo, rows 2..15 zero; k = 8q .. 8q+7 of this 32-k half
-    auto v_fragment = [&](int t, int kk) -> bf16x8 {
-        const int vk = (t * kBK + kk * 32) % d + q * 8;
+    auto v_fragment = [&](int kpos, int kk) -> bf16x8 {      // kpos: the step's first k inside its sub-token
+        const int vk = kpos + kk * 32 + q * 8;
         const u32x4 raw = *reinterpret_cast<const u32x4*>(vtab + (jj & 1) * d + vk);
         const u32x4 zero = {0u, 0u, 0u, 0u};
         return __builtin_bit_cast(bf16x8, jj < 2 ? raw : zero);
@@ -246,7 +248,7 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     // for them; none are needed here: an accumulator is touched again 64 MFMAs later at the earliest, the
     // operands come from LDS reads (s_waitcnt, which the compiler does place), and the epilogue waits below.
     auto half = [&](auto second, const bf16x8 (&fx)[8], const bf16x8 (&fw)[8], bf16x8 (&nx)[8], bf16x8 (&nw)[8],
-                    bf16x8& nvf, int tf, int kf, int tl, const u32x4 (&wst)[8], u32x4 (&wld)[8]) {
+                    int tf, int kf, int tl, const u32x4 (&wst)[8], u32x4 (&wld)[8]) {
         constexpr bool SECOND = decltype(second)::value;
         const int tc = tl < nk ? tl : nk - 1;     // steps past the end re-fetch the last k block (never used)
         const __amdgpu_buffer_rsrc_t rw = w_rsrc(tc);
@@ -262,9 +264,6 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
                 if (i < 8) nx[i] = fread_x(i, tf, kf);
                 else nw[i - 8] = fread_w(i - 8, tf, kf);
             }
-            if constexpr (DO_S) {
-                if (a == 7) nvf = v_fragment(tf, kf);
-            }
             if constexpr (SECOND) {
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, to_lds(sx + (w * 64 + a * 8) * kRowB), 16, gvoff[a],
                                                          tc * kBK * 2, 0, 0);
@@ -278,22 +277,36 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
 
     constexpr int kWaitVm8Lgkm0 = 0x0078;         // s_waitcnt vmcnt(8) lgkmcnt(0)
     bf16x8 fxA[8], fwA[8], fxB[8], fwB[8];
-    bf16x8 vfA = {}, vfB = {};
+    // S is shared out over the blocks of a token tile: block `to` takes the sub-tokens g with g % To == to, so
+    // every block carries the same small extra (one in To of the steps has the eight extra MFMAs).
+    const int To = (C + kBN - 1) / kBN, to = static_cast<int>(o0 / kBN);
+    int s_g = 0, s_gmod = 0, s_kpos = 0;          // sub-token of the current step, g % To, first k inside it
     // One step.  On entry: stage t&1 complete, fragments (t, kk0) in set A, W(t+1) in wst (or on its way).
     auto step = [&](int t, const u32x4 (&wst)[8], u32x4 (&wld)[8]) {
-        if constexpr (DO_S) mma_s(fxA, vfA);
+        const bool s_mine = DO_S && s_gmod == to;   // uniform
+        if constexpr (DO_S) {
+            if (s_mine) mma_s(fxA, v_fragment(s_kpos, 0));
+        }
         __builtin_amdgcn_sched_barrier(0);
         // MFMAs (t, kk0); reads (t, kk1); W(t+1) -> stage (t+1)&1 (free since the previous barrier); W(t+2) -> registers
-        half(std::false_type{}, fxA, fwA, fxB, fwB, vfB, t, 1, t + 2, wst, wld);
+        half(std::false_type{}, fxA, fwA, fxB, fwB, t, 1, t + 2, wst, wld);
         __builtin_amdgcn_s_waitcnt(kWaitVm8Lgkm0);   // A(t+1) landed (the eight younger loads are W(t+2)); this wave's
                                                      // LDS reads and its W(t+1) writes are done
         __syncthreads();                          // stage t&1 is free, stage (t+1)&1 is complete
-        if constexpr (DO_S) mma_s(fxB, vfB);
+        if constexpr (DO_S) {
+            if (s_mine) mma_s(fxB, v_fragment(s_kpos, 1));
+        }
         __builtin_amdgcn_sched_barrier(0);
         // MFMAs (t, kk1); reads (t+1, kk0) (past the end: a stage nobody uses); A(t+2) -> stage t&1
-        half(std::true_type{}, fxB, fwB, fxA, fwA, vfA, t + 1, 0, t + 2, wst, wld);
+        half(std::true_type{}, fxB, fwB, fxA, fwA, t + 1, 0, t + 2, wst, wld);
         if constexpr (DO_S) {
-            if (((t + 1) * kBK) % d == 0) flush_s((t * kBK) / d);
+            s_kpos += kBK;
+            if (s_kpos == d) {                    // the sub-token ends with this step
+                if (s_mine) flush_s(s_g);
+                s_kpos = 0;
+                ++s_g;
+                s_gmod = s_gmod + 1 == To ? 0 : s_gmod + 1;
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -322,7 +335,6 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     for (int b = 0; b < 8; ++b) fxA[b] = fread_x(b, 0, 0);
 #pragma unroll
     for (int a = 0; a < 8; ++a) fwA[a] = fread_w(a, 0, 0);
-    if constexpr (DO_S) vfA = v_fragment(0, 0);
     __builtin_amdgcn_s_waitcnt(0);                // the loop starts with nothing pending, as every later step does
     __builtin_amdgcn_sched_barrier(0);
     for (int t = 0; t < nk; ++t) {
@@ -351,6 +363,11 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         // of its own; the one below is for the stages it overlays.
         __syncthreads();                          // every wave has read its last fragments
         char* ep = lds + w * (128 * 144);
+        // stores through a descriptor over this tile's valid rows: rows past R fall outside it and are
+        // dropped; a lane whose eight outputs lie past C gets an offset outside every descriptor
+        const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+            Out + n0 * C, 0, static_cast<int>(static_cast<int64_t>(rows_x) * C * 2), 0x00020000);
+        const uint32_t row_off = static_cast<uint32_t>(wm * 128 + (lane >> 3)) * static_cast<uint32_t>(C) * 2u;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
 #pragma unroll
@@ -362,13 +379,17 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
                     *reinterpret_cast<u32x2*>(ep + (b * 16 + jj) * 144 + a4 * 32 + q * 8) = out;
                 }
             __builtin_amdgcn_sched_barrier(0);
+            const int64_t o = o0 + wn * 128 + p * 64 + (lane & 7) * 8;
+            const uint32_t col_off = o < C ? row_off + static_cast<uint32_t>(o) * 2u : 0xFFFFFFFFu;
+            u32x4 piece[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = i * 8 + (lane >> 3), chunk = lane & 7;
-                const u32x4 piece = *reinterpret_cast<const u32x4*>(ep + row * 144 + chunk * 16);
-                const int64_t n = n0 + wm * 128 + row, o = o0 + wn * 128 + p * 64 + chunk * 8;
-                if (n < R && o < C) *reinterpret_cast<u32x4*>(Out + n * C + o) = piece;   // eight outputs: all inside or all outside
-            }
+            for (int i = 0; i < 16; ++i)
+                piece[i] = *reinterpret_cast<const u32x4*>(ep + (i * 8 + (lane >> 3)) * 144 + (lane & 7) * 16);
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                __builtin_amdgcn_raw_buffer_store_b128(
+                    piece[i], ro, o < C ? col_off + static_cast<uint32_t>(i * 8) * static_cast<uint32_t>(C) * 2u : 0xFFFFFFFFu,
+                    0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     } else {
@@ -404,13 +425,7 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t* __rest
     const int group_rows = Tn - first_tn < kGroup ? Tn - first_tn : kGroup;
     const int tn = first_tn + (vid % in_group) % group_rows, to = (vid % in_group) / group_rows;
     const int64_t n0 = static_cast<int64_t>(tn) * kBM, o0 = static_cast<int64_t>(to) * kBN;
-    if constexpr (FUSE) {
-        if (to == 0) {
-            linear_tile<true, false>(lds, A, W, v, Out, S, R, C, K, d, n0, o0);
-            return;
-        }
-    }
-    linear_tile<false, NN>(lds, A, W, v, Out, S, R, C, K, d, n0, o0);
+    linear_tile<FUSE, NN>(lds, A, W, v, Out, S, R, C, K, d, n0, o0);
 }
 
 // Any dtype, size and alignment: 64 x 64 output tile per block, 16-k slices through LDS, a 4 x 4 patch
