@@ -239,8 +239,8 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     // Half a step: 64 MFMAs in eight rows (one W fragment against the eight token fragments).  After every row
     // come two LDS reads of the next half's fragments (token fragments first: row 0 of the next half needs all
     // eight; then the W fragments in row order) and this half's share of the two load streams:
-    //   first half  (SECOND = false): one piece of the W tile held in registers (step tw) goes to its LDS stage,
-    //                                 and one load refills the other register set (step tl)
+    //   first half  (SECOND = false): one piece of the W tile held in registers (step tl - 1) goes to its LDS
+    //                                 stage, and one load of step tl refills that register (NN: the other set)
     //   second half (SECOND = true):  one direct-to-LDS load of the A tile of step tl
     // The MFMAs are written as inline assembly with the accumulators tied to AGPRs: with the builtin, the
     // register allocator moves accumulators between the two register files as soon as loads are placed
@@ -335,7 +335,10 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     for (int b = 0; b < 8; ++b) fxA[b] = fread_x(b, 0, 0);
 #pragma unroll
     for (int a = 0; a < 8; ++a) fwA[a] = fread_w(a, 0, 0);
-    __builtin_amdgcn_s_waitcnt(0);                // the loop starts with nothing pending, as every later step does
+    // Nothing is pending when the loop starts: the compiler merges the counters' state at this entry with the
+    // state at the back edge, and reads still outstanding here would make it wait for more at the top of
+    // every step.
+    __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_sched_barrier(0);
     for (int t = 0; t < nk; ++t) {
         if constexpr (NN) {
