@@ -77,7 +77,7 @@ __device__ __forceinline__ lds_ptr to_lds(char* p) { return (lds_ptr)p; }
 //   NN = false: B = W[C, K], k-contiguous (the forward: Out = X W^T)
 //   NN = true:  B = W[K, C], c-contiguous (the backward: grad_input = grad_output W).  The W stream passes
 //               through registers anyway, so a thread fetches an 8 k x 8 column block (eight 16-byte row
-//               pieces), transposes it in registers (column_fragment) and writes eight ready operands into
+//               pieces), transposes it in registers (v_perm_b32) and writes eight ready operands into
 //               the k-contiguous LDS layout of the forward; everything after that is the same code.
 //   DO_S: this block also forms its share of S for its 256 rows (forward only).
 template <bool DO_S, bool NN>
@@ -144,17 +144,19 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         r = NN ? __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff_nn, i * C * 2, 0)        // row 8kg + i
                : __builtin_amdgcn_raw_buffer_load_b128(rw, gvoff[i], tc * kBK * 2, 0);
     };
-    auto store_w_piece = [&](const u32x4 (&wr)[8], int i, int t) {
+    // NN: dword j of column i's fragment (rows 2j, 2j+1 of the 8 x 8 block share it); v_perm_b32 selector bytes
+    // 0-3 pick from the second operand, 4-7 from the first
+    auto w_column_dword = [&](const u32x4 (&wr)[8], int i, int j) -> uint32_t {
+        const uint32_t lo = wr[2 * j][i >> 1], hi = wr[2 * j + 1][i >> 1];
+        return (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+    };
+    // piece i of the W tile of step t, from registers to its LDS stage.  NT: the 16 bytes as loaded.  NN: `col`
+    // holds column 8*chunk + i of the 8 x 8 block, which is k chunk kg of LDS row 8*chunk + i (swizzled as above).
+    auto store_w_piece = [&](const u32x4 (&wr)[8], const u32x4& col, int i, int t) {
         if constexpr (NN) {
-            // column 8*chunk + i of the 8 x 8 block -> k chunk kg of LDS row 8*chunk + i (swizzled as above)
             char* st = lds + (t & 1) * kStage + kBM * kRowB;
-            RawRow<4> rows[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                rows[r].w[0] = wr[r].x; rows[r].w[1] = wr[r].y; rows[r].w[2] = wr[r].z; rows[r].w[3] = wr[r].w;
-            }
             const int n = chunk_w * 8 + i;
-            *reinterpret_cast<bf16x8*>(st + n * kRowB + ((kg ^ ((n >> 1) & 7)) * 16)) = column_fragment(rows, i);
+            *reinterpret_cast<u32x4*>(st + n * kRowB + ((kg ^ ((n >> 1) & 7)) * 16)) = col;
         } else {
             char* st = lds + (t & 1) * kStage + kBM * kRowB + w * (kBN * kRowB / 4);
             *reinterpret_cast<u32x4*>(st + i * 1024 + lane * 16) = wr[i];
@@ -236,9 +238,11 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
         asm volatile("s_nop 7" ::: "memory");
     };
 
-    // Half a step: 64 MFMAs in eight rows (one W fragment against the eight token fragments).  After every row
-    // come two LDS reads of the next half's fragments (token fragments first: row 0 of the next half needs all
-    // eight; then the W fragments in row order) and this half's share of the two load streams:
+    // Half a step: 64 MFMAs in eight rows (one W fragment against the eight token fragments).  Behind the first
+    // MFMAs of every row, one each (an instruction that follows an MFMA issues while the matrix pipe works on
+    // it; a group of several costs about five cycles apiece), come two LDS reads of the next half's fragments
+    // (token fragments first: row 0 of the next half needs all eight; then the W fragments in row order) and
+    // this half's share of the two load streams:
     //   first half  (SECOND = false): one piece of the W tile held in registers (step tl - 1) goes to its LDS
     //                                 stage, and one load of step tl refills that register (NN: the other set)
     //   second half (SECOND = true):  one direct-to-LDS load of the A tile of step tl
@@ -248,28 +252,47 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     // for them; none are needed here: an accumulator is touched again 64 MFMAs later at the earliest, the
     // operands come from LDS reads (s_waitcnt, which the compiler does place), and the epilogue waits below.
     auto half = [&](auto second, const bf16x8 (&fx)[8], const bf16x8 (&fw)[8], bf16x8 (&nx)[8], bf16x8 (&nw)[8],
-                    int tf, int kf, int tl, const u32x4 (&wst)[8], u32x4 (&wld)[8]) {
+                    int tf, int kf, int tl, u32x4 (&wst)[8], u32x4 (&wld)[8]) {
         constexpr bool SECOND = decltype(second)::value;
         const int tc = tl < nk ? tl : nk - 1;     // steps past the end re-fetch the last k block (never used)
         const __amdgpu_buffer_rsrc_t rw = w_rsrc(tc);
         char* sx = lds + (tl & 1) * kStage;
 #pragma unroll
         for (int a = 0; a < 8; ++a) {
+            u32x4 col = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int b = 0; b < 8; ++b)
+            for (int b = 0; b < 8; ++b) {
                 asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fw[a]), "v"(fx[b]));
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int i = a * 2 + h;
-                if (i < 8) nx[i] = fread_x(i, tf, kf);
-                else nw[i - 8] = fread_w(i - 8, tf, kf);
-            }
-            if constexpr (SECOND) {
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, to_lds(sx + (w * 64 + a * 8) * kRowB), 16, gvoff[a],
-                                                         tc * kBK * 2, 0, 0);
-            } else {
-                store_w_piece(wst, a, tl - 1);
-                load_w_piece(wld[a], a, rw, tc);
+                // one other instruction behind an MFMA issues in its shadow; several in a row do not
+                if (b < 2) {
+                    const int i = a * 2 + b;
+                    if (i < 8) nx[i] = fread_x(i, tf, kf);
+                    else nw[i - 8] = fread_w(i - 8, tf, kf);
+                } else if constexpr (SECOND) {
+                    if (b == 2)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, to_lds(sx + (w * 64 + a * 8) * kRowB), 16, gvoff[a],
+                                                                 tc * kBK * 2, 0, 0);
+                    if constexpr (NN) {
+                        // the refilled register moves over to the set the next step stores from; written as
+                        // assembly so that the two moves stay in these slots instead of sinking to the loop's end
+                        if (b == 3 || b == 4) {
+                            const int h = (b - 3) * 2;
+                            const u32x2 src = {wld[a][h], wld[a][h + 1]};
+                            u32x2 dst;
+                            asm volatile("v_mov_b64 %0, %1" : "=v"(dst) : "v"(src));
+                            wst[a][h] = dst[0];
+                            wst[a][h + 1] = dst[1];
+                        }
+                    }
+                } else if constexpr (NN) {        // four permutes build the column, then the store and the refill
+                    if (b < 6) col[b - 2] = w_column_dword(wst, a, b - 2);
+                    else if (b == 6) store_w_piece(wst, col, a, tl - 1);
+                    else load_w_piece(wld[a], a, rw, tc);
+                } else {
+                    if (b == 2) store_w_piece(wst, col, a, tl - 1);
+                    else if (b == 3) load_w_piece(wld[a], a, rw, tc);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -282,7 +305,7 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     const int To = (C + kBN - 1) / kBN, to = static_cast<int>(o0 / kBN);
     int s_g = 0, s_gmod = 0, s_kpos = 0;          // sub-token of the current step, g % To, first k inside it
     // One step.  On entry: stage t&1 complete, fragments (t, kk0) in set A, W(t+1) in wst (or on its way).
-    auto step = [&](int t, const u32x4 (&wst)[8], u32x4 (&wld)[8]) {
+    auto step = [&](int t, u32x4 (&wst)[8], u32x4 (&wld)[8]) {
         const bool s_mine = DO_S && s_gmod == to;   // uniform
         if constexpr (DO_S) {
             if (s_mine) mma_s(fxA, v_fragment(s_kpos, 0));
@@ -317,7 +340,11 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
 #pragma unroll
         for (int i = 0; i < 8; ++i) load_w_piece(wregQ[i], i, rw0, 0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) store_w_piece(wregQ, i, 0);
+        for (int i = 0; i < 8; ++i) {
+            const u32x4 col = {w_column_dword(wregQ, i, 0), w_column_dword(wregQ, i, 1), w_column_dword(wregQ, i, 2),
+                               w_column_dword(wregQ, i, 3)};
+            store_w_piece(wregQ, col, i, 0);
+        }
     } else {
         dma_w(0);
     }
@@ -341,17 +368,11 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_sched_barrier(0);
     for (int t = 0; t < nk; ++t) {
-        if constexpr (NN) {
-            // the transposing store of piece i reads all eight registers of the tile, so the refill goes to a
-            // second set that becomes the first at the end of the step (it landed long before: it was
-            // requested in the first half)
-            step(t, wregP, wregQ);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) wregP[i] = wregQ[i];
-            __builtin_amdgcn_sched_barrier(0);
-        } else {
-            step(t, wregP, wregP);                // piece i is stored, then refilled
-        }
+        // NN: the column of piece i is built from all eight registers of the tile, so the refill goes to a second
+        // set, which moves over during the second half (it was requested in the first).  NT: piece i is stored,
+        // then refilled in place.
+        if constexpr (NN) step(t, wregP, wregQ);
+        else step(t, wregP, wregP);
     }
     __builtin_amdgcn_s_waitcnt(0);                // nothing of this block is in flight when its LDS is released
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have written the accumulators read below
