@@ -52,7 +52,7 @@ def _check(vl, N, D, O, d, dtype, seed=0):
 FUSED = [(300, 128, 260, 64), (512, 256, 512, 128), (256, 64, 256, 64), (700, 192, 100, 64), (131, 2048, 64, 2048),
          (130, 4096, 68, 1024), (1, 64, 4, 64), (1030, 320, 1028, 64), (2304, 128, 2048, 128),
          # sub-tokens shared out over the output tiles: more sub-tokens than tiles (7 over 3), several k steps each
-         (300, 448, 600, 64), (260, 768, 520, 128), (257, 1536, 1024, 256)]
+         (300, 448, 600, 64), (260, 768, 520, 128), (257, 1536, 1024, 256), (300, 4096, 520, 2048)]
 # bf16 MFMA kernel for Y, compress kernel for S (d not a multiple of 64)
 UNFUSED = [(300, 128, 260, 32), (200, 704, 36, 88), (64, 4096, 8, 4096), (90, 64, 256, 8)]
 # everything else: plain FMA kernel (D % 64 != 0, O % 4 != 0)
