@@ -308,7 +308,7 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
     auto step = [&](int t, u32x4 (&wst)[8], u32x4 (&wld)[8]) {
         const bool s_mine = DO_S && s_gmod == to;   // uniform
         if constexpr (DO_S) {
-            if (s_mine) mma_s(fxA, v_fragment(s_kpos, 0));
+            if (__builtin_expect(s_mine, false)) mma_s(fxA, v_fragment(s_kpos, 0));
         }
         __builtin_amdgcn_sched_barrier(0);
         // MFMAs (t, kk0); reads (t, kk1); W(t+1) -> stage (t+1)&1 (free since the previous barrier); W(t+2) -> registers
@@ -317,14 +317,14 @@ __device__ __forceinline__ void linear_tile(char* lds, const uint16_t* __restric
                                                      // LDS reads and its W(t+1) writes are done
         __syncthreads();                          // stage t&1 is free, stage (t+1)&1 is complete
         if constexpr (DO_S) {
-            if (s_mine) mma_s(fxB, v_fragment(s_kpos, 1));
+            if (__builtin_expect(s_mine, false)) mma_s(fxB, v_fragment(s_kpos, 1));
         }
         __builtin_amdgcn_sched_barrier(0);
         // MFMAs (t, kk1); reads (t+1, kk0) (past the end: a stage nobody uses); A(t+2) -> stage t&1
         half(std::true_type{}, fxB, fwB, fxA, fwA, t + 1, 0, t + 2, wst, wld);
         if constexpr (DO_S) {
             s_kpos += kBK;
-            if (s_kpos == d) {                    // the sub-token ends with this step
+            if (__builtin_expect(s_kpos == d, false)) {   // the sub-token ends with this step
                 if (s_mine) flush_s(s_g);
                 s_kpos = 0;
                 ++s_g;
