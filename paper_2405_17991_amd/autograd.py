@@ -21,11 +21,55 @@ and compress in one kernel, one S for the q, k and v projections.
 """
 from __future__ import annotations
 
+import warnings
 from typing import Optional
 
 import torch
 
 from . import binding as _b
+
+
+class _FirstBatchV(torch.nn.Module):
+    """What the three wrapper modules share: the "is v set" flag.
+
+    ``v_ready`` is a buffer so that it travels with the state dict, but reading a device buffer
+    costs a device-to-host synchronisation; ``forward`` therefore looks at a host-side mirror
+    that ``init_v`` and state-dict loading keep in step.  ``v`` is taken from the first batch
+    seen in TRAINING mode (Sec. 3.2, "Cheap initialisation strategies"); a batch whose sub-token
+    mean is zero or not finite leaves the library's fallback direction in ``v`` for that batch
+    only, warns, and the next training batch tries again.
+    """
+
+    def _register_ready(self, device) -> None:
+        self.register_buffer("v_ready", torch.zeros((), device=device, dtype=torch.bool))
+        self._v_ready_host = False
+
+    def _load_from_state_dict(self, state_dict, prefix, *args, **kwargs):
+        super()._load_from_state_dict(state_dict, prefix, *args, **kwargs)
+        key = prefix + "v_ready"
+        if key in state_dict:
+            self._v_ready_host = bool(state_dict[key])     # one read at load time, none per step
+
+    def _init_vectors(self, pairs) -> None:
+        """pairs: [(batch [n, D], M, v buffer)]; sets the flag only if every mean was usable."""
+        ok = True
+        for x2, M, v in pairs:
+            try:
+                _b.velora_init_v(x2, M, v=v)
+            except _b.VeloraError as e:
+                if e.status != 6:
+                    raise
+                ok = False
+                warnings.warn("VeLoRA: the first batch's sub-token mean is zero or not finite; using the "
+                              "uniform direction for this batch and initialising v again from the next one")
+        if ok:
+            self.v_ready.fill_(True)
+            self._v_ready_host = True
+
+    def _need_v(self) -> bool:
+        """True when forward must initialise v first.  Outside training mode an uninitialised module
+        runs the plain dense forward (exact gradients, nothing compressed) instead."""
+        return self.training and not self._v_ready_host
 
 
 class VeLoRALinearFunction(torch.autograd.Function):
@@ -72,7 +116,7 @@ class VeLoRALinearFunction(torch.autograd.Function):
         return grad_input, grad_weight, None, None, None
 
 
-class VeLoRALinear(torch.nn.Module):
+class VeLoRALinear(_FirstBatchV):
     """Bias-free linear layer whose backward uses rank-1 sub-token projections.
 
     ``sub_token_size`` is d (the paper's "M"); ``in_features`` must be a
@@ -92,17 +136,17 @@ class VeLoRALinear(torch.nn.Module):
         torch.nn.init.normal_(w, std=in_features ** -0.5)
         self.weight = torch.nn.Parameter(w)
         self.register_buffer("v", torch.zeros(sub_token_size, device=device, dtype=torch.float32))
-        self.register_buffer("v_ready", torch.zeros((), device=device, dtype=torch.bool))
+        self._register_ready(device)
 
     @torch.no_grad()
     def init_v(self, batch: torch.Tensor) -> None:
-        x2 = batch.reshape(-1, self.in_features).contiguous()
-        _b.velora_init_v(x2, self.M, v=self.v, allow_degenerate=True)
-        self.v_ready.fill_(True)
+        self._init_vectors([(batch.reshape(-1, self.in_features).contiguous(), self.M, self.v)])
 
     def forward(self, input: torch.Tensor) -> torch.Tensor:
-        if not bool(self.v_ready):
+        if self._need_v():
             self.init_v(input.detach())
+        elif not self._v_ready_host:        # evaluation before any training batch: the plain layer
+            return torch.nn.functional.linear(input, self.weight)
         return VeLoRALinearFunction.apply(input, self.weight, self.v, self.M, self.own_gemm)
 
 
@@ -179,7 +223,7 @@ class _SwiGLUDownFunction(torch.autograd.Function):
         return grad_gate, grad_up, grad_w, None, None
 
 
-class VeLoRALlamaMLP(torch.nn.Module):
+class VeLoRALlamaMLP(_FirstBatchV):
     """LLaMA-style gated MLP, ``down(silu(gate(h)) * up(h))``, with VeLoRA on all three
     projections: ``h`` is compressed once for gate and up, and the down
     projection's input is compressed in the kernel that produces it.  Per token the
@@ -197,20 +241,21 @@ class VeLoRALlamaMLP(torch.nn.Module):
         self.w_gate, self.w_up, self.w_down = mk(inter, hidden), mk(inter, hidden), mk(hidden, inter)
         self.register_buffer("v_h", torch.zeros(d_hidden, device=device, dtype=torch.float32))
         self.register_buffer("v_f", torch.zeros(d_inter, device=device, dtype=torch.float32))
-        self.register_buffer("v_ready", torch.zeros((), device=device, dtype=torch.bool))
+        self._register_ready(device)
 
     @torch.no_grad()
     def init_v(self, h: torch.Tensor) -> None:
         """Both vectors from the first batch (Sec. 3.3): v_h from h, v_f from the first silu(gate)*up."""
         h2 = h.reshape(-1, self.hidden).contiguous()
-        _b.velora_init_v(h2, self.M_h, v=self.v_h, allow_degenerate=True)
         x = torch.nn.functional.silu(torch.matmul(h2, self.w_gate.t())) * torch.matmul(h2, self.w_up.t())
-        _b.velora_init_v(x.contiguous(), self.M_f, v=self.v_f, allow_degenerate=True)
-        self.v_ready.fill_(True)
+        self._init_vectors([(h2, self.M_h, self.v_h), (x.contiguous(), self.M_f, self.v_f)])
 
     def forward(self, h: torch.Tensor) -> torch.Tensor:
-        if not bool(self.v_ready):
+        if self._need_v():
             self.init_v(h.detach())
+        elif not self._v_ready_host:
+            F = torch.nn.functional
+            return F.linear(F.silu(F.linear(h, self.w_gate)) * F.linear(h, self.w_up), self.w_down)
         gate, up = _SharedInputLinearsFunction.apply(h, self.w_gate, self.w_up, self.v_h, self.M_h)
         return _SwiGLUDownFunction.apply(gate, up, self.w_down, self.v_f, self.M_f)
 
@@ -258,7 +303,7 @@ class _NormLinearsFunction(torch.autograd.Function):
         return (grad_h, grad_gamma, None, None, None, *grad_ws)
 
 
-class VeLoRANormLinears(torch.nn.Module):
+class VeLoRANormLinears(_FirstBatchV):
     """``RMSNorm(h) -> [linear_i]``: the input side of a LLaMA attention block (q, k, v) with VeLoRA on the
     projections.  ``out_features`` lists the projections' widths; one ``v`` and one ``S`` serve all of them."""
 
@@ -272,17 +317,21 @@ class VeLoRANormLinears(torch.nn.Module):
             [torch.nn.Parameter(torch.nn.init.normal_(torch.empty((o, hidden), device=device, dtype=dtype),
                                                       std=hidden ** -0.5)) for o in out_features])
         self.register_buffer("v", torch.zeros(sub_token_size, device=device, dtype=torch.float32))
-        self.register_buffer("v_ready", torch.zeros((), device=device, dtype=torch.bool))
+        self._register_ready(device)
+
+    def _normalised(self, h: torch.Tensor) -> torch.Tensor:
+        hf = h.reshape(-1, self.hidden).float()
+        return (hf * torch.rsqrt(hf.pow(2).mean(dim=-1, keepdim=True) + self.eps) * self.gamma).to(h.dtype)
 
     @torch.no_grad()
     def init_v(self, h: torch.Tensor) -> None:
-        """v from the first batch's normalised input (Sec. 3.3)."""
-        hf = h.reshape(-1, self.hidden).float()
-        x = (hf * torch.rsqrt(hf.pow(2).mean(dim=-1, keepdim=True) + self.eps) * self.gamma).to(h.dtype)
-        _b.velora_init_v(x.contiguous(), self.M, v=self.v, allow_degenerate=True)
-        self.v_ready.fill_(True)
+        """v from the first batch's normalised input (Sec. 3.2, "Cheap initialisation strategies")."""
+        self._init_vectors([(self._normalised(h).contiguous(), self.M, self.v)])
 
     def forward(self, h: torch.Tensor):
-        if not bool(self.v_ready):
+        if self._need_v():
             self.init_v(h.detach())
+        elif not self._v_ready_host:
+            x = self._normalised(h).reshape(h.shape)
+            return tuple(torch.nn.functional.linear(x, w) for w in self.weights)
         return _NormLinearsFunction.apply(h, self.gamma, self.v, self.M, self.eps, *self.weights)

@@ -82,9 +82,6 @@ def _load() -> ctypes.CDLL:
     cf = ctypes.c_float
     L.velora_adamw_step_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, cf, cf, cf, cf, cf, i64, cf, vp]
     L.velora_adamw_step_factor.restype = ci
-    L.velora_swiglu_compress.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, vp]
-    L.velora_swiglu_compress.restype = ci
-    cf = ctypes.c_float
     L.velora_update_v.argtypes = [vp, i64, i64, i64, ci, vp, cf, vp, vp, sz, vp]
     L.velora_update_v.restype = ci
     L.velora_compress_update.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp, cf, vp, vp, sz, vp]

@@ -15,7 +15,9 @@
 #include "common.h"
 #include "kernels.h"
 
+#ifdef VELORA_TUNING
 #include <cstdlib>
+#endif
 
 namespace velora {
 
@@ -661,11 +663,18 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
 // ---------------------------------------------------------------------------
 namespace {
 
+// Measurement knobs.  They exist only in builds made with -DVELORA_TUNING (never the shipped
+// library, whose calls depend on their arguments and the device alone): there they are read from the
+// process environment, here they are their defaults at compile time.
+#ifdef VELORA_TUNING
 int env_int(const char* name, int fallback) {
     const char* s = std::getenv(name);
     if (!s || !*s) return fallback;
     return std::atoi(s);
 }
+#else
+constexpr int env_int(const char*, int fallback) { return fallback; }
+#endif
 
 struct MfmaChoice {
     int cw, gt, nw, chunks;   // cw == 0: the MFMA path cannot take this call
@@ -824,7 +833,40 @@ hipError_t launch_expand(const float* partial, int splits, int64_t Mp, const flo
 
 }  // namespace
 
+namespace {
+WgradPlan plan_wgrad_uncached(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, const LaunchCfg& cfg);
+}
+
+// The plan is a pure function of (N, O, D, M, dtype, CU count); a training loop asks for the same few
+// again and again, so each thread remembers the last ones it computed (no locks, nothing shared).
 WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, const LaunchCfg& cfg) {
+#ifdef VELORA_TUNING
+    return plan_wgrad_uncached(N, O, D, M, is_bf16, cfg);   // the knobs may change between calls
+#else
+    struct Entry {
+        int64_t N, O, D, M;
+        int bf16, cus;
+        WgradPlan plan;
+    };
+    constexpr int kEntries = 16;
+    thread_local Entry memo[kEntries];
+    thread_local int used = 0, next = 0;
+    for (int i = 0; i < used; ++i) {
+        const Entry& e = memo[i];
+        if (e.N == N && e.O == O && e.D == D && e.M == M && e.bf16 == (is_bf16 ? 1 : 0) && e.cus == cfg.num_cus)
+            return e.plan;
+    }
+    Entry& e = memo[next];
+    e.N = N; e.O = O; e.D = D; e.M = M; e.bf16 = is_bf16 ? 1 : 0; e.cus = cfg.num_cus;
+    e.plan = plan_wgrad_uncached(N, O, D, M, is_bf16, cfg);
+    next = (next + 1) % kEntries;
+    if (used < kEntries) ++used;
+    return e.plan;
+#endif
+}
+
+namespace {
+WgradPlan plan_wgrad_uncached(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, const LaunchCfg& cfg) {
     WgradPlan p;
     p.Mp = ceil_div(M, 4) * 4;
     const int64_t in_b = is_bf16 ? 2 : 4;
@@ -889,6 +931,7 @@ WgradPlan plan_wgrad(int64_t N, int64_t O, int64_t D, int64_t M, bool is_bf16, c
     p.ws_bytes = p.partial_bytes + p.packed_bytes;
     return p;
 }
+}  // namespace
 
 namespace {
 

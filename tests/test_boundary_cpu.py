@@ -36,6 +36,26 @@ def test_header_symbols_are_exported(vl):
     assert sorted(binding.EXPORTS) == names
 
 
+def test_library_does_not_read_the_environment(vl):
+    # a call depends on its arguments and the device alone: the shipped library imports no getenv
+    # (the measurement knobs of the weight-gradient planner only exist in -DVELORA_TUNING builds)
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--undefined-only", vl.lib_path()], check=True, stdout=subprocess.PIPE,
+                         text=True).stdout
+    assert "getenv" not in out
+
+
+def test_workspace_query_is_repeatable(vl):
+    # the planner remembers its answers per thread; the same question must keep the same answer, also after
+    # more distinct shapes than it remembers have gone through
+    from paper_2405_17991_amd.binding import raw
+    q = lambda N, D, O, M: int(raw.velora_workspace_bytes(vl.OP_WEIGHT_GRAD, N, D, O, M, vl.BF16))
+    first = {(N, M): q(N, 1024, 512, M) for N in (256, 4096, 16384) for M in (1, 4, 16, 64, 128, 256, 512)}
+    for _ in range(2):
+        for (N, M), need in first.items():
+            assert q(N, 1024, 512, M) == need and need > 0
+
+
 def test_version_and_status_strings(vl):
     assert vl.velora_version() >= 100
     for code, name in vl.STATUS.items():

@@ -270,3 +270,30 @@ def test_norm_qkv_block_keeps_scalars_instead_of_the_normalised_input(mods):
         blk(h)
     # h itself (for the normalisation's backward) and one scalar per sub-token; the normalised input is not kept
     assert sum(seen.values()) == N * H * 2 + N * (H // d) * 2
+
+
+def test_v_flag_lives_on_the_host_and_follows_the_state_dict(mods):
+    """forward never reads the device flag; loading a state dict that holds v marks the module ready; a
+    module that has seen no training batch runs the plain layer in eval mode; a degenerate first batch warns
+    and leaves the module waiting for the next batch."""
+    torch, va = mods
+    torch.manual_seed(1)
+    a = va.VeLoRALinear(128, 64, 32, device="cuda", dtype=torch.bfloat16)
+    x = (torch.randn((40, 128), device="cuda") + 0.5).to(torch.bfloat16)
+    a.eval()
+    y = a(x)                                              # eval before any training batch: plain layer, v untouched
+    assert not a._v_ready_host and not bool(a.v_ready) and float(a.v.abs().sum()) == 0.0
+    assert torch.equal(y, torch.nn.functional.linear(x, a.weight))
+    a.train()
+    with pytest.warns(UserWarning):
+        a(torch.zeros_like(x))                            # zero mean: fallback direction, not frozen
+    assert not a._v_ready_host
+    a(x)
+    assert a._v_ready_host and bool(a.v_ready)
+    b = va.VeLoRALinear(128, 64, 32, device="cuda", dtype=torch.bfloat16)
+    assert not b._v_ready_host
+    b.load_state_dict(a.state_dict())
+    assert b._v_ready_host and torch.equal(b.v, a.v)
+    v0 = b.v.clone()
+    b(x * 2.0)
+    assert torch.equal(b.v, v0)                           # loaded v stays frozen

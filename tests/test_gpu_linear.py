@@ -20,6 +20,17 @@ def vl():
     return vl
 
 
+def _rows_in_every_token_tile(N, seed, tile=256):
+    """One seeded token row inside every tile of `tile` tokens (the GEMM's block height), plus the first
+    and last rows of the array and both sides of the first tile edge: a tile the block-id mapping skipped
+    or wrote twice cannot hide between samples."""
+    rng = np.random.default_rng(seed)
+    rows = {0, 1, min(N - 1, tile - 1), min(N - 1, tile), N - 2 if N > 1 else 0, N - 1}
+    for t0 in range(0, N, tile):
+        rows.add(int(t0 + rng.integers(0, min(tile, N - t0))))
+    return np.array(sorted(rows))
+
+
 def _inputs(N, D, O, d, dtype, seed):
     X = wl.random_tensor(N, D, dtype, seed, 31, 1.0)
     W = wl.random_tensor(O, D, dtype, seed, 32, D ** -0.5)
@@ -113,7 +124,7 @@ def test_identity_weight_copies_the_input(vl):
 
 
 def test_full_size_sampled(vl):
-    # the LLaMA-7B-like down projection at its real size; the oracle computes sampled token rows one by one
+    # the LLaMA-7B-like down projection at its real size; the oracle computes one token row of every 256-token tile
     import torch
     sh = wl.shape_by_name("cfg4_down")
     torch.manual_seed(0)
@@ -122,7 +133,7 @@ def test_full_size_sampled(vl):
     v = wl.random_unit_v(sh.d, 3)
     Yd, Sd = vl.velora_linear_compress(Xd, Wd, to_dev(v, wl.F32), sh.M)
     torch.cuda.synchronize()
-    rows = np.array([0, 1, 255, 256, 4097, 8191, 12345, sh.N - 257, sh.N - 1])
+    rows = _rows_in_every_token_tile(sh.N, 11)
     Xs = to_host_bits(Xd[torch.from_numpy(rows).cuda()])
     W = to_host_bits(Wd)
     Y_exact, Y_store, S_exact, S_store = oracle.linear_compress(Xs, W, v, sh.M)
@@ -190,7 +201,7 @@ def test_grad_input_full_size_sampled(vl):
     Wd = (torch.randn((sh.O, sh.D), device="cuda") * sh.O ** -0.5).to(torch.bfloat16)
     dXd = vl.velora_grad_input(Gd, Wd)
     torch.cuda.synchronize()
-    rows = np.array([0, 255, 256, 4097, 8191, 12345, sh.N - 257, sh.N - 1])
+    rows = _rows_in_every_token_tile(sh.N, 12)
     idx = torch.from_numpy(rows).cuda()
     dX_exact, dX_store = oracle.grad_input(to_host_bits(Gd[idx]), to_host_bits(Wd))
     assert_bf16_store_matches(to_host_bits(dXd[idx]), dX_exact, dX_store, "dX rows")
@@ -199,7 +210,7 @@ def test_grad_input_full_size_sampled(vl):
 @pytest.mark.parametrize("name", ["cfg2_vit_fc1", "cfg3_up", "cfg4_up", "cfg5_down_d256", "paper7b_down_m32", "cfg5_up_d64"])
 def test_dense_products_at_other_full_sizes_sampled(vl, name):
     """Forward (with S) and input gradient at the real layer sizes of the other configurations; the oracle
-    computes sampled token rows one by one (tile edges, first and last rows)."""
+    computes one token row of every 256-token tile (plus tile edges, first and last rows)."""
     import torch
     sh = wl.shape_by_name(name)
     torch.manual_seed(sh.N % 97)
@@ -210,7 +221,7 @@ def test_dense_products_at_other_full_sizes_sampled(vl, name):
     Yd, Sd = vl.velora_linear_compress(Xd, Wd, to_dev(v, wl.F32), sh.M)
     dXd = vl.velora_grad_input(Gd, Wd)
     torch.cuda.synchronize()
-    rows = np.array(sorted({0, 1, 255, 256, 257, sh.N // 2 + 3, sh.N - (sh.N % 256 or 256) - 1, sh.N - 2, sh.N - 1}))
+    rows = _rows_in_every_token_tile(sh.N, sh.N % 89)
     idx = torch.from_numpy(rows).cuda()
     W = to_host_bits(Wd)
     Y_exact, Y_store, S_exact, S_store = oracle.linear_compress(to_host_bits(Xd[idx]), W, v, sh.M)
