@@ -234,6 +234,32 @@ velora_status velora_weight_grad(const void* G, const void* S, const float* v,
                                  void* ws, size_t ws_bytes, velora_stream stream);
 
 /*
+ * velora_weight_grad for callers that cannot allocate or own a workspace: code under
+ * HIP graph capture that may not call hipMalloc, tight serving or training loops,
+ * harnesses that forbid allocation.  Same arguments, kernels, split and result
+ * (bit for bit) as velora_weight_grad, without `ws`: the partial sums (and, for
+ * M > 48, the re-laid-out S) live in a static device array of
+ * VELORA_STATIC_SCRATCH_BYTES that is part of the library's code object, so every
+ * GPU the library is used on holds that much memory until the process ends.
+ * The call allocates and frees nothing (no hipMalloc / hipFree / allocating library
+ * routine).  The first call on a device looks the array's address up once
+ * (hipGetSymbolAddress, with that device current) and keeps it per device; make that
+ * first call outside a stream capture.
+ * A shape whose workspace requirement (velora_workspace_bytes(VELORA_OP_WEIGHT_GRAD, ...))
+ * exceeds VELORA_STATIC_SCRATCH_BYTES is refused with VELORA_ERR_WORKSPACE before any
+ * launch; the other argument errors are those of velora_weight_grad.
+ * Every call on a GPU uses that GPU's one array, whatever the stream: calls that may
+ * run concurrently on one GPU (different streams, different threads) race on it and
+ * must be serialised by the caller; calls on one stream are safe back to back.  The
+ * array keeps the previous call's contents; the kernels overwrite every word they
+ * later read, nothing has to be cleared.
+ */
+#define VELORA_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+velora_status velora_weight_grad_static(const void* G, const void* S, const float* v,
+                                        int64_t N, int64_t O, int64_t D, int64_t M, velora_dtype in_dt,
+                                        void* dW, velora_dtype dw_dt, int accumulate, velora_stream stream);
+
+/*
  * The factored hand-off of the same gradient.  Since the reconstruction of
  * Sec. 3.2 is Xhat[n, g*d+j] = S[n,g]*v[j], Algorithm 1's grad_weight equals
  * T (x) v with T[o, g] = sum_n G[n, o] * S[n, g]: d times smaller than dW.  A

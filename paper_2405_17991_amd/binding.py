@@ -29,7 +29,8 @@ STATUS = {
 
 EXPORTS = [
     "velora_status_string", "velora_version", "velora_workspace_bytes", "velora_init_v",
-    "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_factor",
+    "velora_compress", "velora_reconstruct", "velora_weight_grad", "velora_weight_grad_static",
+    "velora_weight_grad_factor",
     "velora_expand_factor", "velora_update_v", "velora_compress_update", "velora_adamw_step_factor",
     "velora_swiglu_compress", "velora_rmsnorm_compress", "velora_linear_compress", "velora_grad_input",
 ]
@@ -67,6 +68,8 @@ def _load() -> ctypes.CDLL:
     L.velora_reconstruct.restype = ci
     L.velora_weight_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, ci, ci, vp, sz, vp]
     L.velora_weight_grad.restype = ci
+    L.velora_weight_grad_static.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, ci, ci, vp]
+    L.velora_weight_grad_static.restype = ci
     L.velora_weight_grad_factor.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
     L.velora_weight_grad_factor.restype = ci
     L.velora_expand_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp]
@@ -335,6 +338,34 @@ def velora_weight_grad(G, S, v, D: int, dW=None, dw_dtype=None, accumulate: bool
                                 _dt(dW), 1 if accumulate else 0, ws.data_ptr(), ws.numel(), _stream())
     _raise(st, "velora_weight_grad")
     return dW
+
+
+def velora_weight_grad_static(G, S, v, D: int, dW, accumulate: bool = False):
+    """velora_weight_grad on the library's static device scratch: no workspace argument and no allocation
+    anywhere (the caller passes dW).  Shapes that need more than VELORA_STATIC_SCRATCH_BYTES raise
+    VELORA_ERR_WORKSPACE; calls that may overlap on one GPU must be serialised by the caller."""
+    torch = _torch()
+    _check(G, "G", 2)
+    _check(S, "S", 2)
+    _check(v, "v", 1)
+    _check(dW, "dW", 2)
+    N, O = G.shape
+    N2, M = S.shape
+    if N2 != N:
+        raise ValueError("G and S must have the same number of tokens")
+    if G.dtype != S.dtype:
+        raise TypeError("G and S must share a dtype")
+    if v.dtype != torch.float32:
+        raise TypeError("v must be float32")
+    if tuple(dW.shape) != (O, D):
+        raise ValueError(f"dW must be [{O}, {D}]")
+    st = raw.velora_weight_grad_static(G.data_ptr(), S.data_ptr(), v.data_ptr(), N, O, D, M, _dt(G), dW.data_ptr(),
+                                       _dt(dW), 1 if accumulate else 0, _stream())
+    _raise(st, "velora_weight_grad_static")
+    return dW
+
+
+STATIC_SCRATCH_BYTES = 64 << 20     # VELORA_STATIC_SCRATCH_BYTES of include/velora.h
 
 
 def velora_weight_grad_factor(G, S, T=None, ws=None):

@@ -10,11 +10,16 @@
 
 #include <cmath>
 
+// Scratch of velora_weight_grad_static: part of the code object, one copy per GPU at its own address.
+// Host code never passes this name to a kernel; it passes the address hipGetSymbolAddress returned.
+static __device__ __align__(256) unsigned char velora_static_scratch[VELORA_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using velora::LaunchCfg;
 
 constexpr int kMaxDevices = 64;
+std::atomic<void*> g_static_scratch_ptr[kMaxDevices];   // zero-initialised: not looked up yet
 constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
 
 LaunchCfg current_cfg() {
@@ -250,9 +255,11 @@ velora_status velora_reconstruct(const void* S, const float* v, int64_t N, int64
                                                  static_cast<hipStream_t>(stream)));
 }
 
-velora_status velora_weight_grad(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D,
-                                 int64_t M, velora_dtype in_dt, void* dW, velora_dtype dw_dt, int accumulate,
-                                 void* ws, size_t ws_bytes, velora_stream stream) {
+namespace {
+
+// host-side checks shared by velora_weight_grad and velora_weight_grad_static
+velora_status check_weight_grad(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D,
+                                int64_t M, velora_dtype in_dt, const void* dW, velora_dtype dw_dt) {
     if (!G || !S || !v || !dW) return VELORA_ERR_NULL;
     if (!dtype_ok(in_dt) || !dtype_ok(dw_dt)) return VELORA_ERR_DTYPE;
     if (!shape_ok(N, D, M) || O <= 0 || !size_ok(N, D) || !size_ok(N, O) || !size_ok(O, D) ||
@@ -261,6 +268,16 @@ velora_status velora_weight_grad(const void* G, const void* S, const float* v, i
     const int eb = elem_bytes(in_dt);
     if (ptr_align(G) < eb || ptr_align(S) < eb || ptr_align(v) < 4 || ptr_align(dW) < elem_bytes(dw_dt))
         return VELORA_ERR_ALIGN;
+    return VELORA_OK;
+}
+
+}  // namespace
+
+velora_status velora_weight_grad(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D,
+                                 int64_t M, velora_dtype in_dt, void* dW, velora_dtype dw_dt, int accumulate,
+                                 void* ws, size_t ws_bytes, velora_stream stream) {
+    const velora_status chk = check_weight_grad(G, S, v, N, O, D, M, in_dt, dW, dw_dt);
+    if (chk != VELORA_OK) return chk;
     const LaunchCfg cfg = current_cfg();
     const bool bf = in_dt == VELORA_BF16;
     const velora::WgradPlan plan = velora::plan_wgrad(N, O, D, M, bf, cfg);
@@ -268,6 +285,37 @@ velora_status velora_weight_grad(const void* G, const void* S, const float* v, i
     if (ptr_align(ws) < 16) return VELORA_ERR_ALIGN;
     return hip_status(velora::launch_wgrad(G, S, v, N, O, D, M, bf, ptr_align(G), ptr_align(S), ptr_align(v), dW,
                                            dw_dt == VELORA_BF16, ptr_align(dW), accumulate != 0, ws, plan, cfg,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+velora_status velora_weight_grad_static(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D,
+                                        int64_t M, velora_dtype in_dt, void* dW, velora_dtype dw_dt, int accumulate,
+                                        velora_stream stream) {
+    const velora_status chk = check_weight_grad(G, S, v, N, O, D, M, in_dt, dW, dw_dt);
+    if (chk != VELORA_OK) return chk;
+    const LaunchCfg cfg = current_cfg();
+    const bool bf = in_dt == VELORA_BF16;
+    const velora::WgradPlan plan = velora::plan_wgrad(N, O, D, M, bf, cfg);
+    if (plan.ws_bytes > VELORA_STATIC_SCRATCH_BYTES) return VELORA_ERR_WORKSPACE;   // refused before the device is touched
+    // The array's name is only a host-side handle: its device address differs per GPU and is looked up
+    // once per device, with that device current; from then on only the looked-up pointer is used.
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return VELORA_ERR_HIP;
+    }
+    void* scratch = g_static_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!scratch) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(velora_static_scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return VELORA_ERR_HIP;
+        }
+        g_static_scratch_ptr[dev].store(p, std::memory_order_release);
+        scratch = p;
+    }
+    return hip_status(velora::launch_wgrad(G, S, v, N, O, D, M, bf, ptr_align(G), ptr_align(S), ptr_align(v), dW,
+                                           dw_dt == VELORA_BF16, ptr_align(dW), accumulate != 0, scratch, plan, cfg,
                                            static_cast<hipStream_t>(stream)));
 }
 
