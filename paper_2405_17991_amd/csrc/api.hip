@@ -345,7 +345,8 @@ velora_status velora_expand_factor(const float* T, const float* v, int64_t O, in
     if (!shape_ok(O, D, M) || !size_ok(O, D) || D / M > INT32_MAX / 8 || O > INT32_MAX) return VELORA_ERR_SHAPE;
     if (ptr_align(T) < 4 || ptr_align(v) < 4 || ptr_align(dW) < elem_bytes(dw_dt)) return VELORA_ERR_ALIGN;
     return hip_status(velora::launch_expand_factor(T, v, ptr_align(v), dW, dw_dt == VELORA_BF16, ptr_align(dW),
-                                                   accumulate != 0, O, D, M, static_cast<hipStream_t>(stream)));
+                                                   accumulate != 0, O, D, M, current_cfg(),
+                                                   static_cast<hipStream_t>(stream)));
 }
 
 velora_status velora_adamw_step_factor(const float* T, const float* v, int64_t O, int64_t D, int64_t M, void* W,

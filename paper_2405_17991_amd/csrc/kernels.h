@@ -76,6 +76,7 @@ struct WgradPlan {
     int64_t rows_per_split;
     int64_t Mp;
     int64_t tiles_packed;
+    bool cyclic;       // token chunks are dealt to the splits round-robin instead of as contiguous ranges
     size_t partial_bytes;
     size_t packed_bytes;
     size_t ws_bytes;
@@ -90,7 +91,7 @@ hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N,
 hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t O, int64_t M, bool is_bf16,
                                int g_align, float* T, void* ws, const WgradPlan& plan, hipStream_t st);
 hipError_t launch_expand_factor(const float* T, const float* v, int v_align, void* dW, bool dw_bf16, int dw_align,
-                                bool accumulate, int64_t O, int64_t D, int64_t M, hipStream_t st);
+                                bool accumulate, int64_t O, int64_t D, int64_t M, const LaunchCfg& cfg, hipStream_t st);
 
 // ---- adamw.hip ----
 // Scalars of one AdamW step, precomputed on the host in double precision.

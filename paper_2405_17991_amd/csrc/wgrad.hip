@@ -59,6 +59,9 @@ namespace velora {
 // range and are summed through LDS at the end in a fixed order.
 // grid = (o tiles of 16*CW, splits, g chunks of 16*GT)
 // ---------------------------------------------------------------------------
+#ifndef VELORA_SKIP
+#define VELORA_SKIP 0            // measurement builds only: 1 no S loads, 2 no transposes / MFMAs, 4 no cross-wave sum
+#endif
 constexpr int kStep = 32;        // tokens per MFMA K-step
 constexpr int kWavesPerBlock = 4;
 
@@ -94,7 +97,7 @@ constexpr int kStreamAux = 2;
 // that for every edge (rows past the token range, columns past O, steps past
 // the end) instead of branching.
 template <int CW, int AUX>
-__device__ __forceinline__ RawRow<CW / 2> load_g(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff) {
+__device__ __forceinline__ RawRow<CW / 2> load_g(const __amdgpu_buffer_rsrc_t& rsrc, uint32_t voff) {
     RawRow<CW / 2> r;
     if constexpr (CW == 8) {
         const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, AUX);
@@ -126,15 +129,23 @@ __device__ __forceinline__ void store_tile(float* __restrict__ out, const f32x4&
     if (o < O && g < Mp) *reinterpret_cast<f32x4*>(out + o * Mp + g) = t;
 }
 
+// Which tokens a block sums over.  The token axis is cut into chunks of 128 (four waves x one 32-token
+// step).  `chunk_stride` = 128: the block owns the contiguous range [split * rows_per_split, ...);
+// `chunk_stride` = splits * 128: chunks are dealt to the splits round-robin, block `split` takes chunks
+// split, split + splits, ...  Then all blocks of the grid walk through G together, window by window, and
+// every row of G is fetched by its column tiles at about the same time, which DRAM serves faster than
+// `splits` separate sweeps that are megabytes apart (measured on the 16384 x 4096 layer, loads only:
+// 21.0 us against 22.4 us).  Either way the order of the summation depends on the sizes alone.
 template <int CW, int GT, int NST, bool DIRECT>
 __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t* __restrict__ G,
                                                                 const void* __restrict__ Sany,
                                                                 float* __restrict__ partial, int64_t N, int64_t O,
                                                                 int64_t M, int64_t Mp, int64_t rows_per_split,
-                                                                int64_t tiles_packed) {
+                                                                int64_t tiles_packed, int cyclic) {
     constexpr int OT = 16 * CW;          // output features per block
     constexpr int NACC = GT * CW;        // accumulator tiles per wave
     constexpr int TP = NACC <= 24 ? NACC : (NACC % 24 == 0 ? 24 : 16);   // tiles reduced per pass: 2 regions x <= 24 KB of LDS
+    constexpr int kChunk = kStep * kWavesPerBlock;
     __shared__ f32x4 red[2][TP][kWave];
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -143,50 +154,65 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
     const int jj = lane & 15;
     const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
     const int split = blockIdx.y;
+    const int splits = gridDim.y;
     const int64_t tile0 = static_cast<int64_t>(blockIdx.z) * GT;
-    const int step_first = w;                          // this wave's first step ...
-    constexpr int kStepStride = kWavesPerBlock;        // ... and the distance to its next
-    const int64_t kb = static_cast<int64_t>(split) * rows_per_split;
-    int64_t ke = kb + rows_per_split;
-    if (ke > N) ke = N;
-    const int rows = static_cast<int>(ke - kb);
-    const int n_steps = (rows + kStep - 1) / kStep;
+    // first row, rows from there to the end of what this block may read, chunks it owns, rows between them
+    int64_t row0, span_rows;
+    int n_chunks;
+    uint32_t chunk_stride;
+    if (cyclic) {
+        const int64_t total_chunks = ceil_div(N, kChunk);
+        row0 = static_cast<int64_t>(split) * kChunk;
+        span_rows = N - row0;
+        n_chunks = static_cast<int>((total_chunks - split + splits - 1) / splits);
+        chunk_stride = static_cast<uint32_t>(splits) * kChunk;
+    } else {
+        row0 = static_cast<int64_t>(split) * rows_per_split;
+        span_rows = N - row0 < rows_per_split ? N - row0 : rows_per_split;
+        n_chunks = static_cast<int>(ceil_div(span_rows, kChunk));
+        chunk_stride = kChunk;
+    }
     const bool col_ok = o0 + jj * CW < O;
 
+    // One buffer descriptor per operand for the whole life of the block (rebuilding it for every step
+    // measured 2.6 us slower on the 16384 x 4096 layer than adding the step's offset per lane).  A raw
+    // buffer load whose offset is not below the descriptor's size returns zero without touching memory;
+    // every edge uses that instead of a branch: rows past the end, columns past O (lane offset
+    // 0x7FFFFFFF) and steps past the block's last chunk (step offset 0x80000000); sizes stay below 2^31
+    // (checked on the host), so no sum of a lane and a step offset wraps around.
+    constexpr uint32_t kLaneOut = 0x7FFFFFFFu, kStepOut = 0x80000000u;
     const uint32_t row_bytes = static_cast<uint32_t>(O) * 2u;
-    // Byte offsets of this lane's eight rows inside a step, constant for the
-    // whole kernel.  Lanes whose columns lie past O get an offset no descriptor
-    // can cover, so they read zeros.
     uint32_t voff[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r)
-        voff[r] = col_ok ? static_cast<uint32_t>(q * 8 + r) * row_bytes + static_cast<uint32_t>(jj * CW * 2)
-                         : 0xFFFFFFFFu;
-    const char* gblock = reinterpret_cast<const char*>(G) + (kb * O + o0) * 2;
-    const uint32_t gblock_bytes = static_cast<uint32_t>(rows) * row_bytes - static_cast<uint32_t>(o0 * 2);
-    const uint32_t step_bytes = static_cast<uint32_t>(kStep) * row_bytes;
-    // S of this block.  Packed path: steps kb/32 .., tiles tile0 .. of the
-    // fragment array, one descriptor for the whole range.  Direct path (few
-    // group tiles): the rows kb .. ke of S[N, M] itself; lane (jj, q) gathers
-    // S[8q + e][16*tile + jj], e < 8, as eight 2-byte loads per tile.
-    const uint32_t s_step_bytes = DIRECT ? static_cast<uint32_t>(kStep) * static_cast<uint32_t>(M) * 2u
-                                         : static_cast<uint32_t>(tiles_packed) * 1024u;
-    const char* sblock = DIRECT ? reinterpret_cast<const char*>(Sany) + kb * M * 2
-                                : reinterpret_cast<const char*>(Sany) + ((kb / kStep) * tiles_packed + tile0) * 1024;
-    const uint32_t sblock_bytes = DIRECT ? static_cast<uint32_t>(rows) * static_cast<uint32_t>(M) * 2u
-                                         : static_cast<uint32_t>(n_steps) * s_step_bytes - static_cast<uint32_t>(tile0) * 1024u;
-    uint32_t s_voff[DIRECT ? GT : 1][DIRECT ? 8 : 1];
-    if constexpr (DIRECT) {
+        voff[r] = col_ok ? static_cast<uint32_t>(q * 8 + r) * row_bytes + static_cast<uint32_t>(jj * CW * 2) : kLaneOut;
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(G) + (row0 * O + o0) * 2), 0,
+        static_cast<int>(static_cast<uint32_t>(span_rows) * row_bytes - static_cast<uint32_t>(o0 * 2)), 0x00020000);
+    // S of this block.  Direct path (few group tiles): S[N, M] itself, lane (jj, q) gathers
+    // S[8q + e][16*tile + jj], e < 8, as eight 2-byte loads per tile.  Packed path: the fragment array,
+    // entry (32-token step, tile), 1 KiB each.
+    const uint32_t s_row_bytes = DIRECT ? static_cast<uint32_t>(M) * 2u : static_cast<uint32_t>(tiles_packed) * (1024u / kStep);
+    const char* sbase = DIRECT ? reinterpret_cast<const char*>(Sany) + row0 * M * 2
+                               : reinterpret_cast<const char*>(Sany) + ((row0 / kStep) * tiles_packed + tile0) * 1024;
+    const int64_t span_steps = ceil_div(span_rows, kStep);
+    const uint32_t s_bytes = DIRECT ? static_cast<uint32_t>(span_rows) * static_cast<uint32_t>(M) * 2u
+                                    : static_cast<uint32_t>(span_steps * tiles_packed - tile0) * 1024u;
+    const __amdgpu_buffer_rsrc_t s_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(sbase), 0, static_cast<int>(s_bytes), 0x00020000);
+    uint32_t s_voff[GT][DIRECT ? 8 : 1];
 #pragma unroll
-        for (int a = 0; a < GT; ++a) {
+    for (int a = 0; a < GT; ++a) {
+        if constexpr (DIRECT) {
             const int64_t g = (tile0 + a) * 16 + jj;
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 s_voff[a][e] = g < M ? (static_cast<uint32_t>(q * 8 + e) * static_cast<uint32_t>(M) + static_cast<uint32_t>(g)) * 2u
-                                     : 0xFFFFFFFFu;
+                                     : kLaneOut;
+        } else {
+            // tiles past the last real one are not in the array
+            s_voff[a][0] = tile0 + a < tiles_packed ? static_cast<uint32_t>(lane) * 16u + a * 1024u : kLaneOut;
         }
-    } else {
-        s_voff[0][0] = static_cast<uint32_t>(lane) * 16u;
     }
 
     f32x4 acc[GT][CW];
@@ -196,33 +222,25 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
         for (int c = 0; c < CW; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     WgradStage<CW, GT, DIRECT> st[NST];
-    auto load_g_step = [&](WgradStage<CW, GT, DIRECT>& sg, int t) {
-        // descriptor for this step: starts at the step's first token and ends
-        // with the block's token range (empty for steps past the range)
-        const uint32_t off = static_cast<uint32_t>(t) * step_bytes;
-        const uint32_t left = t < n_steps ? gblock_bytes - off : 0u;
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<char*>(gblock + (t < n_steps ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
+    // first row of this wave's step in chunk i, relative to row0 (a multiple of 32)
+    auto step_row = [&](int i) -> uint32_t { return static_cast<uint32_t>(i) * chunk_stride + static_cast<uint32_t>(w * kStep); };
+    auto load_g_step = [&](WgradStage<CW, GT, DIRECT>& sg, int i) {
+        const uint32_t off = i < n_chunks ? step_row(i) * row_bytes : kStepOut;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) sg.g[r] = load_g<CW, kStreamAux>(rsrc, voff[r]);
+        for (int r = 0; r < 8; ++r) sg.g[r] = load_g<CW, kStreamAux>(g_rsrc, voff[r] + off);
     };
-    auto load_s_step = [&](WgradStage<CW, GT, DIRECT>& sg, int t) {
-        const uint32_t off = static_cast<uint32_t>(t) * s_step_bytes;
-        const uint32_t left = (t < n_steps && off < sblock_bytes) ? sblock_bytes - off : 0u;
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<char*>(sblock + (left ? off : 0u)), 0, static_cast<int>(left), 0x00020000);
+    auto load_s_step = [&](WgradStage<CW, GT, DIRECT>& sg, int i) {
+        const uint32_t off = i < n_chunks ? step_row(i) * s_row_bytes : kStepOut;
         if constexpr (DIRECT) {
 #pragma unroll
             for (int a = 0; a < GT; ++a)
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    sg.s[a][e] = static_cast<uint32_t>(__builtin_amdgcn_raw_buffer_load_b16(rsrc, s_voff[a][e], 0, 0));
+                    sg.s[a][e] = static_cast<uint32_t>(__builtin_amdgcn_raw_buffer_load_b16(s_rsrc, s_voff[a][e] + off, 0, 0));
         } else {
 #pragma unroll
             for (int a = 0; a < GT; ++a) {
-                // tiles past the last real one are not in the array: an offset no descriptor covers reads zeros
-                const uint32_t so = tile0 + a < tiles_packed ? s_voff[0][0] + a * 1024u : 0xFFFFFFFFu;
-                const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, so, 0, 0);
+                const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(s_rsrc, s_voff[a][0] + off, 0, 0);
                 sg.s[a][0] = x.x; sg.s[a][1] = x.y; sg.s[a][2] = x.z; sg.s[a][3] = x.w;
             }
         }
@@ -240,45 +258,74 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
         return __builtin_bit_cast(bf16x8, f);
     };
 
-    // Register ring: NST steps of this wave are in flight at any time.  G's raw
-    // registers are free once its fragments are built, S's once the MFMAs have
-    // been issued, so each is re-loaded at that point.  Steps past the end of
-    // the range load zeros, which keeps the loop free of branches.
+    // Register ring: NST steps of this wave are in flight.  Loads return in the order they were
+    // issued, S first (it comes from L2), then G.  A trip waits for its step, turns the raw
+    // registers into MFMA operands, re-issues both loads for the step NST chunks ahead into the
+    // registers it has just freed, and only then runs the MFMAs, so that the wave always has at
+    // least NST - 1 whole steps on their way while it computes.  Steps past the last chunk load
+    // zeros, which keeps the loop free of branches.
 #pragma unroll
     for (int s = 0; s < NST; ++s) {
-        load_g_step(st[s], step_first + s * kStepStride);
-        load_s_step(st[s], step_first + s * kStepStride);
+        load_s_step(st[s], s);
+        load_g_step(st[s], s);
     }
-    for (int base = step_first; base < n_steps; base += NST * kStepStride) {
+    for (int i = 0; i < n_chunks; i += NST) {
 #pragma unroll
         for (int s = 0; s < NST; ++s) {
-            const int tn = base + (s + NST) * kStepStride;
-            bf16x8 gf[CW];
+            bf16x8 gf[CW], sf[GT];
+#if VELORA_SKIP & 2
+            {
+                uint32_t x = 0;
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+#pragma unroll
+                    for (int k = 0; k < CW / 2; ++k) x ^= st[s].g[r].w[k];
+                acc[0][0][0] += __uint_as_float(x & 0x3fffffffu);
+            }
+#pragma unroll
+            for (int c = 0; c < CW; ++c) gf[c] = bf16x8{};
+#else
 #pragma unroll
             for (int c = 0; c < CW; ++c) gf[c] = column_fragment(st[s].g, c);
-            load_g_step(st[s], tn);
+#endif
 #pragma unroll
-            for (int a = 0; a < GT; ++a) {
-                const bf16x8 sf = s_fragment(st[s], a);
+            for (int a = 0; a < GT; ++a) sf[a] = s_fragment(st[s], a);
+            __builtin_amdgcn_sched_barrier(0);
+            if (!(VELORA_SKIP & 1)) load_s_step(st[s], i + s + NST);
+            load_g_step(st[s], i + s + NST);
+            __builtin_amdgcn_sched_barrier(0);
+#if !(VELORA_SKIP & 2)
+#pragma unroll
+            for (int a = 0; a < GT; ++a)
 #pragma unroll
                 for (int c = 0; c < CW; ++c)
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
-            }
-            // keep the scheduler from hoisting the S reload above the MFMAs
-            // that still read the old fragments (it would double their registers)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf[a], gf[c], acc[a][c], 0, 0, 0);
+#endif
             __builtin_amdgcn_sched_barrier(0);
-            load_s_step(st[s], tn);
         }
     }
+#if VELORA_SKIP & 4
+    // measurement only: no barrier is reached by anyone; wave 0 stores its own sums
+    if (w == 0) {
+        float* o_ = partial + static_cast<int64_t>(split) * O * Mp;
+#pragma unroll
+        for (int a = 0; a < GT; ++a)
+#pragma unroll
+            for (int c = 0; c < CW; ++c) store_tile<CW>(o_, acc[a][c], o0, jj, q, c, (tile0 + a) * 16, O, Mp);
+    }
+    return;
+#endif
 
-    // Sum the four waves in a fixed order, (w0 + w1) + (w2 + w3), through LDS in
-    // the accumulators' own register layout (16-byte LDS accesses, no transpose):
-    // waves 1 and 3 publish, waves 0 and 2 add; wave 2 publishes its sum in the
-    // region it has just read, wave 0 adds it and stores the tiles to the
-    // block's partial tile straight from its registers.
+    // Sum the four waves in a fixed order, (w0 + w1) + (w2 + w3), through LDS in the accumulators' own
+    // register layout (16-byte LDS accesses, no transpose): waves 1 and 3 publish, waves 0 and 2 add.
+    // Then wave 2 publishes the first half of its sums and wave 0 the second half of its own, each adds
+    // what the other published (the same two numbers either way round, so every tile is
+    // (w0 + w1) + (w2 + w3) bit for bit) and stores its half of the block's partial tile straight from
+    // its registers: the stores of the tile, which end the block, come from two waves at once.
     float* out = partial + static_cast<int64_t>(split) * O * Mp;
 #pragma unroll
     for (int p0 = 0; p0 < NACC; p0 += TP) {
+        constexpr int H = (TP + 1) / 2;                       // tiles of a pass finished by wave 0; wave 2 takes the rest
         if (w == 1 || w == 3) {
 #pragma unroll
             for (int i = 0; i < TP; ++i)
@@ -289,19 +336,19 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
 #pragma unroll
             for (int i = 0; i < TP; ++i)
                 if (p0 + i < NACC) acc[(p0 + i) / CW][(p0 + i) % CW] += red[w >> 1][i][lane];
-        }
-        if (w == 2) {
+            // wave 2 hands over tiles [0, H), wave 0 tiles [H, TP), each in the region it has just read
 #pragma unroll
             for (int i = 0; i < TP; ++i)
-                if (p0 + i < NACC) red[1][i][lane] = acc[(p0 + i) / CW][(p0 + i) % CW];
+                if (p0 + i < NACC && (w == 2) == (i < H)) red[w >> 1][i][lane] = acc[(p0 + i) / CW][(p0 + i) % CW];
         }
         __syncthreads();
-        if (w == 0) {
+        if (w == 0 || w == 2) {
 #pragma unroll
             for (int i = 0; i < TP; ++i)
-                if (p0 + i < NACC) {
+                if (p0 + i < NACC && (w == 0) == (i < H)) {
                     const int a = (p0 + i) / CW, c = (p0 + i) % CW;
-                    const f32x4 t = acc[a][c] + red[1][i][lane];
+                    const f32x4 other = red[w == 0 ? 1 : 0][i][lane];
+                    const f32x4 t = w == 0 ? acc[a][c] + other : other + acc[a][c];
                     store_tile<CW>(out, t, o0, jj, q, c, (tile0 + a) * 16, O, Mp);
                 }
         }
@@ -659,6 +706,94 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
 }
 
 // ---------------------------------------------------------------------------
+// Kernel 2, flat form: dW[o, g*d + j] (+)= T[o, g] * v[j] from an already summed T (row stride
+// t_stride), as ONE sweep of the whole grid over dW: 16-byte vector i of the array belongs to thread
+// i mod (grid * 256), so that at any moment all compute units write one contiguous window of a
+// megabyte.  HBM takes that at 6.3 TB/s on this chip; the same bytes written as one private row per
+// block reach 5.5-5.7 TB/s, and more than two blocks per compute unit 4.9 TB/s (plain fill kernels on
+// the 4096 x 11008 float32 array).  Hence one block per compute unit and eight stores in flight per
+// thread.  The loads of T and v for the NEXT eight stores are issued before this trip's stores: a
+// trip that waits for its own loads leaves the store stream idle meanwhile (31.0 us against 29.7 us
+// on that array; the fill alone takes 28.6 us).  The (row, group, position) of a vector is kept up to
+// date by additions instead of divisions.  VW elements per vector: 4 (float32, and bf16 with 8-byte
+// stores) or 8 (bf16, needs d % 8 == 0).  Needs d % VW == 0, 16-byte aligned v, dW aligned to its
+// store, and fewer than 2^31 - 2^24 vectors.
+// ---------------------------------------------------------------------------
+template <bool OUT_BF16, int VW>
+__global__ __launch_bounds__(256) void wgrad_expand_flat_kernel(const float* __restrict__ T, int64_t t_stride,
+                                                               const float* __restrict__ v, void* __restrict__ dW,
+                                                               uint32_t n_vec, uint32_t Dv, uint32_t dv, uint32_t M,
+                                                               int accumulate) {
+    constexpr int U = 8;
+    const uint32_t stride = gridDim.x * 256u;
+    // position of this thread's next vector: row o, vector c of the row = group g, vector j of the sub-token
+    uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    uint32_t o = i / Dv, c = i - o * Dv, g = c / dv, j = c - g * dv;
+    // one step of `stride` vectors in the same coordinates
+    const uint32_t so = stride / Dv, sc = stride - so * Dv, sg = sc / dv, sj = sc - sg * dv;
+    float t[U];
+    f32x4 va[U], vb[U];
+    uint32_t idx[U];
+    auto fetch = [&]() {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            idx[u] = i;
+            const bool ok = i < n_vec;
+            t[u] = ok ? T[static_cast<int64_t>(o) * t_stride + g] : 0.f;
+            const float* vp = v + static_cast<size_t>(ok ? j : 0u) * VW;
+            va[u] = *reinterpret_cast<const f32x4*>(vp);
+            if constexpr (VW == 8) vb[u] = *reinterpret_cast<const f32x4*>(vp + 4);
+            // advance by one stride: vectors of the sub-token, groups, vectors of the row, rows
+            i += stride;
+            o += so; c += sc; g += sg; j += sj;
+            if (j >= dv) { j -= dv; ++g; }
+            if (c >= Dv) { c -= Dv; g -= M; ++o; }
+        }
+    };
+    fetch();
+    while (idx[0] < n_vec) {
+        float r[U][VW];
+        uint32_t id[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            id[u] = idx[u];
+            r[u][0] = t[u] * va[u].x; r[u][1] = t[u] * va[u].y; r[u][2] = t[u] * va[u].z; r[u][3] = t[u] * va[u].w;
+            if constexpr (VW == 8) {
+                r[u][4] = t[u] * vb[u].x; r[u][5] = t[u] * vb[u].y; r[u][6] = t[u] * vb[u].z; r[u][7] = t[u] * vb[u].w;
+            }
+        }
+        fetch();
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (id[u] >= n_vec) continue;
+            const size_t e = static_cast<size_t>(id[u]) * VW;
+            if constexpr (!OUT_BF16) {
+                f32x4* q = reinterpret_cast<f32x4*>(static_cast<float*>(dW) + e);
+                f32x4 x = {r[u][0], r[u][1], r[u][2], r[u][3]};
+                if (accumulate) x += *q;
+                __builtin_nontemporal_store(x, q);
+            } else if constexpr (VW == 8) {
+                u32x4* q = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dW) + e);
+                if (accumulate) {
+                    const u32x4 old = *q;
+                    r[u][0] += bf16_lo(old.x); r[u][1] += bf16_hi(old.x); r[u][2] += bf16_lo(old.y); r[u][3] += bf16_hi(old.y);
+                    r[u][4] += bf16_lo(old.z); r[u][5] += bf16_hi(old.z); r[u][6] += bf16_lo(old.w); r[u][7] += bf16_hi(old.w);
+                }
+                __builtin_nontemporal_store(u32x4{pack_bf16x2(r[u][0], r[u][1]), pack_bf16x2(r[u][2], r[u][3]),
+                                                  pack_bf16x2(r[u][4], r[u][5]), pack_bf16x2(r[u][6], r[u][7])}, q);
+            } else {
+                u32x2* q = reinterpret_cast<u32x2*>(static_cast<uint16_t*>(dW) + e);
+                if (accumulate) {
+                    const u32x2 old = *q;
+                    r[u][0] += bf16_lo(old.x); r[u][1] += bf16_hi(old.x); r[u][2] += bf16_lo(old.y); r[u][3] += bf16_hi(old.y);
+                }
+                __builtin_nontemporal_store(u32x2{pack_bf16x2(r[u][0], r[u][1]), pack_bf16x2(r[u][2], r[u][3])}, q);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 namespace {
@@ -742,7 +877,7 @@ hipError_t launch_mfma(const void* G, const void* s_operand, float* partial, int
               static_cast<unsigned>(chunks));
     hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST, DIRECT>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(G), s_operand, partial, N, O, M, plan.Mp, plan.rows_per_split,
-                       plan.tiles_packed);
+                       plan.tiles_packed, plan.cyclic ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -775,6 +910,17 @@ hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_oper
     // shape): a CU sustains a fixed number of outstanding cache-line requests, which
     // four waves with one 32-token step each already exceed, and deeper rings only
     // cost registers.
+    // Steps in flight per wave.  Two for two to four group tiles, where a step's S loads, transposes and
+    // MFMAs take long enough that a wave with a single step in flight leaves the memory pipe short
+    // (measured: 31 against 38 us on N = 16384, O = 4096, M = 43; 82 against 88 us on O = 13824, M = 20);
+    // one for a single tile, where the second step only costs registers (25.0 against 25.6 us on
+    // O = 4096, M = 16), and for five and more tiles, where it does not fit the register file.
+    const int ring = env_int("VELORA_WGRAD_RING", 0);   // measurement builds: 1 or 2 for every tile count
+    if (ring != 1) {
+        if (ring == 2) { VELORA_MFMA_CASE(8, 1, 2, true) VELORA_MFMA_CASE(4, 1, 2, true) }
+        VELORA_MFMA_CASE(8, 2, 2, true) VELORA_MFMA_CASE(8, 3, 2, true) VELORA_MFMA_CASE(8, 4, 2, false)
+        VELORA_MFMA_CASE(4, 2, 2, true) VELORA_MFMA_CASE(4, 3, 2, true) VELORA_MFMA_CASE(4, 4, 2, false)
+    }
     VELORA_MFMA_CASE(8, 1, 1, true) VELORA_MFMA_CASE(8, 2, 1, true) VELORA_MFMA_CASE(8, 3, 1, true)
     VELORA_MFMA_CASE(8, 4, 1, false) VELORA_MFMA_CASE(8, 5, 1, false) VELORA_MFMA_CASE(8, 6, 1, false)
     VELORA_MFMA_CASE(4, 1, 1, true) VELORA_MFMA_CASE(4, 2, 1, true) VELORA_MFMA_CASE(4, 3, 1, true)
@@ -929,6 +1075,12 @@ WgradPlan plan_wgrad_uncached(int64_t N, int64_t O, int64_t D, int64_t M, bool i
         p.packed_bytes = static_cast<size_t>(ceil_div(N, kStep)) * static_cast<size_t>(p.tiles_packed) * 1024;
     }
     p.ws_bytes = p.partial_bytes + p.packed_bytes;
+    // Chunks of 128 tokens dealt to the splits round-robin (see wgrad_partial_mfma_kernel) when a block's
+    // 32-bit offsets can span the whole arrays; otherwise every split keeps a contiguous range.
+    const double lim = 2147483648.0 - 16777216.0;
+    p.cyclic = is_bf16 && env_int("VELORA_WGRAD_CYCLIC", 1) != 0 &&
+               static_cast<double>(N) * static_cast<double>(O) * 2.0 < lim &&
+               static_cast<double>(N) * static_cast<double>(M) * 2.0 < lim && static_cast<double>(p.packed_bytes) < lim;
     return p;
 }
 }  // namespace
@@ -979,6 +1131,36 @@ hipError_t expand_any(const float* partial, int splits, int64_t Mp, const float*
                : launch_expand<false, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, false, st);
 }
 
+template <bool OUT_BF16, int VW>
+hipError_t launch_expand_flat(const float* T, int64_t t_stride, const float* v, void* dW, int64_t O, int64_t D,
+                              int64_t M, bool accumulate, const LaunchCfg& cfg, hipStream_t st) {
+    const int64_t n_vec = O * D / VW;
+    int64_t blocks = cfg.num_cus;                                // one block per compute unit
+    if (blocks > ceil_div(n_vec, 256)) blocks = ceil_div(n_vec, 256);
+    hipLaunchKernelGGL((wgrad_expand_flat_kernel<OUT_BF16, VW>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, T,
+                       t_stride, v, dW, static_cast<uint32_t>(n_vec), static_cast<uint32_t>(D / VW),
+                       static_cast<uint32_t>(D / M / VW), static_cast<uint32_t>(M), accumulate ? 1 : 0);
+    return hipGetLastError();
+}
+
+// dW (+)= T (x) v from a summed T with row stride t_stride: the flat sweep when its vectors fit the
+// shape and the pointers, else the row-by-row kernel on a single "split".
+hipError_t expand_from_t(const float* T, int64_t t_stride, const float* v, int v_align, void* dW, bool dw_bf16,
+                         int dw_align, bool accumulate, int64_t O, int64_t D, int64_t M, const LaunchCfg& cfg,
+                         hipStream_t st) {
+    const int64_t d = D / M;
+    const bool small = static_cast<double>(O) * static_cast<double>(D) / 4.0 < 2147483648.0 - 16777216.0;
+    if (small && v_align >= 16 && env_int("VELORA_WGRAD_FLAT", 1) != 0) {
+        if (!dw_bf16 && d % 4 == 0 && dw_align >= 16)
+            return launch_expand_flat<false, 4>(T, t_stride, v, dW, O, D, M, accumulate, cfg, st);
+        if (dw_bf16 && d % 8 == 0 && dw_align >= 16)
+            return launch_expand_flat<true, 8>(T, t_stride, v, dW, O, D, M, accumulate, cfg, st);
+        if (dw_bf16 && d % 4 == 0 && dw_align >= 8)
+            return launch_expand_flat<true, 4>(T, t_stride, v, dW, O, D, M, accumulate, cfg, st);
+    }
+    return expand_any(T, 1, t_stride, v, v_align, dW, dw_bf16, dw_align, accumulate, O, D, M, st);
+}
+
 }  // namespace
 
 // T[o, g] = sum over splits of partial[split][o][g], fixed order; T is dense [O, M].
@@ -1025,8 +1207,8 @@ hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t 
 }
 
 hipError_t launch_expand_factor(const float* T, const float* v, int v_align, void* dW, bool dw_bf16, int dw_align,
-                                bool accumulate, int64_t O, int64_t D, int64_t M, hipStream_t st) {
-    return expand_any(T, 1, M, v, v_align, dW, dw_bf16, dw_align, accumulate, O, D, M, st);
+                                bool accumulate, int64_t O, int64_t D, int64_t M, const LaunchCfg& cfg, hipStream_t st) {
+    return expand_from_t(T, M, v, v_align, dW, dw_bf16, dw_align, accumulate, O, D, M, cfg, st);
 }
 
 }  // namespace velora
