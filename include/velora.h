@@ -304,6 +304,23 @@ velora_status velora_adamw_step_factor(const float* T, const float* v, int64_t O
                                        float beta2, float eps, float weight_decay, int64_t step, float grad_scale,
                                        velora_stream stream);
 
+/*
+ * Measurement aid, not part of the method: the plainest streaming kernels this
+ * library can write, for a benchmark that wants to state a kernel's rate against
+ * a ceiling measured on the same box in the same run (the hot path is bound by
+ * HBM; see velora_compress and velora_weight_grad).
+ *   kind 0  read:  every 16-byte vector of src[0, bytes) is loaded once; sink
+ *                  (device, 64 uint32, zeroed by the caller or not) receives
+ *                  folded words so that the loads are real.  dst is ignored.
+ *   kind 1  write: zeros to dst[0, bytes).  src and sink are ignored.
+ *   kind 2  copy:  dst[0, bytes) = src[0, bytes).  sink is ignored.
+ * bytes > 0 and a multiple of 16, the pointers used 16-byte aligned
+ * (VELORA_ERR_SHAPE / VELORA_ERR_ALIGN / VELORA_ERR_NULL otherwise); one block
+ * per compute unit, eight 16-byte accesses in flight per thread, non-temporal.
+ */
+velora_status velora_bandwidth_probe(int kind, const void* src, void* dst, int64_t bytes, uint32_t* sink,
+                                     velora_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

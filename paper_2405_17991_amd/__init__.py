@@ -12,7 +12,7 @@ that ``python -m paper_2405_17991_amd.build`` can (re)build it.
 _NAMES = (
     "VeloraError", "lib_path", "velora_compress", "velora_init_v", "velora_reconstruct",
     "velora_status_string", "velora_version", "velora_weight_grad", "velora_weight_grad_static",
-    "STATIC_SCRATCH_BYTES", "velora_weight_grad_factor",
+    "STATIC_SCRATCH_BYTES", "velora_bandwidth_probe", "velora_weight_grad_factor",
     "velora_expand_factor", "velora_update_v", "velora_compress_update", "velora_adamw_step_factor", "velora_swiglu_compress", "velora_rmsnorm_compress", "velora_linear_compress", "velora_grad_input",
     "velora_workspace_bytes", "OP_COMPRESS", "OP_INIT_V", "OP_RECONSTRUCT",
     "OP_WEIGHT_GRAD", "OP_WEIGHT_GRAD_FACTOR", "F32", "BF16", "STATUS",

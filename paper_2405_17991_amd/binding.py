@@ -33,6 +33,7 @@ EXPORTS = [
     "velora_weight_grad_factor",
     "velora_expand_factor", "velora_update_v", "velora_compress_update", "velora_adamw_step_factor",
     "velora_swiglu_compress", "velora_rmsnorm_compress", "velora_linear_compress", "velora_grad_input",
+    "velora_bandwidth_probe",
 ]
 
 
@@ -85,6 +86,8 @@ def _load() -> ctypes.CDLL:
     cf = ctypes.c_float
     L.velora_adamw_step_factor.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, cf, cf, cf, cf, cf, i64, cf, vp]
     L.velora_adamw_step_factor.restype = ci
+    L.velora_bandwidth_probe.argtypes = [ci, vp, vp, i64, vp, vp]
+    L.velora_bandwidth_probe.restype = ci
     L.velora_update_v.argtypes = [vp, i64, i64, i64, ci, vp, cf, vp, vp, sz, vp]
     L.velora_update_v.restype = ci
     L.velora_compress_update.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp, cf, vp, vp, sz, vp]
@@ -363,6 +366,18 @@ def velora_weight_grad_static(G, S, v, D: int, dW, accumulate: bool = False):
                                        _dt(dW), 1 if accumulate else 0, _stream())
     _raise(st, "velora_weight_grad_static")
     return dW
+
+
+def velora_bandwidth_probe(kind: str, src=None, dst=None, sink=None):
+    """The library's plainest streaming kernels (a measurement aid): kind 'read' (src, sink = 64 int32),
+    'write' (dst) or 'copy' (src -> dst), over the whole tensors."""
+    k = {"read": 0, "write": 1, "copy": 2}[kind]
+    t = src if k != 1 else dst
+    nbytes = t.numel() * t.element_size()
+    st = raw.velora_bandwidth_probe(k, src.data_ptr() if src is not None else None,
+                                    dst.data_ptr() if dst is not None else None, nbytes,
+                                    sink.data_ptr() if sink is not None else None, _stream())
+    _raise(st, "velora_bandwidth_probe")
 
 
 STATIC_SCRATCH_BYTES = 64 << 20     # VELORA_STATIC_SCRATCH_BYTES of include/velora.h

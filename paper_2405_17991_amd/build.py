@@ -18,7 +18,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libvelora.so")
-SOURCES = ["api.hip", "compress.hip", "init_v.hip", "wgrad.hip", "adamw.hip", "swiglu.hip", "rmsnorm.hip", "linear.hip"]
+SOURCES = ["api.hip", "compress.hip", "init_v.hip", "wgrad.hip", "adamw.hip", "swiglu.hip", "rmsnorm.hip", "linear.hip", "probe.hip"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "kernels.h"),
            os.path.join(os.path.dirname(HERE), "include", "velora.h")]
 

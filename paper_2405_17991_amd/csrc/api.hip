@@ -381,4 +381,13 @@ velora_status velora_adamw_step_factor(const float* T, const float* v, int64_t O
                                                   static_cast<hipStream_t>(stream)));
 }
 
+velora_status velora_bandwidth_probe(int kind, const void* src, void* dst, int64_t bytes, uint32_t* sink,
+                                     velora_stream stream) {
+    if (kind < 0 || kind > 2 || bytes <= 0 || bytes % 16 != 0) return VELORA_ERR_SHAPE;
+    if ((kind != 1 && !src) || (kind != 0 && !dst) || (kind == 0 && !sink)) return VELORA_ERR_NULL;
+    if ((kind != 1 && ptr_align(src) < 16) || (kind != 0 && ptr_align(dst) < 16) || (kind == 0 && ptr_align(sink) < 4))
+        return VELORA_ERR_ALIGN;
+    return hip_status(velora::launch_probe(kind, src, dst, bytes, sink, current_cfg(), static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -93,6 +93,12 @@ hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t 
 hipError_t launch_expand_factor(const float* T, const float* v, int v_align, void* dW, bool dw_bf16, int dw_align,
                                 bool accumulate, int64_t O, int64_t D, int64_t M, const LaunchCfg& cfg, hipStream_t st);
 
+// ---- probe.hip ----
+// kind 0: read `bytes` of src (a folded word per block is xor-ed into sink[0..63]); 1: write `bytes` of
+// zeros to dst; 2: copy.  bytes a multiple of 16, pointers 16-byte aligned.
+hipError_t launch_probe(int kind, const void* src, void* dst, int64_t bytes, uint32_t* sink, const LaunchCfg& cfg,
+                        hipStream_t st);
+
 // ---- adamw.hip ----
 // Scalars of one AdamW step, precomputed on the host in double precision.
 struct AdamWScalars {

@@ -862,7 +862,7 @@ MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan)
         return ch;
     if (tl.chunks > 65535) return ch;
     if (static_cast<double>(plan.rows_per_split) * static_cast<double>(M) * 2.0 >= 2147483648.0) return ch;
-    int cw = 8;
+    int cw = env_int("VELORA_WGRAD_CW", 8);
     while (cw >= 4 && (O % cw != 0 || g_align < 2 * cw)) cw >>= 1;
     if (cw < 4) return ch;
     ch.cw = cw; ch.gt = tl.gt; ch.nw = tl.nw; ch.chunks = static_cast<int>(tl.chunks);
