@@ -334,7 +334,7 @@ velora_status velora_weight_grad_factor(const void* G, const void* S, int64_t N,
     const velora::WgradPlan plan = velora::plan_wgrad(N, O, M, M, bf, cfg);
     if (!ws || ws_bytes < plan.ws_bytes) return VELORA_ERR_WORKSPACE;
     if (ptr_align(ws) < 16) return VELORA_ERR_ALIGN;
-    return hip_status(velora::launch_wgrad_factor(G, S, N, O, M, bf, ptr_align(G), T, ws, plan,
+    return hip_status(velora::launch_wgrad_factor(G, S, N, O, M, bf, ptr_align(G), ptr_align(S), T, ws, plan,
                                                   static_cast<hipStream_t>(stream)));
 }
 

@@ -205,7 +205,10 @@ hipError_t launch_compress_vec(const void* X, const float* v, void* S, int64_t n
                                hipStream_t st) {
     constexpr int SEG = kWave / P;
     const int64_t n_chunks = ceil_div(n_sub, static_cast<int64_t>(SEG) * U);
-    const int grid = grid_for(n_chunks, kBlock / kWave, cfg.max_blocks);
+    // Sub-tokens of more than 64 vectors (L > 1) keep 8 KB per wave in flight with fewer, longer sums per
+    // wave; two blocks per compute unit then do better than eight (29.7 against 32.2 us on N = 16384,
+    // D = 5120, d = 1024), as they do for a plain read stream on this chip.
+    const int grid = grid_for(n_chunks, kBlock / kWave, L > 1 ? cfg.num_cus * 2 : cfg.max_blocks);
     hipLaunchKernelGGL((compress_vec_kernel<E, P, L, U>), dim3(grid), dim3(kBlock), 0, st,
                        static_cast<const typename E::vec*>(X), v, static_cast<typename E::type*>(S), n_sub, vps);
     return hipGetLastError();

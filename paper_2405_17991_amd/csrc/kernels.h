@@ -89,7 +89,7 @@ hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N,
 
 // T[O, M] = G^T S only (the factor of the gradient), and its expansion dW (+)= T (x) v.
 hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t O, int64_t M, bool is_bf16,
-                               int g_align, float* T, void* ws, const WgradPlan& plan, hipStream_t st);
+                               int g_align, int s_align, float* T, void* ws, const WgradPlan& plan, hipStream_t st);
 hipError_t launch_expand_factor(const float* T, const float* v, int v_align, void* dW, bool dw_bf16, int dw_align,
                                 bool accumulate, int64_t O, int64_t D, int64_t M, const LaunchCfg& cfg, hipStream_t st);
 

@@ -15,6 +15,7 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <atomic>
 #ifdef VELORA_TUNING
 #include <cstdlib>
 #endif
@@ -353,6 +354,207 @@ __global__ __launch_bounds__(256) void wgrad_partial_mfma_kernel(const uint16_t*
                 }
         }
         if (p0 + TP < NACC) __syncthreads();   // the next pass overwrites both regions
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 1, MFMA path with loader waves (up to three group tiles, 16-byte aligned G and S).
+//
+// The per-wave kernel above makes every wave do everything in turn: wait for its loads, transpose,
+// issue the next loads, run the MFMAs.  While a wave transposes and multiplies it requests nothing,
+// and with the whole accumulator tile in its registers only one such wave fits on a SIMD, so the
+// memory pipe drains at every step (the same kernel with the arithmetic taken out streams G 5 us
+// faster on N = 16384, O = 4096, M = 43).  Here the two jobs belong to different waves of one block:
+//   waves 0-3  only load: G tiles (32 tokens x 128 features each) and the S rows of the same tokens go
+//              straight from memory into an LDS ring (buffer loads with the LDS bit: no registers, no
+//              waiting for one's own arithmetic); a lane whose offset lies outside the descriptor
+//              writes zeros, so edges need no branches here either;
+//   waves 4-7  only compute: each takes one 32-token step of every 128-token chunk out of LDS (eight
+//              16-byte reads per lane for G, eight 2-byte reads per group tile for S), transposes it
+//              in registers exactly as above and runs the MFMAs; they issue no memory loads at all.
+// One barrier per chunk hands a filled slot to the computing waves and an emptied one back to the
+// loaders; the ring has three slots, so the loaders are always one to two chunks (43-88 KB per
+// compute unit) ahead.  Every wave executes every barrier, whatever its role, and the trip count is the
+// same for all waves of a block.  The cross-wave sum and the stores at the end are those of the
+// per-wave kernel, done by waves 4-7 in the ring's memory.
+// Dynamic LDS: 3 x (32 KB + GT x 4 KB) + 16 bytes.  grid = (o tiles of 128, splits, 1).
+// ---------------------------------------------------------------------------
+constexpr int kWsSlots = 3;
+constexpr int kWsGroupRows = kStep * kWavesPerBlock;                  // 128 tokens per chunk
+constexpr int kWsGBytes = kWsGroupRows * 256;                         // one chunk of a 128-feature stripe
+constexpr size_t ws_kernel_lds_bytes(int gt) { return static_cast<size_t>(kWsSlots) * (kWsGBytes + gt * 4096) + 16; }
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+template <int GT>
+__global__ __launch_bounds__(512) void wgrad_partial_ws_kernel(const uint16_t* __restrict__ G,
+                                                              const uint16_t* __restrict__ S,
+                                                              float* __restrict__ partial, int64_t N, int64_t O,
+                                                              int64_t M, int64_t Mp, int64_t rows_per_split,
+                                                              int cyclic) {
+    constexpr int CW = 8, OT = 128;
+    constexpr int NACC = GT * CW;
+    constexpr int TP = NACC;                              // <= 24 tiles: one pass of the cross-wave sum
+    constexpr int kSBytes = GT * 4096;                    // S rows of one chunk: 128 tokens x M x 2 bytes <= this
+    constexpr int kSlotBytes = kWsGBytes + kSBytes;
+    constexpr int kLoadsPerChunk = 8 + GT;                // per loader wave: 8 of G, GT of S
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const bool loader = w < kWavesPerBlock;
+    const int mw = w - kWavesPerBlock;                    // computing wave: which 32-token step of a chunk
+    const int q = lane >> 4;
+    const int jj = lane & 15;
+    const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
+    const int split = blockIdx.y;
+    const int splits = gridDim.y;
+    int64_t row0, span_rows;
+    int n_chunks;
+    uint32_t chunk_stride;
+    if (cyclic) {
+        const int64_t total_chunks = ceil_div(N, kWsGroupRows);
+        row0 = static_cast<int64_t>(split) * kWsGroupRows;
+        span_rows = N - row0;
+        n_chunks = static_cast<int>((total_chunks - split + splits - 1) / splits);
+        chunk_stride = static_cast<uint32_t>(splits) * kWsGroupRows;
+    } else {
+        row0 = static_cast<int64_t>(split) * rows_per_split;
+        span_rows = N - row0 < rows_per_split ? N - row0 : rows_per_split;
+        n_chunks = static_cast<int>(ceil_div(span_rows, kWsGroupRows));
+        chunk_stride = kWsGroupRows;
+    }
+    constexpr uint32_t kLaneOut = 0x7FFFFFFFu, kStepOut = 0x80000000u;
+    const uint32_t row_bytes = static_cast<uint32_t>(O) * 2u;
+    const uint32_t s_row_bytes = static_cast<uint32_t>(M) * 2u;
+
+    // ---- loader state: lane (lr = lane / 16, piece = lane % 16) fetches 16 bytes of row 32*w + 4*r + lr
+    const bool col_ok = o0 + jj * CW < O;
+    const uint32_t voff_g0 =
+        col_ok ? static_cast<uint32_t>(32 * (w & 3) + q) * row_bytes + static_cast<uint32_t>(jj * 16) : kLaneOut;
+    const uint32_t voff_gstep = col_ok ? 4u * row_bytes : 0u;     // from one of the eight loads to the next
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(G) + (row0 * O + o0) * 2), 0,
+        static_cast<int>(static_cast<uint32_t>(span_rows) * row_bytes - static_cast<uint32_t>(o0 * 2)), 0x00020000);
+    const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(S) + row0 * M * 2), 0,
+        static_cast<int>(static_cast<uint32_t>(span_rows) * s_row_bytes), 0x00020000);
+    auto issue_chunk = [&](int i) {
+        char* slot = lds + (i % kWsSlots) * kSlotBytes;
+        const bool real = i < n_chunks;
+        const uint32_t g_off = real ? static_cast<uint32_t>(i) * chunk_stride * row_bytes : kStepOut;
+        const uint32_t s_off = real ? static_cast<uint32_t>(i) * chunk_stride * s_row_bytes : kStepOut;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(g_rsrc, (lds_void_ptr)(slot + (32 * (w & 3) + 4 * r) * 256), 16,
+                                                     voff_g0 + r * voff_gstep + g_off, 0, 0, kStreamAux);
+        // the chunk's S rows are one contiguous run of 128 * M * 2 bytes; KB j of it goes to loader wave j % 4
+#pragma unroll
+        for (int t = 0; t < GT; ++t) {
+            const uint32_t kb = static_cast<uint32_t>((w & 3) + 4 * t);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(s_rsrc, (lds_void_ptr)(slot + kWsGBytes + kb * 1024), 16,
+                                                     kb * 1024u + static_cast<uint32_t>(lane) * 16u + s_off, 0, 0, 0);
+        }
+    };
+
+    // ---- computing state
+    f32x4 acc[GT][CW];
+#pragma unroll
+    for (int a = 0; a < GT; ++a)
+#pragma unroll
+        for (int c = 0; c < CW; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // byte offsets inside a slot: this lane's first G row (the other seven are 256 bytes apart) and its S
+    // value of token 8q + e, group jj (tile a: + 32 a bytes).  A lane whose group lies past M in the last
+    // tile reads some other token's value there and replaces it by zero afterwards.
+    const int zero_off = kWsSlots * kSlotBytes;
+    const int g_lds0 = (32 * (mw & 3) + 8 * q) * 256 + jj * 16;
+    int s_lds[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s_lds[e] = kWsGBytes + ((32 * (mw & 3) + 8 * q + e) * static_cast<int>(M) + jj) * 2;
+    const bool last_tile_ok = (GT - 1) * 16 + jj < M;
+    (void)zero_off;
+
+    // Two loops, one per role, with the same number of barriers.  Barrier i says: chunk i is in its slot
+    // for everybody, and the slot of chunk i - 1 is free again.  It is a bare s_barrier: the loaders have
+    // just waited for exactly the loads that matter, and the computing waves' LDS reads of chunk i - 1
+    // ended with the MFMAs that consumed them; __syncthreads() would add a fence that makes every loader
+    // wait for ALL its loads, the chunk in flight included.
+    if (loader) {
+        issue_chunk(0);
+        issue_chunk(1);
+        for (int i = 0; i < n_chunks; ++i) {
+            // everything but the youngest chunk's loads of this wave has landed in LDS
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (kLoadsPerChunk & 15) | ((kLoadsPerChunk >> 4) << 14));
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue_chunk(i + 2);
+        }
+    } else {
+        for (int i = 0; i < n_chunks; ++i) {
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const int slot_off = (i % kWsSlots) * kSlotBytes;
+            RawRow<4> rows[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const uint4 x = *reinterpret_cast<const uint4*>(lds + slot_off + g_lds0 + r * 256);
+                rows[r].w[0] = x.x; rows[r].w[1] = x.y; rows[r].w[2] = x.z; rows[r].w[3] = x.w;
+            }
+            uint32_t sv[GT][8];
+#pragma unroll
+            for (int a = 0; a < GT; ++a)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    sv[a][e] = *reinterpret_cast<const uint16_t*>(lds + slot_off + s_lds[e] + a * 32);
+            bf16x8 gf[CW];
+#pragma unroll
+            for (int c = 0; c < CW; ++c) gf[c] = column_fragment(rows, c);
+#pragma unroll
+            for (int a = 0; a < GT; ++a) {
+                uint4 f = make_uint4(__builtin_amdgcn_perm(sv[a][1], sv[a][0], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[a][3], sv[a][2], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[a][5], sv[a][4], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[a][7], sv[a][6], 0x05040100u));
+                if (a == GT - 1 && !last_tile_ok) f = make_uint4(0u, 0u, 0u, 0u);
+                const bf16x8 sf = __builtin_bit_cast(bf16x8, f);
+#pragma unroll
+                for (int c = 0; c < CW; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
+            }
+        }
+    }
+    // the loaders' last two (empty) chunks must have landed before the ring is reused
+    if (loader) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+
+    // (w4 + w5) + (w6 + w7), as in the per-wave kernel; the loaders only keep the barriers company
+    f32x4 (*red)[TP][kWave] = reinterpret_cast<f32x4 (*)[TP][kWave]>(lds);
+    float* out = partial + static_cast<int64_t>(split) * O * Mp;
+    constexpr int H = (TP + 1) / 2;
+    if (mw == 1 || mw == 3) {
+#pragma unroll
+        for (int i = 0; i < TP; ++i) red[mw >> 1][i][lane] = acc[i / CW][i % CW];
+    }
+    __syncthreads();
+    if (mw == 0 || mw == 2) {
+#pragma unroll
+        for (int i = 0; i < TP; ++i) acc[i / CW][i % CW] += red[mw >> 1][i][lane];
+#pragma unroll
+        for (int i = 0; i < TP; ++i)
+            if ((mw == 2) == (i < H)) red[mw >> 1][i][lane] = acc[i / CW][i % CW];
+    }
+    __syncthreads();
+    if (mw == 0 || mw == 2) {
+#pragma unroll
+        for (int i = 0; i < TP; ++i)
+            if ((mw == 0) == (i < H)) {
+                const int a = i / CW, c = i % CW;
+                const f32x4 other = red[mw == 0 ? 1 : 0][i][lane];
+                const f32x4 t = mw == 0 ? acc[a][c] + other : other + acc[a][c];
+                store_tile<CW>(out, t, o0, jj, q, c, a * 16, O, Mp);
+            }
     }
 }
 
@@ -814,6 +1016,7 @@ constexpr int env_int(const char*, int fallback) { return fallback; }
 struct MfmaChoice {
     int cw, gt, nw, chunks;   // cw == 0: the MFMA path cannot take this call
     bool shared;
+    bool s_align16;           // S is 16-byte aligned (the loader-wave kernel moves it in 16-byte pieces)
 };
 
 // How a block covers the group axis.  Depends on M only, so the workspace query
@@ -852,8 +1055,8 @@ Tiling tiling_for(int64_t M) {
 // issue slots than the packing pre-pass does time) or the packed fragment array.
 bool direct_s(const Tiling& t) { return !t.shared && t.gt <= 3; }
 
-MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, const WgradPlan& plan) {
-    MfmaChoice ch{0, 0, 4, 0, false};
+MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, int s_align, const WgradPlan& plan) {
+    MfmaChoice ch{0, 0, 4, 0, false, s_align >= 16};
     const Tiling tl = tiling_for(M);
     // byte offsets inside a block's token range are 32-bit
     if (static_cast<double>(plan.rows_per_split) * static_cast<double>(O) * 2.0 >= 2147483648.0) return ch;
@@ -878,6 +1081,28 @@ hipError_t launch_mfma(const void* G, const void* s_operand, float* partial, int
     hipLaunchKernelGGL((wgrad_partial_mfma_kernel<CW, GT, NST, DIRECT>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(G), s_operand, partial, N, O, M, plan.Mp, plan.rows_per_split,
                        plan.tiles_packed, plan.cyclic ? 1 : 0);
+    return hipGetLastError();
+}
+
+template <int GT>
+hipError_t launch_ws(const void* G, const void* S, float* partial, int64_t N, int64_t O, int64_t M, const WgradPlan& plan,
+                     hipStream_t st) {
+    // more than 64 KB of dynamic LDS has to be allowed once per device and kernel
+    static std::atomic<bool> allowed[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const size_t lds_bytes = ws_kernel_lds_bytes(GT);
+    if (dev < 0 || dev >= 64 || !allowed[dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_ws_kernel<GT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) allowed[dev].store(true, std::memory_order_release);
+    }
+    dim3 grid(static_cast<unsigned>(ceil_div(O, 128)), static_cast<unsigned>(plan.splits), 1);
+    hipLaunchKernelGGL((wgrad_partial_ws_kernel<GT>), grid, dim3(512), lds_bytes, st, static_cast<const uint16_t*>(G),
+                       static_cast<const uint16_t*>(S), partial, N, O, M, plan.Mp, plan.rows_per_split,
+                       plan.cyclic ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -906,6 +1131,19 @@ hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_oper
     VELORA_SHARED_G_CASE(8, 4, 8, 4) VELORA_SHARED_G_CASE(12, 4, 8, 4) VELORA_SHARED_G_CASE(16, 4, 8, 4)
     VELORA_SHARED_G_CASE(8, 8, 8, 4) VELORA_SHARED_G_CASE(16, 8, 8, 4)
     if (ch.shared) { *handled = false; return hipSuccess; }
+    // loader waves + computing waves: up to three group tiles straight from S[N, M], 16-byte loads of both
+    // (N * M even: a buffer load checks its range per 4 bytes, and the last 2-byte value of an odd-sized S
+    // would sit in a word that straddles the end of the array)
+    // With a single group tile the per-wave kernel is as fast (62.4 against 63.2 us on N = 16384, O = 11008,
+    // M = 16) and stays; with two or three the split is worth 2-6 us (29.0 against 30.8 us on O = 4096,
+    // M = 43; 78.5 against 84.4 us on O = 13824, M = 20).
+    const int ws_mode = env_int("VELORA_WGRAD_WS", 1);   // measurement builds: 0 never, 2 also for one tile
+    if (ch.cw == 8 && ch.gt <= 3 && (ch.gt >= 2 || ws_mode == 2) && ch.s_align16 && plan.tiles_packed == 0 &&
+        (N * M) % 2 == 0 && ws_mode != 0) {
+        if (ch.gt == 1) return launch_ws<1>(G, s_operand, partial, N, O, M, plan, st);
+        if (ch.gt == 2) return launch_ws<2>(G, s_operand, partial, N, O, M, plan, st);
+        return launch_ws<3>(G, s_operand, partial, N, O, M, plan, st);
+    }
     // Ring depth 1 everywhere it was measured (2-4 were 1-5 us slower on every layer
     // shape): a CU sustains a fixed number of outstanding cache-line requests, which
     // four waves with one 32-token step each already exceed, and deeper rings only
@@ -1089,12 +1327,12 @@ namespace {
 
 // pack (if needed) + partial kernel: leaves partial[splits][O][Mp] in the workspace
 hipError_t launch_partials(const void* G, const void* S, int64_t N, int64_t O, int64_t M, bool is_bf16, int g_align,
-                           void* ws, const WgradPlan& plan, int phases, hipStream_t st) {
+                           int s_align, void* ws, const WgradPlan& plan, int phases, hipStream_t st) {
     float* partial = static_cast<float*>(ws);
     hipError_t e = hipSuccess;
     bool done = false;
     if (is_bf16 && env_int("VELORA_WGRAD_FORCE_SIMPLE", 0) == 0) {
-        const MfmaChoice ch = choose_mfma(O, M, g_align, plan);
+        const MfmaChoice ch = choose_mfma(O, M, g_align, s_align, plan);
         if (ch.cw != 0) {
             const void* s_operand = S;
             if (plan.tiles_packed > 0) {
@@ -1188,9 +1426,8 @@ hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N,
                         bool is_bf16, int g_align, int s_align, int v_align, void* dW, bool dw_bf16, int dw_align,
                         bool accumulate, void* ws, const WgradPlan& plan, const LaunchCfg& cfg, hipStream_t st) {
     (void)cfg;
-    (void)s_align;
     const int phases = env_int("VELORA_WGRAD_PHASES", 7);   // tuning aid: 1 pack, 2 partial, 4 expand
-    hipError_t e = launch_partials(G, S, N, O, M, is_bf16, g_align, ws, plan, phases, st);
+    hipError_t e = launch_partials(G, S, N, O, M, is_bf16, g_align, s_align, ws, plan, phases, st);
     if (e != hipSuccess) return e;
     if (!(phases & 4)) return hipSuccess;
     return expand_any(static_cast<const float*>(ws), plan.splits, plan.Mp, v, v_align, dW, dw_bf16, dw_align, accumulate,
@@ -1198,8 +1435,8 @@ hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N,
 }
 
 hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t O, int64_t M, bool is_bf16,
-                               int g_align, float* T, void* ws, const WgradPlan& plan, hipStream_t st) {
-    hipError_t e = launch_partials(G, S, N, O, M, is_bf16, g_align, ws, plan, 7, st);
+                               int g_align, int s_align, float* T, void* ws, const WgradPlan& plan, hipStream_t st) {
+    hipError_t e = launch_partials(G, S, N, O, M, is_bf16, g_align, s_align, ws, plan, 7, st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(O * M, 256))), dim3(256), 0, st,
                        static_cast<const float*>(ws), T, plan.splits, O, M, plan.Mp);

@@ -242,6 +242,16 @@ WGRAD_CASES = [
     (130, 32, 40, 1, wl.BF16),                 # d = 1: dW = G^T S
     (90, 48, 512, 512, wl.BF16),               # M = 1: rank-one gradient
     (1, 16, 64, 16, wl.BF16), (31, 8, 16, 8, wl.BF16),
+    # two and three group tiles take the kernel whose loader waves stage G and S in LDS: token counts around
+    # its 128-token chunks (127, 128, 129, one short of and one past several chunks per split), output widths
+    # around its 128-feature tiles, group counts at both ends of each tile count, an odd N * M (falls back to
+    # the per-wave kernel), and enough tokens that every split walks the three-slot ring more than once
+    (127, 128, 544, 32, wl.BF16), (128, 8, 1024, 32, wl.BF16), (129, 136, 1056, 32, wl.BF16),   # M = 17, 32, 33
+    (2, 264, 1536, 32, wl.BF16),                 # M = 48, two tokens
+    (383, 120, 704, 16, wl.BF16),                # M = 44, odd N, even N * M
+    (385, 128, 752, 16, wl.BF16),                # M = 47, N * M odd
+    (40000, 128, 272, 16, wl.BF16),              # M = 17: 313 chunks, more than two per split
+    (33000, 256, 1376, 32, wl.BF16),             # M = 43, ragged last chunk
 ]
 
 
