@@ -559,6 +559,178 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws_kernel(const uint16_t* _
 }
 
 // ---------------------------------------------------------------------------
+// Kernel 1, loader waves, four to six group tiles (M up to 96).
+//
+// The same division of labour as above for tile counts whose accumulators no longer fit one wave per
+// 128 features.  Chunks are 64 tokens (two 32-token steps), so that three ring slots of G (16 KB) and S
+// rows (up to 12 KB) fit in LDS; the computing waves split a chunk four ways, by step (2) and by half of
+// the 128 features (2): wave (step, half) reads 8 bytes per G row (its four strided columns), holds
+// GT x 4 accumulator tiles, and takes its S values for one group tile at a time.  S comes straight from
+// S[N, M]: no re-layout pre-pass (one launch and a round trip of S through memory less than the
+// per-wave kernel needs at these tile counts).  At the end the two steps of each half are added
+// (step 0 + step 1) and the step-0 waves store their halves of the tile.
+// Dynamic LDS: 3 x (16 KB + NS x 4 KB), NS = 2 (four tiles) or 3.  grid = (o tiles of 128, splits, 1).
+// ---------------------------------------------------------------------------
+constexpr int kWs64Rows = 64;
+constexpr int kWs64GBytes = kWs64Rows * 256;
+constexpr int ws64_s_kb4(int gt) { return (2 * gt + 3) / 4; }          // 4 KB units of S area per slot
+constexpr size_t ws64_kernel_lds_bytes(int gt) { return static_cast<size_t>(kWsSlots) * (kWs64GBytes + ws64_s_kb4(gt) * 4096); }
+
+// column c (0..3) of an 8-row block whose rows hold four 16-bit values (two dwords)
+__device__ __forceinline__ bf16x8 column_fragment4(const uint2 (&rows)[8], int c) {
+    uint32_t f[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t a = (c >> 1) ? rows[2 * i].y : rows[2 * i].x;
+        const uint32_t b = (c >> 1) ? rows[2 * i + 1].y : rows[2 * i + 1].x;
+        f[i] = (c & 1) ? __builtin_amdgcn_perm(b, a, 0x07060302u) : __builtin_amdgcn_perm(b, a, 0x05040100u);
+    }
+    return __builtin_bit_cast(bf16x8, make_uint4(f[0], f[1], f[2], f[3]));
+}
+
+template <int GT>
+__global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t* __restrict__ G,
+                                                                const uint16_t* __restrict__ S,
+                                                                float* __restrict__ partial, int64_t N, int64_t O,
+                                                                int64_t M, int64_t Mp, int64_t rows_per_split,
+                                                                int cyclic) {
+    constexpr int CW = 8, OT = 128, CH = 4;               // CH: column tiles per computing wave
+    constexpr int NS = ws64_s_kb4(GT);                    // S loads per loader wave and chunk
+    constexpr int kSlotBytes = kWs64GBytes + NS * 4096;
+    constexpr int kLoadsPerChunk = 4 + NS;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const bool loader = w < 4;
+    const int mw = w - 4;
+    const int step = mw & 1, half = (mw >> 1) & 1;
+    const int q = lane >> 4;
+    const int jj = lane & 15;
+    const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
+    const int split = blockIdx.y;
+    const int splits = gridDim.y;
+    // the planner's ranges are multiples of 128 tokens; here a chunk is 64, two per 128
+    int64_t row0, span_rows;
+    int n_chunks;
+    uint32_t pair_stride;                                 // rows from one 128-token pair of chunks to the next
+    if (cyclic) {
+        const int64_t total_pairs = ceil_div(N, 128);
+        row0 = static_cast<int64_t>(split) * 128;
+        span_rows = N - row0;
+        n_chunks = 2 * static_cast<int>((total_pairs - split + splits - 1) / splits);
+        pair_stride = static_cast<uint32_t>(splits) * 128u;
+    } else {
+        row0 = static_cast<int64_t>(split) * rows_per_split;
+        span_rows = N - row0 < rows_per_split ? N - row0 : rows_per_split;
+        n_chunks = 2 * static_cast<int>(ceil_div(span_rows, 128));
+        pair_stride = 128u;
+    }
+    auto chunk_row = [&](int i) -> uint32_t { return static_cast<uint32_t>(i >> 1) * pair_stride + static_cast<uint32_t>(i & 1) * 64u; };
+    constexpr uint32_t kLaneOut = 0x7FFFFFFFu, kStepOut = 0x80000000u;
+    const uint32_t row_bytes = static_cast<uint32_t>(O) * 2u;
+    const uint32_t s_row_bytes = static_cast<uint32_t>(M) * 2u;
+
+    const bool col_ok = o0 + jj * CW < O;
+    const uint32_t voff_g0 =
+        col_ok ? static_cast<uint32_t>(16 * (w & 3) + q) * row_bytes + static_cast<uint32_t>(jj * 16) : kLaneOut;
+    const uint32_t voff_gstep = col_ok ? 4u * row_bytes : 0u;
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(G) + (row0 * O + o0) * 2), 0,
+        static_cast<int>(static_cast<uint32_t>(span_rows) * row_bytes - static_cast<uint32_t>(o0 * 2)), 0x00020000);
+    const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(S) + row0 * M * 2), 0,
+        static_cast<int>(static_cast<uint32_t>(span_rows) * s_row_bytes), 0x00020000);
+    auto issue_chunk = [&](int i) {
+        char* slot = lds + (i % kWsSlots) * kSlotBytes;
+        const bool real = i < n_chunks;
+        const uint32_t g_off = real ? chunk_row(i) * row_bytes : kStepOut;
+        const uint32_t s_off = real ? chunk_row(i) * s_row_bytes : kStepOut;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(g_rsrc, (lds_void_ptr)(slot + (16 * (w & 3) + 4 * r) * 256), 16,
+                                                     voff_g0 + r * voff_gstep + g_off, 0, 0, kStreamAux);
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+            const uint32_t kb = static_cast<uint32_t>((w & 3) + 4 * t);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(s_rsrc, (lds_void_ptr)(slot + kWs64GBytes + kb * 1024), 16,
+                                                     kb * 1024u + static_cast<uint32_t>(lane) * 16u + s_off, 0, 0, 0);
+        }
+    };
+
+    f32x4 acc[GT][CH];
+#pragma unroll
+    for (int a = 0; a < GT; ++a)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int g_lds0 = (32 * step + 8 * q) * 256 + jj * 16 + half * 8;
+    int s_lds[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s_lds[e] = kWs64GBytes + ((32 * step + 8 * q + e) * static_cast<int>(M) + jj) * 2;
+    const bool last_tile_ok = (GT - 1) * 16 + jj < M;
+
+    if (loader) {
+        issue_chunk(0);
+        issue_chunk(1);
+        for (int i = 0; i < n_chunks; ++i) {
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (kLoadsPerChunk & 15) | ((kLoadsPerChunk >> 4) << 14));
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue_chunk(i + 2);
+        }
+    } else {
+        for (int i = 0; i < n_chunks; ++i) {
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const int slot_off = (i % kWsSlots) * kSlotBytes;
+            uint2 rows[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) rows[r] = *reinterpret_cast<const uint2*>(lds + slot_off + g_lds0 + r * 256);
+            bf16x8 gf[CH];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) gf[c] = column_fragment4(rows, c);
+#pragma unroll
+            for (int a = 0; a < GT; ++a) {
+                uint32_t sv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sv[e] = *reinterpret_cast<const uint16_t*>(lds + slot_off + s_lds[e] + a * 32);
+                uint4 f = make_uint4(__builtin_amdgcn_perm(sv[1], sv[0], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[3], sv[2], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[5], sv[4], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[7], sv[6], 0x05040100u));
+                if (a == GT - 1 && !last_tile_ok) f = make_uint4(0u, 0u, 0u, 0u);
+                const bf16x8 sf = __builtin_bit_cast(bf16x8, f);
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
+            }
+        }
+    }
+    if (loader) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+
+    // step 0 + step 1 for each half of the features; the step-0 waves store
+    constexpr int NT = GT * CH;                            // tiles per computing wave (<= 24)
+    f32x4 (*red)[NT][kWave] = reinterpret_cast<f32x4 (*)[NT][kWave]>(lds);
+    float* out = partial + static_cast<int64_t>(split) * O * Mp;
+    if (!loader && step == 1) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) red[half][i][lane] = acc[i / CH][i % CH];
+    }
+    __syncthreads();
+    if (!loader && step == 0) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const int a = i / CH, c = i % CH;
+            const f32x4 t = acc[a][c] + red[half][i][lane];
+            store_tile<CW>(out, t, o0, jj, q, half * CH + c, a * 16, O, Mp);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Kernel 1, MFMA path for many group tiles (8, 12 or 16 per block).
 //
 // With that many tiles a wave cannot hold accumulators for all of them, so the
@@ -1106,6 +1278,27 @@ hipError_t launch_ws(const void* G, const void* S, float* partial, int64_t N, in
     return hipGetLastError();
 }
 
+template <int GT>
+hipError_t launch_ws64(const void* G, const void* S, float* partial, int64_t N, int64_t O, int64_t M,
+                       const WgradPlan& plan, hipStream_t st) {
+    static std::atomic<bool> allowed[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const size_t lds_bytes = ws64_kernel_lds_bytes(GT);
+    if (dev < 0 || dev >= 64 || !allowed[dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_ws64_kernel<GT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) allowed[dev].store(true, std::memory_order_release);
+    }
+    dim3 grid(static_cast<unsigned>(ceil_div(O, 128)), static_cast<unsigned>(plan.splits), 1);
+    hipLaunchKernelGGL((wgrad_partial_ws64_kernel<GT>), grid, dim3(512), lds_bytes, st, static_cast<const uint16_t*>(G),
+                       static_cast<const uint16_t*>(S), partial, N, O, M, plan.Mp, plan.rows_per_split,
+                       plan.cyclic ? 1 : 0);
+    return hipGetLastError();
+}
+
 #define VELORA_MFMA_CASE(CW, GT, NST, DIRECT) \
     if (ch.cw == CW && ch.gt == GT)           \
         return launch_mfma<CW, GT, NST, DIRECT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
@@ -1333,6 +1526,19 @@ hipError_t launch_partials(const void* G, const void* S, int64_t N, int64_t O, i
     bool done = false;
     if (is_bf16 && env_int("VELORA_WGRAD_FORCE_SIMPLE", 0) == 0) {
         const MfmaChoice ch = choose_mfma(O, M, g_align, s_align, plan);
+        // Four group tiles: loader waves, S straight from S[N, M], no re-layout pre-pass (N * M even for the
+        // same reason as in dispatch_mfma): 28.6 against 36.2 us on N = 16384, O = 4096, M = 64 and 35.6
+        // against 42.6 us on O = 5120, M = 54, pre-pass included.  With five tiles the same kernel measured
+        // level on O = 5120 and 11 % slower on O = 13824 (M = 80), so five and six stay with the per-wave
+        // kernel (measurement builds: VELORA_WGRAD_WS=2 sends them here too).
+        const int ws_mode = env_int("VELORA_WGRAD_WS", 1);
+        if (ch.cw == 8 && !ch.shared && ch.gt >= 4 && ch.gt <= (ws_mode == 2 ? 6 : 4) && ch.chunks == 1 && ch.s_align16 &&
+            (N * M) % 2 == 0 && ws_mode != 0) {
+            if (!(phases & 2)) return hipSuccess;
+            if (ch.gt == 4) return launch_ws64<4>(G, S, partial, N, O, M, plan, st);
+            if (ch.gt == 5) return launch_ws64<5>(G, S, partial, N, O, M, plan, st);
+            return launch_ws64<6>(G, S, partial, N, O, M, plan, st);
+        }
         if (ch.cw != 0) {
             const void* s_operand = S;
             if (plan.tiles_packed > 0) {

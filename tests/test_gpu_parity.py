@@ -252,6 +252,10 @@ WGRAD_CASES = [
     (385, 128, 752, 16, wl.BF16),                # M = 47, N * M odd
     (40000, 128, 272, 16, wl.BF16),              # M = 17: 313 chunks, more than two per split
     (33000, 256, 1376, 32, wl.BF16),             # M = 43, ragged last chunk
+    # four group tiles: the loader-wave kernel with 64-token chunks and the features split over two waves
+    (63, 128, 1568, 32, wl.BF16), (64, 72, 2048, 32, wl.BF16), (65, 264, 2016, 32, wl.BF16),   # M = 49, 64, 63
+    (1000, 136, 416, 8, wl.BF16),                # M = 52
+    (30000, 128, 512, 8, wl.BF16),               # M = 64: many chunks per split
 ]
 
 
