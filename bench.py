@@ -327,7 +327,8 @@ def _linear_record(vl, torch, sh, v, dev, launches):
 def _mlp_block_record(torch, dev):
     """A whole LLaMA-7B-like gated MLP block (hidden 4096, intermediate 11008, 16384 tokens, bf16), forward +
     backward through autograd: the plain block against the same block with VeLoRA on its three projections
-    (paper Sec. 4: what the method costs in time and what it frees in memory).  Memory = what stays allocated
+    (paper Sec. 5.5, "Comparison with gradient checkpointing", Table 7: what the method costs in time and what
+    it frees in memory).  Memory = what stays allocated
     between the end of the forward and the start of the backward, beyond weights, input and output.
     Not part of `value`."""
     from paper_2405_17991_amd import autograd as va

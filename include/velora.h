@@ -1,8 +1,8 @@
 /*
  * libvelora -- C ABI of the MI355X (gfx950) implementation of the VeLoRA hot
  * path: rank-1 sub-token compression of a linear layer's input activations and
- * the weight gradient built on it (paper Sec. 3.2 "VeLoRA", Sec. 3.3 "Cheap
- * initialisation strategies", Algorithm 1).
+ * the weight gradient built on it (paper Sec. 3.1 "VeLoRA", Sec. 3.2 "Cheap
+ * initialisation strategies", Listing 1).
  *
  * Symbols
  *   N  tokens (batch x sequence, flattened)      D  input features
@@ -83,8 +83,8 @@ size_t velora_workspace_bytes(velora_op op, int64_t N, int64_t D, int64_t O, int
                               velora_dtype in_dt);
 
 /*
- * Initialise the projection vector (Sec. 3.3: the average of the first batch's
- * sub-tokens; Sec. 3.2: unit length):
+ * Initialise the projection vector (Sec. 3.2: the average of the first batch's
+ * sub-tokens; Sec. 3.1: unit length):
  *     m[j] = 1/(N*M) * sum_{n<N, g<M} X[n, g*d + j],      v = m / ||m||_2
  * The average runs over all tokens AND all groups: one v per layer.
  *   X   [N, D] device, dtype xdt (read only)
@@ -98,7 +98,7 @@ velora_status velora_init_v(const void* X, int64_t N, int64_t D, int64_t M, velo
 
 /*
  * Per-batch projection vector (the "running average" and instance-wise rows of
- * the initialisation ablation, Sec. 5.2 / Table 4c; the paper gives no formula,
+ * the initialisation ablation, Sec. 5.3 / Table 5c; the paper gives no formula,
  * this is the reading taken):
  *     m_b = mean of this batch's N*M sub-tokens
  *     m   = mean_state ? beta * mean_state + (1 - beta) * m_b : m_b
@@ -128,7 +128,7 @@ velora_status velora_compress_update(const void* X, const float* v_in, int64_t N
                                      float* v_out, void* ws, size_t ws_bytes, velora_stream stream);
 
 /*
- * group + compress (Sec. 3.2, Eq. 1):  S[n, g] = sum_{j<d} X[n, g*d + j] * v[j].
+ * group + compress (Sec. 3.1, Eq. 1):  S[n, g] = sum_{j<d} X[n, g*d + j] * v[j].
  *   X [N, D] device, dtype xdt (read only);  v [d] device float32 (read only)
  *   S [N, M] device, dtype xdt (written; float32 accumulate, RNE on store)
  */
@@ -137,10 +137,11 @@ velora_status velora_compress(const void* X, const float* v, int64_t N, int64_t 
 
 /*
  * The same compress, taken where X is produced.  The layer the paper compresses
- * first is the MLP down projection of an LLaMA block (Sec. 4), whose input is
- * the elementwise product X = silu(gate) * up, silu(x) = x / (1 + exp(-x)).  This
+ * first is the MLP down projection of an LLaMA block (Sec. 4, opening paragraph;
+ * Sec. 5.4 "Choice of layers"), whose input is the elementwise product
+ * X = silu(gate) * up, silu(x) = x / (1 + exp(-x)).  This
  * call writes X and, in the same pass and from the very values it stores,
- * S = compress(group(X), v) (Sec. 3.2, Eq. 1): X is never re-read for
+ * S = compress(group(X), v) (Sec. 3.1, Eq. 1): X is never re-read for
  * compression.  float32 arithmetic, one RNE rounding when X is stored; S is what
  * velora_compress returns on the stored X (bit for bit when gate, up and X are
  * 16-byte aligned and d is a multiple of 8 (bf16) or 4 (f32); otherwise X is
@@ -152,8 +153,8 @@ velora_status velora_swiglu_compress(const void* gate, const void* up, const flo
                                      int64_t M, velora_dtype dt, void* X, void* S, velora_stream stream);
 
 /*
- * The forward of the layer with the compression taken from the same pass (Sec. 3.2
- * and Algorithm 1, forward: the output is the dense product, next to it
+ * The forward of the layer with the compression taken from the same pass (Sec. 3.1
+ * and Listing 1, forward: the output is the dense product, next to it
  * compress(group(input), v) is what is kept for backward):
  *     Y[n, o] = sum_c X[n, c] * W[o, c]         (W in the nn.Linear layout [O, D])
  *     S[n, g] = sum_{j<d} X[n, g*d + j] * v[j]
@@ -172,7 +173,7 @@ velora_status velora_linear_compress(const void* X, const void* W, const float* 
                                      int64_t M, velora_dtype dt, void* Y, void* S, velora_stream stream);
 
 /*
- * The other half of the layer's backward (Algorithm 1, backward:
+ * The other half of the layer's backward (Listing 1, backward:
  * grad_input = grad_output @ weight; it needs neither the input nor S):
  *     dX[n, c] = sum_o G[n, o] * W[o, c]
  * Products of the stored inputs accumulated in float32, one RNE rounding when dX
@@ -187,10 +188,10 @@ velora_status velora_grad_input(const void* G, const void* W, int64_t N, int64_t
 
 /*
  * The other producer: the attention projections of an LLaMA block (the paper
- * compresses the value projection's input, Sec. 4) read X = RMSNorm(H),
+ * compresses the value projection's input, Sec. 4 and Sec. 5.4) read X = RMSNorm(H),
  *     X[n, j] = H[n, j] / sqrt(mean_j H[n, j]^2 + eps) * gamma[j].
  * This call writes X and, from the values it stores, S = compress(group(X), v)
- * (Sec. 3.2, Eq. 1) in one pass over H.  float32 arithmetic, one RNE rounding
+ * (Sec. 3.1, Eq. 1) in one pass over H.  float32 arithmetic, one RNE rounding
  * when X is stored; S is what velora_compress returns on the stored X (bit for
  * bit in the fused kernel: H, X, gamma 16-byte aligned, d / 8 (bf16) or d / 4
  * (f32) a power of two <= 64, D <= 8192 (bf16) or 4096 (f32); otherwise X is
@@ -204,7 +205,7 @@ velora_status velora_rmsnorm_compress(const void* H, const float* gamma, float e
                                       velora_stream stream);
 
 /*
- * reconstruct + ungroup (Sec. 3.2, second equation):  Xhat[n, g*d + j] = S[n, g] * v[j].
+ * reconstruct + ungroup (Sec. 3.1, Eq. 2):  Xhat[n, g*d + j] = S[n, g] * v[j].
  * The materialising form; velora_weight_grad never needs it.
  *   S [N, M] device, dtype dt (read only);  v [d] device float32 (read only)
  *   Xhat [N, D] device, dtype dt (written)
@@ -213,7 +214,7 @@ velora_status velora_reconstruct(const void* S, const float* v, int64_t N, int64
                                  velora_dtype dt, void* Xhat, velora_stream stream);
 
 /*
- * Weight gradient from the compressed activations (Algorithm 1, backward:
+ * Weight gradient from the compressed activations (Listing 1, backward:
  * input_hat = ungroup(reconstruct(z, v)); grad_weight = grad_output^T @ input_hat):
  *     dW[o, g*d + j] (+)= sum_{n<N} G[n, o] * S[n, g] * v[j]
  * evaluated as T = G^T S followed by the expansion with v, which is the same
@@ -261,7 +262,7 @@ velora_status velora_weight_grad_static(const void* G, const void* S, const floa
 
 /*
  * The factored hand-off of the same gradient.  Since the reconstruction of
- * Sec. 3.2 is Xhat[n, g*d+j] = S[n,g]*v[j], Algorithm 1's grad_weight equals
+ * Sec. 3.1 is Xhat[n, g*d+j] = S[n,g]*v[j], Listing 1's grad_weight equals
  * T (x) v with T[o, g] = sum_n G[n, o] * S[n, g]: d times smaller than dW.  A
  * caller that reduces gradients across devices or applies the update itself
  * can take T and expand later (or never materialise dW).
@@ -284,8 +285,8 @@ velora_status velora_expand_factor(const float* T, const float* v, int64_t O, in
 
 /*
  * AdamW step taken straight from the factored gradient (the paper's training
- * set-ups, Sec. 4, use AdamW; the gradient is Algorithm 1's grad_weight in the
- * factored form above).  With g[o, g*d + j] = grad_scale * T[o, g] * v[j], in
+ * set-ups, Sec. 4.1 "Implementation details", use AdamW; the gradient is
+ * Listing 1's grad_weight in the factored form above).  With g[o, g*d + j] = grad_scale * T[o, g] * v[j], in
  * place and in float32:
  *     W <- W * (1 - lr * weight_decay)
  *     exp_avg    <- beta1 * exp_avg    + (1 - beta1) * g

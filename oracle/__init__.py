@@ -1,7 +1,7 @@
 """CPU oracle for the VeLoRA hot path -- TEST INFRASTRUCTURE ONLY.
 
 Thin ctypes loader around ``velora_oracle.cpp`` (plain C++17, double
-precision, written from the paper's Sec. 3.2/3.3 definitions and Algorithm 1).
+precision, written from the paper's Sec. 3.1/3.2 definitions and Listing 1).
 Only the tests, the smoke check and the benchmark's ``cpu_baseline`` leg may
 import this package; the product package never does.
 
@@ -234,8 +234,8 @@ def _store(x: np.ndarray, dt: int) -> np.ndarray:
 
 def linear_compress(X: np.ndarray, W: np.ndarray, v: np.ndarray, M: int,
                     threads: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
-    """Algorithm 1's forward as one call: the dense product Y = X @ W^T (W stored
-    [O, D]; "forward compute is preserved") and, next to it, Sec. 3.2's compress of
+    """Listing 1's forward as one call: the dense product Y = X @ W^T (W stored
+    [O, D]; the listing leaves the dense product as it is) and, next to it, Sec. 3.1's compress of
     the same X, which is what the layer keeps for backward.  Both from their
     definitions in float64, then stored in the inputs' dtype.
     -> (Y_exact float64[N, O], Y_store storage[N, O], S_exact float64[N, M], S_store storage[N, M])
@@ -246,7 +246,7 @@ def linear_compress(X: np.ndarray, W: np.ndarray, v: np.ndarray, M: int,
 
 
 def grad_input(G: np.ndarray, W: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
-    """Algorithm 1, backward: grad_input = grad_output @ weight, dX[n, c] = sum_o G[n, o] * W[o, c]
+    """Listing 1, backward: grad_input = grad_output @ weight, dX[n, c] = sum_o G[n, o] * W[o, c]
     with W stored [O, D]; float64 (numpy's matmul on the widened inputs), then stored in the inputs' dtype.
     -> (dX_exact float64[N, D], dX_store storage[N, D])"""
     G, W = _c(G), _c(W)
@@ -263,9 +263,9 @@ def grad_input(G: np.ndarray, W: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
 def adamw_step_factor(T: np.ndarray, v: np.ndarray, W: np.ndarray, exp_avg: np.ndarray, exp_avg_sq: np.ndarray,
                       lr: float, beta1: float, beta2: float, eps: float, weight_decay: float, step: int,
                       grad_scale: float = 1.0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """One AdamW step (the optimiser of the paper's training set-ups, Sec. 4;
+    """One AdamW step (the optimiser of the paper's training set-ups, Sec. 4.1;
     decoupled weight decay, bias-corrected moments) on a weight whose gradient is
-    given in the factored form of Sec. 3.2's reconstruction,
+    given in the factored form of Sec. 3.1's reconstruction,
     dW[o, g*d + j] = grad_scale * T[o, g] * v[j].  Everything in float64:
 
         W   <- W * (1 - lr * weight_decay)
@@ -298,7 +298,7 @@ def swiglu_compress(gate: np.ndarray, up: np.ndarray, v: np.ndarray, M: int,
                     threads: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
     """The input of an LLaMA-style down projection, produced and compressed in one
     go: X = silu(gate) * up with silu(x) = x / (1 + exp(-x)) (float64), stored in the
-    inputs' dtype (one round-to-nearest-even for bfloat16); then Sec. 3.2's
+    inputs' dtype (one round-to-nearest-even for bfloat16); then Sec. 3.1's
     compress applied to the STORED X, exactly as `compress` would be applied to it
     afterwards.  gate, up: [N, D] storage arrays of one dtype.
     -> (X_exact float64[N, D], X_store storage[N, D], S_exact float64[N, M], S_store storage[N, M])
@@ -326,7 +326,7 @@ def rmsnorm_compress(H: np.ndarray, gamma: np.ndarray, eps: float, v: np.ndarray
                      threads: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
     """The input of an LLaMA-style attention projection, produced and compressed in
     one go: X[n, :] = H[n, :] / sqrt(mean_j H[n, j]^2 + eps) * gamma (float64),
-    stored in H's dtype (one round-to-nearest-even for bfloat16); then Sec. 3.2's
+    stored in H's dtype (one round-to-nearest-even for bfloat16); then Sec. 3.1's
     compress applied to the STORED X.  H: [N, D] storage array; gamma: float32 [D].
     -> (X_exact float64[N, D], X_store storage[N, D], S_exact float64[N, M], S_store storage[N, M])
     """

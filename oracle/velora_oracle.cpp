@@ -6,19 +6,18 @@
 // product path never calls it and shares no code, header, table or helper
 // with it.  It is written from the paper's definitions:
 //
-//   group / ungroup   : Sec. 3.2 ("VeLoRA"), Eq. 1 and the un-numbered
-//                       reconstruction equation below it (a reshape that
+//   group / ungroup   : Sec. 3.1 ("VeLoRA"), Eq. 1 and Eq. 2 (a reshape that
 //                       splits every token of depth D into D/d contiguous,
 //                       non-overlapping sub-tokens of size d);
-//   compress(z; v)    : Sec. 3.2, z_p = z . v  (one scalar per sub-token);
-//   reconstruct(z_p;v): Sec. 3.2, z_hat = z_p . v^T;
-//   proj_v            : Sec. 3.2, (z . v) . v^T with v a fixed unit vector;
-//   init of v         : Sec. 3.3 "Cheap initialisation strategies" (average
-//                       of the first batch's sub-tokens) + unit length (3.2);
-//   per-batch v       : Sec. 5.2 "Initialisation strategy" / Table 4c (running
+//   compress(z; v)    : Sec. 3.1, z_p = z . v  (one scalar per sub-token);
+//   reconstruct(z_p;v): Sec. 3.1, z_hat = z_p . v^T;
+//   proj_v            : Sec. 3.1, (z . v) . v^T with v a fixed unit vector;
+//   init of v         : Sec. 3.2 "Cheap initialisation strategies" (average
+//                       of the first batch's sub-tokens) + unit length (Sec. 3.1);
+//   per-batch v       : Sec. 5.3 "Initialisation strategy" / Table 5c (running
 //                       average, instance-wise); no formula is printed, the
 //                       reading is stated at the function;
-//   grad_weight       : Algorithm 1 (backward): grad_output^T @ input_hat.
+//   grad_weight       : Listing 1 (backward): grad_output^T @ input_hat.
 //
 // Naming: the paper writes M for the sub-token size.  Here d is the sub-token
 // size and M = D/d the number of sub-tokens per token.
@@ -108,7 +107,7 @@ extern "C" {
 uint16_t velora_oracle_round_bf16(double x) { return round_to_bf16(x); }
 double velora_oracle_widen_bf16(uint16_t b) { return widen_bf16(b); }
 
-// Sec. 3.3: v = average of all N*M sub-tokens of the first batch; Sec. 3.2:
+// Sec. 3.2: v = average of all N*M sub-tokens of the first batch; Sec. 3.1:
 // unit length.  mean_out (may be null) receives the un-normalised average.
 // Returns 0, or 6 when the average is zero or not finite, in which case
 // v[j] = 1/sqrt(d) (the paper is silent on this case).
@@ -143,7 +142,7 @@ int velora_oracle_init_v(const void* X, int dt, int64_t N, int64_t D, int64_t M,
 }
 
 // Per-batch vector (the "running average" / instance-wise rows of the
-// initialisation ablation, Sec. 5.2, Table 4c).  The paper prints no formula;
+// initialisation ablation, Sec. 5.3, Table 5c).  The paper prints no formula;
 // the reading taken: m_b = this batch's sub-token average (as in init_v),
 // m = beta * state_in + (1 - beta) * m_b when a state is given, else m = m_b;
 // state_out = m rounded to float32; v = m / ||m|| (from the unrounded m).
@@ -172,7 +171,7 @@ int velora_oracle_update_v(const void* X, int dt, int64_t N, int64_t D, int64_t 
     return 0;
 }
 
-// Sec. 3.2: S[n, g] = sum_j X[n, g*d + j] * v[j].
+// Sec. 3.1: S[n, g] = sum_j X[n, g*d + j] * v[j].
 // S_exact (double, may be null) and S_store (storage dtype, may be null).
 void velora_oracle_compress(const void* X, int dt, const float* v, int64_t N, int64_t D, int64_t M,
                             double* S_exact, void* S_store, int nthreads) {
@@ -189,7 +188,7 @@ void velora_oracle_compress(const void* X, int dt, const float* v, int64_t N, in
     });
 }
 
-// Sec. 3.2: Xhat[n, g*d + j] = S[n, g] * v[j]  (reconstruct, then ungroup).
+// Sec. 3.1: Xhat[n, g*d + j] = S[n, g] * v[j]  (reconstruct, then ungroup).
 void velora_oracle_reconstruct(const void* S, int dt, const float* v, int64_t N, int64_t D, int64_t M,
                                double* Xhat, int nthreads) {
     const int64_t d = D / M;
@@ -203,7 +202,7 @@ void velora_oracle_reconstruct(const void* S, int dt, const float* v, int64_t N,
     });
 }
 
-// Algorithm 1, backward: materialise Xhat, then dW[o, c] = sum_n G[n, o] * Xhat[n, c].
+// Listing 1, backward: materialise Xhat, then dW[o, c] = sum_n G[n, o] * Xhat[n, c].
 void velora_oracle_weight_grad_bruteforce(const void* G, const void* S, const float* v,
                                           int64_t N, int64_t O, int64_t D, int64_t M, int dt,
                                           double* dW, int nthreads) {
@@ -272,7 +271,7 @@ void velora_oracle_weight_grad_factored(const void* G, const void* S, const floa
     });
 }
 
-// Algorithm 1, forward ("forward compute is preserved"): Y[n, o] = sum_c X[n, c] * W[o, c],
+// Listing 1, forward (the dense product is left as it is): Y[n, o] = sum_c X[n, c] * W[o, c],
 // with the weight stored [O, D] as the shape of grad_weight implies.
 void velora_oracle_linear(const void* X, const void* W, int dt, int64_t N, int64_t D, int64_t O,
                           double* Y, int nthreads) {

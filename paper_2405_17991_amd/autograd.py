@@ -1,17 +1,17 @@
 """A linear layer that trains with VeLoRA's compressed activations (paper
-Algorithm 1), wired into PyTorch autograd.
+Listing 1), wired into PyTorch autograd.
 
 Forward: the dense product is untouched (``out = input @ weight.T`` through the
-vendor GEMM, "forward compute is preserved"); next to it the library's compress
+vendor GEMM: the listing leaves the dense product as it is); next to it the library's compress
 kernel produces ``S[N, M]`` and *that* is what autograd keeps instead of the
 input.  Backward: ``grad_input = grad_output @ weight`` (vendor GEMM, does not
 need the input) and ``grad_weight`` from ``velora_weight_grad`` on
 ``(grad_output, S, v)``; the reconstructed input is never formed.  ``v`` is set
-from the first batch (Sec. 3.3) and then frozen.
+from the first batch (Sec. 3.2) and then frozen.
 
 Only the two VeLoRA steps run in this package's kernels; the two dense GEMMs
 are not part of the method and use ``torch.matmul``.  The saved activation
-shrinks from ``N*D`` to ``N*M = N*D/d`` elements (Sec. 3.2).
+shrinks from ``N*D`` to ``N*M = N*D/d`` elements (Sec. 3.1).
 
 ``VeLoRALlamaMLP`` applies the same rule to a whole gated MLP block: the block
 input is compressed once for the gate and up projections, and the down
@@ -159,7 +159,7 @@ def saved_activation_bytes(N: int, D: int, d: int, elem_bytes: int = 2) -> dict:
 class _SharedInputLinearsFunction(torch.autograd.Function):
     """Two bias-free linears on the same input (an MLP's gate and up projections):
     the input is compressed ONCE and both weight gradients are formed from the
-    same S (Algorithm 1 applied to each layer; the saved tensor is shared)."""
+    same S (Listing 1 applied to each layer; the saved tensor is shared)."""
 
     @staticmethod
     def forward(ctx, input, w_a, w_b, v, M):
@@ -245,7 +245,7 @@ class VeLoRALlamaMLP(_FirstBatchV):
 
     @torch.no_grad()
     def init_v(self, h: torch.Tensor) -> None:
-        """Both vectors from the first batch (Sec. 3.3): v_h from h, v_f from the first silu(gate)*up."""
+        """Both vectors from the first batch (Sec. 3.2): v_h from h, v_f from the first silu(gate)*up."""
         h2 = h.reshape(-1, self.hidden).contiguous()
         x = torch.nn.functional.silu(torch.matmul(h2, self.w_gate.t())) * torch.matmul(h2, self.w_up.t())
         self._init_vectors([(h2, self.M_h, self.v_h), (x.contiguous(), self.M_f, self.v_f)])

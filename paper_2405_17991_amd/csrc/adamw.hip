@@ -1,8 +1,8 @@
 // AdamW step fed by the factored weight gradient.
 //
-// Sec. 3.2's reconstruction makes Algorithm 1's grad_weight a rank-structured
+// Sec. 3.1's reconstruction makes Listing 1's grad_weight a rank-structured
 // array, dW[o, g*d + j] = T[o, g] * v[j], and the paper's training set-ups
-// (Sec. 4) hand it to AdamW.  This kernel forms each gradient element in
+// (Sec. 4.1, "Implementation details") hand it to AdamW.  This kernel forms each gradient element in
 // registers from T and v and applies the optimiser update in the same pass, so
 // the [O, D] gradient is never written to or read back from HBM: per element it
 // moves the weight and the two moments in and out and nothing else.

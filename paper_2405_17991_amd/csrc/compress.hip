@@ -1,4 +1,4 @@
-// group + compress, and reconstruct + ungroup (paper Sec. 3.2).
+// group + compress, and reconstruct + ungroup (paper Sec. 3.1).
 //
 // X[N, D] is row-major and d divides D, so "split every token into M = D/d
 // sub-tokens" is nothing but reading the flat array in runs of d elements:
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void compress_generic_kernel(const typename E:
 }
 
 // ---------------------------------------------------------------------------
-// reconstruct + ungroup (Sec. 3.2): Xhat[k*d + j] = S[k] * v[j].  Write-bound.
+// reconstruct + ungroup (Sec. 3.1): Xhat[k*d + j] = S[k] * v[j].  Write-bound.
 // The grid's thread count is a multiple of the 16-byte vectors per sub-token
 // (vps, host-checked), so a thread keeps the same position j inside the
 // sub-token for the whole grid-stride loop: its slice of v lives in registers

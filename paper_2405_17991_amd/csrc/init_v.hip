@@ -1,6 +1,6 @@
-// Initialisation of the projection vector (paper Sec. 3.3, "Cheap
+// Initialisation of the projection vector (paper Sec. 3.2, "Cheap
 // initialisation strategies": the average of the first batch's sub-tokens;
-// Sec. 3.2: v has unit length):
+// Sec. 3.1: v has unit length):
 //     m[j] = 1/(N*M) * sum_k X[k*d + j],   v = m / ||m||_2
 // i.e. the column mean of the flat [N*M, d] view of X.  One streaming pass over
 // X (HBM-bound) produces per-block float32 partial column sums; they are

@@ -1,6 +1,6 @@
 // Forward linear layer with the compression taken from the same tiles (paper
-// Algorithm 1, forward: out = input @ weight^T next to compress(group(input), v)
-// of Sec. 3.2).  Y[N, O] = X[N, D] * W[O, D]^T as a bf16 MFMA GEMM whose LDS
+// Listing 1, forward: out = input @ weight^T next to compress(group(input), v)
+// of Sec. 3.1).  Y[N, O] = X[N, D] * W[O, D]^T as a bf16 MFMA GEMM whose LDS
 // tiles of X also feed the dot with v, so X is read from HBM once for both.
 //
 // GEMM.  Block tile 256 tokens x 256 outputs x 64 k, four waves in a 2 x 2 grid

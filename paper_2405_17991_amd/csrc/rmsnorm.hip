@@ -2,7 +2,7 @@
 // paper compresses the value projection's input, Sec. 4): that input is
 // X = RMSNorm(H) = H / sqrt(mean(H^2) + eps) * gamma, a row-wise kernel that has
 // to stream H in and X out anyway.  This one also forms, from the values it
-// stores, S = compress(group(X), v) of Sec. 3.2, so X is never re-read for
+// stores, S = compress(group(X), v) of Sec. 3.1, so X is never re-read for
 // compression.  S uses the lane layout and summation order of
 // compress_vec_kernel and equals velora_compress(X, v) bit for bit.
 #include "common.h"

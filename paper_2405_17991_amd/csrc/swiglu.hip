@@ -2,8 +2,8 @@
 // projection of an LLaMA block (Sec. 4): its input X = silu(gate) * up is an
 // elementwise product that some kernel has to stream out anyway, so this one
 // writes X and, from the very values it stores, the compressed activations
-// S = compress(group(X), v) of Sec. 3.2 in the same pass.  X is then never
-// re-read for compression: the extra pass of Algorithm 1's forward disappears.
+// S = compress(group(X), v) of Sec. 3.1 in the same pass.  X is then never
+// re-read for compression: the extra pass of Listing 1's forward disappears.
 //
 // S is computed from the stored (rounded) X with the lane layout and summation
 // order of compress_vec_kernel, so it equals velora_compress(X, v) bit for bit.

@@ -1,8 +1,8 @@
-// Weight gradient from compressed activations (paper Algorithm 1, backward:
+// Weight gradient from compressed activations (paper Listing 1, backward:
 // grad_weight = grad_output^T @ ungroup(reconstruct(z, v))).
 //
 // Because the reconstructed input is Xhat[n, g*d + j] = S[n, g] * v[j]
-// (Sec. 3.2), the gradient factors exactly:
+// (Sec. 3.1), the gradient factors exactly:
 //     T[o, g]        = sum_n G[n, o] * S[n, g]            (a skinny GEMM, K = N)
 //     dW[o, g*d + j] = T[o, g] * v[j]                     (an expansion)
 // which needs d times fewer flops than the dense product and never forms Xhat.

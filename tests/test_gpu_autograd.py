@@ -1,4 +1,4 @@
-"""The autograd wrapper around the two VeLoRA kernels (paper Algorithm 1): the
+"""The autograd wrapper around the two VeLoRA kernels (paper Listing 1): the
 forward output is the dense product, the weight gradient is the one built from
 compressed activations, and what autograd keeps for backward shrinks by d."""
 import numpy as np
@@ -34,7 +34,7 @@ def test_layer_forward_backward(mods, dtype, B, T, D, O, d):
     out = layer(x)
     assert out.shape == (B, T, O) and bool(layer.v_ready)
     ref = torch.nn.functional.linear(x.detach(), layer.weight.detach())
-    assert torch.equal(out.detach(), ref)                                      # forward compute is preserved
+    assert torch.equal(out.detach(), ref)                                      # the dense forward is untouched
     g = to_dev(Gh, sdt).reshape(B, T, O)
     out.backward(g)
     # v: the normalised mean of the first batch's sub-tokens

@@ -1,5 +1,5 @@
 """The layer's forward with the compression taken from the same pass
-(velora_linear_compress: paper Algorithm 1, forward, and Sec. 3.2) against the
+(velora_linear_compress: paper Listing 1, forward, and Sec. 3.1) against the
 CPU oracle: Y = X @ W^T and S = compress(X, v), element by element."""
 import numpy as np
 import pytest

@@ -1,10 +1,10 @@
 """Pins for the CPU oracle: everything here runs without a GPU.
 
 The oracle (oracle/velora_oracle.cpp) is checked against things other than
-itself: a hand-worked example (tests/golden/worked_example_sec3_2.txt), closed
-forms, projector invariants that follow from |v| = 1 (paper Sec. 3.2), the
+itself: a hand-worked example (tests/golden/worked_example_sec3_1.txt), closed
+forms, projector invariants that follow from |v| = 1 (paper Sec. 3.1), the
 gradient-similarity identity of the appendix ("Gradient Similarity"), the
-no-sub-token special case of Sec. 3.3 ("Connection to parameter efficient
+no-sub-token special case of Sec. 3.2 ("Connection to parameter efficient
 fine-tuning"), special cases that reduce to a gather or to a textbook matrix
 product, and pure-Python brute force on tiny inputs.
 """
@@ -17,7 +17,7 @@ import pytest
 import oracle
 import workloads as wl
 
-GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_example_sec3_2.txt")
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_example_sec3_1.txt")
 
 
 def _read_golden():
@@ -384,7 +384,7 @@ class TestWeightGrad:
                 assert (dW[mask] == 0).all()
 
     def test_no_subtoken_case_is_rank_one(self):
-        # Sec. 3.3 "Connection to parameter efficient fine-tuning": with d = D the
+        # Sec. 3.2 "Connection to parameter efficient fine-tuning": with d = D the
         # gradient is (G^T X v) v^T.
         N, O, D = 12, 5, 16
         X = _rand((N, D), 77)
@@ -455,7 +455,7 @@ class TestLinear:
 
 
 class TestLinearCompress:
-    """Algorithm 1's forward as one call: pinned to the library matmul, to a triple loop on a tiny case,
+    """Listing 1's forward as one call: pinned to the library matmul, to a triple loop on a tiny case,
     and to the already pinned compress."""
 
     def test_triple_loop_and_library(self):
@@ -536,7 +536,7 @@ class TestAdamWFactor:
         W, m, u = W0, np.zeros_like(W0), np.zeros_like(W0)
         for step in range(1, 6):
             T = T0 * (1.0 + 0.3 * step) * (-1.0) ** step
-            # the library is fed the gradient in its plain definition (Algorithm 1 backward)
+            # the library is fed the gradient in its plain definition (Listing 1 backward)
             G = np.zeros_like(W0)
             for o in range(T.shape[0]):
                 for g in range(T.shape[1]):

@@ -137,7 +137,7 @@ def all_shapes() -> List[Shape]:
     # exercised on the down projection.
     s.append(_mk("cfg5_down_d512", 5, BF16, n5, 13824, 5120, 512, "outlier_chan", 0.005, tid))
     # Beyond the five configurations: the paper's own setting for LLaMA-7B, 32 sub-tokens
-    # per token ("M = D/32", Sec. 5.2 and its sub-token-size ablation), on configuration 4's layers.
+    # per token ("M = D/32", Sec. 5.2 "Sub-token size", Table 5b), on configuration 4's layers.
     s.append(_mk("paper7b_attn_m32", 6, BF16, n4, 4096, 4096, 128, "student_t4", 0.005, 0))
     s.append(_mk("paper7b_up_m32", 6, BF16, n4, 4096, 11008, 128, "student_t4", 0.005, 1))
     s.append(_mk("paper7b_down_m32", 6, BF16, n4, 11008, 4096, 344, "student_t4", 0.005, 2))
