@@ -16,6 +16,7 @@
 #include "kernels.h"
 
 #include <atomic>
+#include <type_traits>
 #ifdef VELORA_TUNING
 #include <cstdlib>
 #endif
@@ -1080,89 +1081,175 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
 }
 
 // ---------------------------------------------------------------------------
-// Kernel 2, flat form: dW[o, g*d + j] (+)= T[o, g] * v[j] from an already summed T (row stride
-// t_stride), as ONE sweep of the whole grid over dW: 16-byte vector i of the array belongs to thread
-// i mod (grid * 256), so that at any moment all compute units write one contiguous window of a
-// megabyte.  HBM takes that at 6.3 TB/s on this chip; the same bytes written as one private row per
-// block reach 5.5-5.7 TB/s, and more than two blocks per compute unit 4.9 TB/s (plain fill kernels on
-// the 4096 x 11008 float32 array).  Hence one block per compute unit and eight stores in flight per
-// thread.  The loads of T and v for the NEXT eight stores are issued before this trip's stores: a
-// trip that waits for its own loads leaves the store stream idle meanwhile (31.0 us against 29.7 us
-// on that array; the fill alone takes 28.6 us).  The (row, group, position) of a vector is kept up to
-// date by additions instead of divisions.  VW elements per vector: 4 (float32, and bf16 with 8-byte
-// stores) or 8 (bf16, needs d % 8 == 0).  Needs d % VW == 0, 16-byte aligned v, dW aligned to its
-// store, and fewer than 2^31 - 2^24 vectors.
+// Kernel 2, window sweep: dW as ONE sweep of the whole grid, straight from the split partials.
+// 16-byte vector i of dW belongs to thread i mod (grid * 256), so that at any moment all compute
+// units write one contiguous window of grid * 4 KB.  HBM takes that order at 6.2-6.3 TB/s on this
+// chip; the same bytes written as one private row (or 32 KB piece) per block reach 5.5-5.7 TB/s and
+// more than two blocks per compute unit 4.9 TB/s (plain fill kernels on the 4096 x 11008 float32
+// array).  Hence one block per compute unit and eight stores in flight per thread.
+// A group's 16-byte vectors are consecutive (D = M * d), so vector i needs T at flat index i / dv,
+// and the 256 vectors of a block in one window touch at most 256 / dv + 2 consecutive entries of
+// it.  For the U windows of the NEXT trip the block's first U * NL threads each load one entry's
+// partials (all splits, summed in split order) ahead of the stores, and put the sums into the
+// other half of a small LDS table afterwards; the stores read T and v from LDS, so the only
+// vector-memory instructions between them are those few loads.  One bare barrier per trip (a fence
+// would wait for the stores).  Needs dv >= 16, d <= 2048, at most 8 * NS8 splits, partials
+// below 2 GiB and fewer than 2^31 - 2^24 vectors.
 // ---------------------------------------------------------------------------
-template <bool OUT_BF16, int VW>
-__global__ __launch_bounds__(256) void wgrad_expand_flat_kernel(const float* __restrict__ T, int64_t t_stride,
-                                                               const float* __restrict__ v, void* __restrict__ dW,
-                                                               uint32_t n_vec, uint32_t Dv, uint32_t dv, uint32_t M,
-                                                               int accumulate) {
-    constexpr int U = 8;
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+constexpr int kSweepU = 8;
+constexpr int kSweepNL = 18;
+
+template <bool OUT_BF16, int VW, int NS8, bool ACC>
+__global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __restrict__ partial,
+                                                                uint32_t split_stride_b, uint32_t part_bytes,
+                                                                const float* __restrict__ v, void* __restrict__ dW,
+                                                                uint32_t n_vec, uint32_t dv, uint32_t dv_inv,
+                                                                uint32_t M, uint32_t Mp, uint32_t n_groups) {
+    constexpr int U = kSweepU, NL = kSweepNL, NS = 8 * NS8;
+    constexpr uint32_t VB = OUT_BF16 ? 2u * VW : 16u;       // bytes of one vector of dW
+    __shared__ float Tt[2][U * NL + 1];                     // [half][window * nl + entry]; the last slot is a dump
+    __shared__ __attribute__((aligned(16))) float vs[2048];
     const uint32_t stride = gridDim.x * 256u;
-    // position of this thread's next vector: row o, vector c of the row = group g, vector j of the sub-token
-    uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    uint32_t o = i / Dv, c = i - o * Dv, g = c / dv, j = c - g * dv;
-    // one step of `stride` vectors in the same coordinates
-    const uint32_t so = stride / Dv, sc = stride - so * Dv, sg = sc / dv, sj = sc - sg * dv;
-    float t[U];
-    f32x4 va[U], vb[U];
-    uint32_t idx[U];
-    auto fetch = [&]() {
+    const uint32_t t = threadIdx.x;
+    for (uint32_t k = t; k < dv * VW; k += 256u) vs[k] = v[k];
+
+    // Everything below is straight-line code inside one loop whose only branches are uniform: with
+    // divergent branches around the loads and stores the compiler's wait-count bookkeeping falls back
+    // to "wait for everything", which drains the store stream once per trip (35 against 31 us).
+    // Threads without a table entry load from past the end of the descriptor (zeros, no memory
+    // request) and write their sum to the dump slot; stores past the end of dW are dropped by the
+    // range check of a descriptor that is rebuilt for every trip.
+    const uint32_t nl = 255u / dv + 2u;                     // table entries one window of a block can touch
+    const bool fetcher = t < static_cast<uint32_t>(U) * nl;
+    const uint32_t fu = t / nl, fk = t - fu * nl;
+    const uint32_t slot = fetcher ? t : static_cast<uint32_t>(U * NL);
+    // The partial loads and the waits for them are written out (inline assembly): the compiler's
+    // wait-count pass merges the loop's first and later iterations and then waits for the previous
+    // trip's stores as well (vmcnt(13) where 24 operations may stay in flight).  Loads and stores
+    // share one in-order counter on this chip, so "at most n younger operations outstanding" is the
+    // exact condition; operations the compiler does not know of only make its own waits stricter.
+    const uint64_t pa64 = reinterpret_cast<uint64_t>(partial);
+    const i32x4 pr_words = {static_cast<int>(pa64 & 0xFFFFFFFFu), static_cast<int>((pa64 >> 32) & 0xFFFFu),
+                            static_cast<int>(part_bytes), 0x00020000};   // base, stride 0, bytes, raw 32-bit data
+    auto fetch = [&](float (&px)[NS], uint32_t trip_base) {   // trip_base: the block's first vector in window 0 of that trip
+        const uint32_t b = trip_base + fu * stride;             // the block's first vector in window fu
+        const uint32_t L = b / dv + fk;
+        const bool ok = fetcher && b < n_vec && L < n_groups;
+        const uint32_t o = L / M, g = L - o * M;
+        const uint32_t off = ok ? (o * Mp + g) * 4u : 0x80000000u;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            asm volatile("buffer_load_dword %0, %1, %2, 0 offen"
+                         : "=v"(px[s])
+                         : "v"(off + s * split_stride_b), "s"(pr_words)
+                         : "memory");
+    };
+    // wait until at most `younger` vector-memory operations issued after px's loads are outstanding
+    auto landed = [&](float (&px)[NS], auto younger) {
+        constexpr int n = decltype(younger)::value;
+        static_assert(n >= 0 && n <= 63, "vmcnt has six bits");
+#pragma unroll
+        for (int s0 = 0; s0 < NS; s0 += 8)
+            asm volatile("s_waitcnt vmcnt(%8)"
+                         : "+v"(px[s0]), "+v"(px[s0 + 1]), "+v"(px[s0 + 2]), "+v"(px[s0 + 3]), "+v"(px[s0 + 4]),
+                           "+v"(px[s0 + 5]), "+v"(px[s0 + 6]), "+v"(px[s0 + 7])
+                         : "n"(n)
+                         : "memory");
+    };
+    auto publish = [&](const float (&px)[NS], int half) {
+        float sum = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) sum += px[s];
+        Tt[half][slot] = sum;
+    };
+    auto lds_barrier = [&]() {
+        __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): LDS writes done; vector memory is not waited for
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    // Which 256-vector piece of a window the block takes.  Blocks are dealt to the eight XCDs round-robin,
+    // and each XCD has its own L2: with piece = block id every XCD would fetch every line of the partials
+    // (8 x 5.8 MB on the 4096 x 11008 layer with 8 splits); with the pieces of one XCD next to each other
+    // it fetches an eighth of them.  The order in which the chip as a whole writes dW does not change.
+    const uint32_t piece = (gridDim.x & 7u) == 0u ? (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    uint32_t jb = (piece * 256u) % dv;          // position of the block's first vector of the window inside its group
+    const uint32_t sr = stride % dv;
+    auto store_trip = [&](uint32_t base, int half) {
+        // the trip's U windows seen from the block's first vector of window 0: at most U * stride vectors
+        const uint32_t left = n_vec - base;                       // base < n_vec here
+        const uint32_t span = left < U * stride ? left : U * stride;
+        const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
+            static_cast<unsigned char*>(dW) + static_cast<size_t>(base) * VB, 0, span * VB, 0x00020000);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            idx[u] = i;
-            const bool ok = i < n_vec;
-            t[u] = ok ? T[static_cast<int64_t>(o) * t_stride + g] : 0.f;
-            const float* vp = v + static_cast<size_t>(ok ? j : 0u) * VW;
-            va[u] = *reinterpret_cast<const f32x4*>(vp);
-            if constexpr (VW == 8) vb[u] = *reinterpret_cast<const f32x4*>(vp + 4);
-            // advance by one stride: vectors of the sub-token, groups, vectors of the row, rows
-            i += stride;
-            o += so; c += sc; g += sg; j += sj;
-            if (j >= dv) { j -= dv; ++g; }
-            if (c >= Dv) { c -= Dv; g -= M; ++o; }
+            const uint32_t off = (u * stride + t) * VB;           // past `span` vectors: dropped (loads: zero)
+            const uint32_t x = jb + t;
+            const uint32_t k = __umulhi(x, dv_inv);               // x / dv (x < dv + 256)
+            const uint32_t j = x - k * dv;
+            jb += sr;
+            if (jb >= dv) jb -= dv;
+            const float tg = Tt[half][u * nl + k];
+            const f32x4 va = *reinterpret_cast<const f32x4*>(vs + j * VW);
+            if constexpr (!OUT_BF16) {
+                f32x4 r = {tg * va.x, tg * va.y, tg * va.z, tg * va.w};
+                if constexpr (ACC) r += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0));
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, r), wr, off, 0, kStreamAux);
+            } else if constexpr (VW == 8) {
+                const f32x4 vb = *reinterpret_cast<const f32x4*>(vs + j * VW + 4);
+                float r[8] = {tg * va.x, tg * va.y, tg * va.z, tg * va.w, tg * vb.x, tg * vb.y, tg * vb.z, tg * vb.w};
+                if constexpr (ACC) {
+                    const u32x4 old = __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0);
+                    r[0] += bf16_lo(old.x); r[1] += bf16_hi(old.x); r[2] += bf16_lo(old.y); r[3] += bf16_hi(old.y);
+                    r[4] += bf16_lo(old.z); r[5] += bf16_hi(old.z); r[6] += bf16_lo(old.w); r[7] += bf16_hi(old.w);
+                }
+                __builtin_amdgcn_raw_buffer_store_b128(u32x4{pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]),
+                                                             pack_bf16x2(r[4], r[5]), pack_bf16x2(r[6], r[7])},
+                                                       wr, off, 0, kStreamAux);
+            } else {
+                float r[4] = {tg * va.x, tg * va.y, tg * va.z, tg * va.w};
+                if constexpr (ACC) {
+                    const u32x2 old = __builtin_amdgcn_raw_buffer_load_b64(wr, off, 0, 0);
+                    r[0] += bf16_lo(old.x); r[1] += bf16_hi(old.x); r[2] += bf16_lo(old.y); r[3] += bf16_hi(old.y);
+                }
+                __builtin_amdgcn_raw_buffer_store_b64(u32x2{pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3])}, wr, off, 0,
+                                                      kStreamAux);
+            }
         }
     };
-    fetch();
-    while (idx[0] < n_vec) {
-        float r[U][VW];
-        uint32_t id[U];
+
+    // Loads run R trips ahead of the stores that use them, so that the wait in front of publish() is
+    // for loads that have had R - 1 whole trips of stores to come back; p[r] are the landing
+    // registers of trips r, r + R, ...  Behind the loads of trip k + 1 when they are waited for:
+    // in the steady state (R - 1) later fetches and R trips of stores (and of loads of the old
+    // values when accumulating); for the first trips, whose fetches were issued back to back, one
+    // trip of stores at least.  The smaller count serves for both (it only asks that stores three
+    // trips old have completed as well).
+    constexpr int R = NS8 == 1 ? 4 : 2;
+    constexpr int kPerTrip = ACC ? 2 * U : U;
+    using Wait0 = std::integral_constant<int, 0>;
+    using WaitN = std::integral_constant<int, (R - 1) * NS + kPerTrip>;
+    const uint32_t tstep = U * stride;
+    uint32_t base = piece * 256u;               // the block's first vector in window 0 of the current trip
+    float p[R][NS];
+    fetch(p[0], base);
+    landed(p[0], Wait0{});
+    publish(p[0], 0);
+    lds_barrier();
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            id[u] = idx[u];
-            r[u][0] = t[u] * va[u].x; r[u][1] = t[u] * va[u].y; r[u][2] = t[u] * va[u].z; r[u][3] = t[u] * va[u].w;
-            if constexpr (VW == 8) {
-                r[u][4] = t[u] * vb[u].x; r[u][5] = t[u] * vb[u].y; r[u][6] = t[u] * vb[u].z; r[u][7] = t[u] * vb[u].w;
-            }
-        }
-        fetch();
+    for (int r = 1; r < R; ++r) fetch(p[r], base + r * tstep);
+    while (base < n_vec) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (id[u] >= n_vec) continue;
-            const size_t e = static_cast<size_t>(id[u]) * VW;
-            if constexpr (!OUT_BF16) {
-                f32x4* q = reinterpret_cast<f32x4*>(static_cast<float*>(dW) + e);
-                f32x4 x = {r[u][0], r[u][1], r[u][2], r[u][3]};
-                if (accumulate) x += *q;
-                __builtin_nontemporal_store(x, q);
-            } else if constexpr (VW == 8) {
-                u32x4* q = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dW) + e);
-                if (accumulate) {
-                    const u32x4 old = *q;
-                    r[u][0] += bf16_lo(old.x); r[u][1] += bf16_hi(old.x); r[u][2] += bf16_lo(old.y); r[u][3] += bf16_hi(old.y);
-                    r[u][4] += bf16_lo(old.z); r[u][5] += bf16_hi(old.z); r[u][6] += bf16_lo(old.w); r[u][7] += bf16_hi(old.w);
-                }
-                __builtin_nontemporal_store(u32x4{pack_bf16x2(r[u][0], r[u][1]), pack_bf16x2(r[u][2], r[u][3]),
-                                                  pack_bf16x2(r[u][4], r[u][5]), pack_bf16x2(r[u][6], r[u][7])}, q);
-            } else {
-                u32x2* q = reinterpret_cast<u32x2*>(static_cast<uint16_t*>(dW) + e);
-                if (accumulate) {
-                    const u32x2 old = *q;
-                    r[u][0] += bf16_lo(old.x); r[u][1] += bf16_hi(old.x); r[u][2] += bf16_lo(old.y); r[u][3] += bf16_hi(old.y);
-                }
-                __builtin_nontemporal_store(u32x2{pack_bf16x2(r[u][0], r[u][1]), pack_bf16x2(r[u][2], r[u][3])}, q);
-            }
+        for (int r = 0; r < R; ++r) {           // trip k with k % R == r; R is even, so its table half is r & 1
+            if (base >= n_vec) break;
+            fetch(p[r], base + R * tstep);
+            store_trip(base, r & 1);
+            landed(p[(r + 1) % R], WaitN{});
+            publish(p[(r + 1) % R], (r + 1) & 1);
+            lds_barrier();
+            base += tstep;
         }
     }
 }
@@ -1575,36 +1662,6 @@ hipError_t expand_any(const float* partial, int splits, int64_t Mp, const float*
                : launch_expand<false, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, false, st);
 }
 
-template <bool OUT_BF16, int VW>
-hipError_t launch_expand_flat(const float* T, int64_t t_stride, const float* v, void* dW, int64_t O, int64_t D,
-                              int64_t M, bool accumulate, const LaunchCfg& cfg, hipStream_t st) {
-    const int64_t n_vec = O * D / VW;
-    int64_t blocks = cfg.num_cus;                                // one block per compute unit
-    if (blocks > ceil_div(n_vec, 256)) blocks = ceil_div(n_vec, 256);
-    hipLaunchKernelGGL((wgrad_expand_flat_kernel<OUT_BF16, VW>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, T,
-                       t_stride, v, dW, static_cast<uint32_t>(n_vec), static_cast<uint32_t>(D / VW),
-                       static_cast<uint32_t>(D / M / VW), static_cast<uint32_t>(M), accumulate ? 1 : 0);
-    return hipGetLastError();
-}
-
-// dW (+)= T (x) v from a summed T with row stride t_stride: the flat sweep when its vectors fit the
-// shape and the pointers, else the row-by-row kernel on a single "split".
-hipError_t expand_from_t(const float* T, int64_t t_stride, const float* v, int v_align, void* dW, bool dw_bf16,
-                         int dw_align, bool accumulate, int64_t O, int64_t D, int64_t M, const LaunchCfg& cfg,
-                         hipStream_t st) {
-    const int64_t d = D / M;
-    const bool small = static_cast<double>(O) * static_cast<double>(D) / 4.0 < 2147483648.0 - 16777216.0;
-    if (small && v_align >= 16 && env_int("VELORA_WGRAD_FLAT", 1) != 0) {
-        if (!dw_bf16 && d % 4 == 0 && dw_align >= 16)
-            return launch_expand_flat<false, 4>(T, t_stride, v, dW, O, D, M, accumulate, cfg, st);
-        if (dw_bf16 && d % 8 == 0 && dw_align >= 16)
-            return launch_expand_flat<true, 8>(T, t_stride, v, dW, O, D, M, accumulate, cfg, st);
-        if (dw_bf16 && d % 4 == 0 && dw_align >= 8)
-            return launch_expand_flat<true, 4>(T, t_stride, v, dW, O, D, M, accumulate, cfg, st);
-    }
-    return expand_any(T, 1, t_stride, v, v_align, dW, dw_bf16, dw_align, accumulate, O, D, M, st);
-}
-
 }  // namespace
 
 // T[o, g] = sum over splits of partial[split][o][g], fixed order; T is dense [O, M].
@@ -1628,16 +1685,73 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
     T[i] = s;
 }
 
+namespace {
+
+template <bool OUT_BF16, int VW>
+hipError_t launch_expand_sweep(const float* partial, int splits, int64_t split_stride, size_t part_bytes, int64_t t_stride,
+                               const float* v, void* dW, int64_t O, int64_t D, int64_t M, bool accumulate,
+                               const LaunchCfg& cfg, hipStream_t st) {
+    const int64_t n_vec = O * D / VW;
+    const uint32_t dv = static_cast<uint32_t>(D / M / VW);
+    int64_t blocks = cfg.num_cus;                                // one block per compute unit
+    if (blocks > ceil_div(n_vec, 256)) blocks = ceil_div(n_vec, 256);
+    const uint32_t dv_inv = static_cast<uint32_t>(4294967296ull / dv) + 1u;   // exact x / dv for x * dv < 2^32
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, partial,
+                           static_cast<uint32_t>(split_stride * 4), static_cast<uint32_t>(part_bytes), v, dW,
+                           static_cast<uint32_t>(n_vec), dv, dv_inv, static_cast<uint32_t>(M),
+                           static_cast<uint32_t>(t_stride), static_cast<uint32_t>(O * M));
+        return hipGetLastError();
+    };
+    if (splits <= 8)
+        return accumulate ? go(wgrad_expand_sweep_kernel<OUT_BF16, VW, 1, true>)
+                          : go(wgrad_expand_sweep_kernel<OUT_BF16, VW, 1, false>);
+    return accumulate ? go(wgrad_expand_sweep_kernel<OUT_BF16, VW, 2, true>)
+                      : go(wgrad_expand_sweep_kernel<OUT_BF16, VW, 2, false>);
+}
+
+// dW (+)= (sum over splits of partial[split]) (x) v, rows of partial `t_stride` floats apart: the window
+// sweep when its vectors fit the shape and the pointers, else the row-by-row kernel.
+hipError_t expand_best(const float* partial, int splits, int64_t t_stride, const float* v, int v_align, void* dW,
+                       bool dw_bf16, int dw_align, bool accumulate, int64_t O, int64_t D, int64_t M,
+                       const LaunchCfg& cfg, hipStream_t st) {
+    const int64_t d = D / M;
+    const double lim = 2147483648.0 - 16777216.0;
+    const size_t part_bytes = static_cast<size_t>(splits) * static_cast<size_t>(O) * static_cast<size_t>(t_stride) * 4;
+    // sixteen split strides stay below 2^30 bytes: the offsets of the splits a kernel asks for beyond
+    // the last real one then land past the end of the descriptor (zeros) without wrapping around
+    // Rows of 32 KB and more: measured against the row-by-row kernel on whole calls, alternating in one
+    // process, the sweep is level or ahead on every such layer shape (-0.4 us on 4096 x 11008 with M = 43,
+    // -2.1 us with M = 64, -8.9 us on 5120 x 13824 with M = 216); with shorter rows the many small blocks
+    // of the row kernel interleave as well or better (+1..2 us for the sweep on the 5120-wide layers).
+    const int sweep_mode = env_int("VELORA_WGRAD_SWEEP", 1);   // measurement builds: 0 never, 2 whenever it fits
+    const bool long_rows = D * (dw_bf16 ? 2 : 4) >= 32768;
+    const bool fits = static_cast<double>(O) * static_cast<double>(D) / 4.0 < lim &&
+                      static_cast<double>(O) * static_cast<double>(t_stride) <= 16777216.0 && splits <= 16 && d <= 2048 &&
+                      (sweep_mode == 2 || (sweep_mode == 1 && long_rows));
+    if (fits) {
+        const int64_t ss = O * t_stride;
+        if (!dw_bf16 && d % 4 == 0 && d / 4 >= 16 && dw_align >= 16)
+            return launch_expand_sweep<false, 4>(partial, splits, ss, part_bytes, t_stride, v, dW, O, D, M, accumulate, cfg, st);
+        if (dw_bf16 && d % 8 == 0 && d / 8 >= 16 && dw_align >= 16)
+            return launch_expand_sweep<true, 8>(partial, splits, ss, part_bytes, t_stride, v, dW, O, D, M, accumulate, cfg, st);
+        if (dw_bf16 && d % 4 == 0 && d / 4 >= 16 && dw_align >= 8)
+            return launch_expand_sweep<true, 4>(partial, splits, ss, part_bytes, t_stride, v, dW, O, D, M, accumulate, cfg, st);
+    }
+    return expand_any(partial, splits, t_stride, v, v_align, dW, dw_bf16, dw_align, accumulate, O, D, M, st);
+}
+
+}  // namespace
+
 hipError_t launch_wgrad(const void* G, const void* S, const float* v, int64_t N, int64_t O, int64_t D, int64_t M,
                         bool is_bf16, int g_align, int s_align, int v_align, void* dW, bool dw_bf16, int dw_align,
                         bool accumulate, void* ws, const WgradPlan& plan, const LaunchCfg& cfg, hipStream_t st) {
-    (void)cfg;
     const int phases = env_int("VELORA_WGRAD_PHASES", 7);   // tuning aid: 1 pack, 2 partial, 4 expand
     hipError_t e = launch_partials(G, S, N, O, M, is_bf16, g_align, s_align, ws, plan, phases, st);
     if (e != hipSuccess) return e;
     if (!(phases & 4)) return hipSuccess;
-    return expand_any(static_cast<const float*>(ws), plan.splits, plan.Mp, v, v_align, dW, dw_bf16, dw_align, accumulate,
-                      O, D, M, st);
+    return expand_best(static_cast<const float*>(ws), plan.splits, plan.Mp, v, v_align, dW, dw_bf16, dw_align, accumulate,
+                       O, D, M, cfg, st);
 }
 
 hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t O, int64_t M, bool is_bf16,
@@ -1651,7 +1765,7 @@ hipError_t launch_wgrad_factor(const void* G, const void* S, int64_t N, int64_t 
 
 hipError_t launch_expand_factor(const float* T, const float* v, int v_align, void* dW, bool dw_bf16, int dw_align,
                                 bool accumulate, int64_t O, int64_t D, int64_t M, const LaunchCfg& cfg, hipStream_t st) {
-    return expand_from_t(T, M, v, v_align, dW, dw_bf16, dw_align, accumulate, O, D, M, cfg, st);
+    return expand_best(T, 1, M, v, v_align, dW, dw_bf16, dw_align, accumulate, O, D, M, cfg, st);
 }
 
 }  // namespace velora

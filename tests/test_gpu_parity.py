@@ -303,6 +303,57 @@ def test_weight_grad_bf16_output_and_accumulate(vl, N, O, D, d):
     assert rel_fro(to_host_f64(dWa), wl.to_f64(baseb, wl.BF16) + want) <= TOL_BF16_STORE
 
 
+# Rows of dW of 32 KB and more are written by the window-sweep kernel: one sweep of the whole grid over dW
+# with a per-block table of T.  Cases: fewer blocks than compute units (a multiple of eight and not), a
+# sub-token of 43 or 86 vectors (table positions drift from window to window), 16 vectors (the smallest the
+# kernel takes) and 512, a ragged last trip, more than eight token ranges, bf16 dW in 16-byte and 8-byte
+# vectors, accumulation, and the hand-off entry points on the same shapes.
+LONG_ROW_CASES = [
+    # (N, O, D, d, dW dtype)
+    (300, 8, 8192, 64, "f32"), (300, 5, 8256, 172, "f32"), (200, 3, 16384, 1024, "f32"),
+    (2000, 300, 8192, 2048, "f32"), (700, 131, 11008, 344, "f32"), (8192, 2048, 8192, 256, "f32"),
+    (300, 8, 16384, 128, "bf16"), (260, 12, 16512, 172, "bf16"), (1500, 260, 16384, 256, "bf16"),
+]
+
+
+@pytest.mark.parametrize("N,O,D,d,dw", LONG_ROW_CASES)
+def test_weight_grad_long_rows(vl, N, O, D, d, dw):
+    torch = _torch()
+    M = D // d
+    G = wl.random_tensor(N, O, wl.BF16, seed=N + O + 11, stream=7, sigma=0.02)
+    S = wl.random_tensor(N, M, wl.BF16, seed=N + M + 12, stream=8)
+    v = wl.random_unit_v(d, seed=d + 5)
+    Gd, Sd, vd = to_dev(G, wl.BF16), to_dev(S, wl.BF16), to_dev(v, wl.F32)
+    T_ref, want = oracle.weight_grad_factored(G, S, v, D)
+    tdt = torch.float32 if dw == "f32" else torch.bfloat16
+    tol = TOL_F32_FROM_BF16 if dw == "f32" else TOL_BF16_STORE
+    dW = vl.velora_weight_grad(Gd, Sd, vd, D, dw_dtype=tdt)
+    got = to_host_f64(dW)
+    assert got.shape == (O, D)
+    assert rel_fro(got, want) <= tol
+    if dw == "f32":
+        assert rel_max(got, want) <= tol
+    # every row on its own (a misplaced table entry would spoil single rows, not the norm of the whole)
+    row_err = np.linalg.norm(got - want, axis=1) / (np.linalg.norm(want, axis=1) + 1e-300)
+    assert row_err.max() <= 4 * tol
+    # accumulate into an existing gradient of the same dtype
+    if dw == "f32":
+        base = wl.random_tensor(O, D, wl.F32, seed=4, sigma=0.5)
+        acc = to_dev(base, wl.F32)
+        base64 = base.astype(np.float64)
+    else:
+        base = wl.random_tensor(O, D, wl.BF16, seed=5, sigma=0.5)
+        acc = to_dev(base, wl.BF16)
+        base64 = wl.to_f64(base, wl.BF16)
+    vl.velora_weight_grad(Gd, Sd, vd, D, dW=acc, accumulate=True)
+    assert rel_fro(to_host_f64(acc), base64 + want) <= tol
+    # the hand-off: expanding an exactly known T is one float32 multiply per element
+    if dw == "f32":
+        T1 = (torch.arange(O * M, dtype=torch.float32, device="cuda").reshape(O, M) % 1021.0) - 7.0
+        dW1 = vl.velora_expand_factor(T1, vd, D).cpu().numpy().reshape(O, M, d)
+        assert (dW1 == T1.cpu().numpy()[:, :, None] * v[None, None, :]).all()
+
+
 @pytest.mark.parametrize("N,O,D,d,dtype", [
     (256, 64, 64, 16, wl.F32), (1000, 256, 768, 64, wl.BF16), (450, 72, 1376, 32, wl.BF16),
     (520, 120, 5120, 64, wl.BF16), (300, 64, 1728, 8, wl.BF16), (150, 30, 64, 16, wl.BF16),
