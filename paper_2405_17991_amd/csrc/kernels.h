@@ -77,6 +77,7 @@ struct WgradPlan {
     int64_t Mp;
     int64_t tiles_packed;
     bool cyclic;       // token chunks are dealt to the splits round-robin instead of as contiguous ranges
+    int num_cus;       // compute units the plan was made for
     size_t partial_bytes;
     size_t packed_bytes;
     size_t ws_bytes;

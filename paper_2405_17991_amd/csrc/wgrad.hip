@@ -1586,6 +1586,7 @@ WgradPlan plan_wgrad_uncached(int64_t N, int64_t O, int64_t D, int64_t M, bool i
     p.splits = static_cast<int>(ceil_div(N, rows));
     p.partial_bytes = static_cast<size_t>(p.splits) * static_cast<size_t>(O) * static_cast<size_t>(p.Mp) * sizeof(float);
     p.partial_bytes = (p.partial_bytes + 255) / 256 * 256;
+    p.num_cus = cfg.num_cus;
     p.tiles_packed = 0;
     p.packed_bytes = 0;
     if (is_bf16 && !direct_s(tl)) {
@@ -1615,11 +1616,16 @@ hipError_t launch_partials(const void* G, const void* S, int64_t N, int64_t O, i
         const MfmaChoice ch = choose_mfma(O, M, g_align, s_align, plan);
         // Four group tiles: loader waves, S straight from S[N, M], no re-layout pre-pass (N * M even for the
         // same reason as in dispatch_mfma): 28.6 against 36.2 us on N = 16384, O = 4096, M = 64 and 35.6
-        // against 42.6 us on O = 5120, M = 54, pre-pass included.  With five tiles the same kernel measured
-        // level on O = 5120 and 11 % slower on O = 13824 (M = 80), so five and six stay with the per-wave
-        // kernel (measurement builds: VELORA_WGRAD_WS=2 sends them here too).
+        // against 42.6 us on O = 5120, M = 54, pre-pass included.  Five and six tiles: the same kernel when
+        // every block is resident at once (at most one per compute unit), where the per-wave kernel's four
+        // waves are all a compute unit has to hide latency with (O = 5120: 59.7 against 65.0 us at M = 74,
+        // 65.9 against 67.2 us at M = 80); with several rounds of blocks it is level or behind
+        // (O = 13824, M = 80: 147 against 144 us), so those stay with the per-wave kernel.
+        // (measurement builds: VELORA_WGRAD_WS=0 never, 2 for every launch with four to six tiles)
         const int ws_mode = env_int("VELORA_WGRAD_WS", 1);
-        if (ch.cw == 8 && !ch.shared && ch.gt >= 4 && ch.gt <= (ws_mode == 2 ? 6 : 4) && ch.chunks == 1 && ch.s_align16 &&
+        const bool one_round = ceil_div(O, 128) * plan.splits <= plan.num_cus;
+        const int ws64_max_gt = ws_mode == 2 || one_round ? 6 : 4;
+        if (ch.cw == 8 && !ch.shared && ch.gt >= 4 && ch.gt <= ws64_max_gt && ch.chunks == 1 && ch.s_align16 &&
             (N * M) % 2 == 0 && ws_mode != 0) {
             if (!(phases & 2)) return hipSuccess;
             if (ch.gt == 4) return launch_ws64<4>(G, S, partial, N, O, M, plan, st);

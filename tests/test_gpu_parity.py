@@ -256,6 +256,9 @@ WGRAD_CASES = [
     (63, 128, 1568, 32, wl.BF16), (64, 72, 2048, 32, wl.BF16), (65, 264, 2016, 32, wl.BF16),   # M = 49, 64, 63
     (1000, 136, 416, 8, wl.BF16),                # M = 52
     (30000, 128, 512, 8, wl.BF16),               # M = 64: many chunks per split
+    # five and six group tiles in the same kernel (all blocks resident at once)
+    (64, 64, 1040, 16, wl.BF16), (700, 128, 1520, 16, wl.BF16), (333, 200, 1536, 16, wl.BF16),   # M = 65, 95, 96
+    (9000, 256, 640, 8, wl.BF16),                # M = 80: several chunks per split
 ]
 
 
