@@ -387,12 +387,29 @@ constexpr size_t ws_kernel_lds_bytes(int gt) { return static_cast<size_t>(kWsSlo
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
+// Token (0..31 inside a 32-token step) of K slot (q, e) of the MFMA operands.  Any one-to-one choice is
+// valid as long as G and S agree; it decides which LDS banks a 2-byte read of S hits.  Such a read is
+// served half a wave at a time, i.e. lane groups q = 0, 1 together and q = 2, 3 together, 16 lanes x 2
+// bytes = 8 banks each; the two groups' rows of S are dq tokens = dq * 2M bytes apart, and they collide
+// when that is close to a multiple of 128 bytes (M = 32, 48, 80 with dq = 8).  The four maps put the
+// pair dq = 8, 1, 2 or 4 tokens apart; the host picks the one whose distance is nearest to 64 bytes
+// mod 128 (measured at M = 80, O = 5120: 37.5 us with dq = 8, 35.4 us with dq = 2).  A power-of-two
+// M >= 64 collides under every map.
+__device__ __forceinline__ int token_of_slot(int mode, int q, int e) {
+    switch (mode) {
+        case 1: return q + 4 * e;
+        case 2: return 2 * (q & 1) + (q >> 1) + 4 * e;
+        case 3: return 4 * (q & 1) + (q >> 1) + 2 * (e & 1) + 8 * (e >> 1);
+        default: return 8 * q + e;
+    }
+}
+
 template <int GT>
 __global__ __launch_bounds__(512) void wgrad_partial_ws_kernel(const uint16_t* __restrict__ G,
                                                               const uint16_t* __restrict__ S,
                                                               float* __restrict__ partial, int64_t N, int64_t O,
                                                               int64_t M, int64_t Mp, int64_t rows_per_split,
-                                                              int cyclic) {
+                                                              int cyclic, int tau_mode) {
     constexpr int CW = 8, OT = 128;
     constexpr int NACC = GT * CW;
     constexpr int TP = NACC;                              // <= 24 tiles: one pass of the cross-wave sum
@@ -468,10 +485,13 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws_kernel(const uint16_t* _
     // value of token 8q + e, group jj (tile a: + 32 a bytes).  A lane whose group lies past M in the last
     // tile reads some other token's value there and replaces it by zero afterwards.
     const int zero_off = kWsSlots * kSlotBytes;
-    const int g_lds0 = (32 * (mw & 3) + 8 * q) * 256 + jj * 16;
-    int s_lds[8];
+    int g_lds[8], s_lds[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s_lds[e] = kWsGBytes + ((32 * (mw & 3) + 8 * q + e) * static_cast<int>(M) + jj) * 2;
+    for (int e = 0; e < 8; ++e) {
+        const int tok = 32 * (mw & 3) + token_of_slot(tau_mode, q, e);
+        g_lds[e] = tok * 256 + jj * 16;
+        s_lds[e] = kWsGBytes + (tok * static_cast<int>(M) + jj) * 2;
+    }
     const bool last_tile_ok = (GT - 1) * 16 + jj < M;
     (void)zero_off;
 
@@ -500,7 +520,7 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws_kernel(const uint16_t* _
             RawRow<4> rows[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                const uint4 x = *reinterpret_cast<const uint4*>(lds + slot_off + g_lds0 + r * 256);
+                const uint4 x = *reinterpret_cast<const uint4*>(lds + slot_off + g_lds[r]);
                 rows[r].w[0] = x.x; rows[r].w[1] = x.y; rows[r].w[2] = x.z; rows[r].w[3] = x.w;
             }
             uint32_t sv[GT][8];
@@ -594,7 +614,7 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t*
                                                                 const uint16_t* __restrict__ S,
                                                                 float* __restrict__ partial, int64_t N, int64_t O,
                                                                 int64_t M, int64_t Mp, int64_t rows_per_split,
-                                                                int cyclic) {
+                                                                int cyclic, int tau_mode) {
     constexpr int CW = 8, OT = 128, CH = 4;               // CH: column tiles per computing wave
     constexpr int NS = ws64_s_kb4(GT);                    // S loads per loader wave and chunk
     constexpr int kSlotBytes = kWs64GBytes + NS * 4096;
@@ -664,10 +684,13 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t*
     for (int a = 0; a < GT; ++a)
 #pragma unroll
         for (int c = 0; c < CH; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int g_lds0 = (32 * step + 8 * q) * 256 + jj * 16 + half * 8;
-    int s_lds[8];
+    int g_lds[8], s_lds[8];                               // token_of_slot: which token sits in K slot (q, e)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s_lds[e] = kWs64GBytes + ((32 * step + 8 * q + e) * static_cast<int>(M) + jj) * 2;
+    for (int e = 0; e < 8; ++e) {
+        const int tok = 32 * step + token_of_slot(tau_mode, q, e);
+        g_lds[e] = tok * 256 + jj * 16 + half * 8;
+        s_lds[e] = kWs64GBytes + (tok * static_cast<int>(M) + jj) * 2;
+    }
     const bool last_tile_ok = (GT - 1) * 16 + jj < M;
 
     if (loader) {
@@ -688,7 +711,7 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t*
             const int slot_off = (i % kWsSlots) * kSlotBytes;
             uint2 rows[8];
 #pragma unroll
-            for (int r = 0; r < 8; ++r) rows[r] = *reinterpret_cast<const uint2*>(lds + slot_off + g_lds0 + r * 256);
+            for (int r = 0; r < 8; ++r) rows[r] = *reinterpret_cast<const uint2*>(lds + slot_off + g_lds[r]);
             bf16x8 gf[CH];
 #pragma unroll
             for (int c = 0; c < CH; ++c) gf[c] = column_fragment4(rows, c);
@@ -1343,6 +1366,20 @@ hipError_t launch_mfma(const void* G, const void* s_operand, float* partial, int
     return hipGetLastError();
 }
 
+// The token_of_slot map for S rows of M values: the pair distance (in bytes, mod 128) nearest to 64.
+int pick_tau_mode(int64_t M) {
+    const int forced = env_int("VELORA_WGRAD_TAU", -1);
+    if (forced >= 0) return forced;
+    static const int kDq[4] = {8, 1, 2, 4};
+    int best = 0, best_dist = 1 << 30;
+    for (int m = 0; m < 4; ++m) {
+        const int off = static_cast<int>((kDq[m] * M * 2) % 128);
+        const int dist = off > 64 ? off - 64 : 64 - off;
+        if (dist < best_dist) { best_dist = dist; best = m; }
+    }
+    return best;
+}
+
 template <int GT>
 hipError_t launch_ws(const void* G, const void* S, float* partial, int64_t N, int64_t O, int64_t M, const WgradPlan& plan,
                      hipStream_t st) {
@@ -1361,7 +1398,7 @@ hipError_t launch_ws(const void* G, const void* S, float* partial, int64_t N, in
     dim3 grid(static_cast<unsigned>(ceil_div(O, 128)), static_cast<unsigned>(plan.splits), 1);
     hipLaunchKernelGGL((wgrad_partial_ws_kernel<GT>), grid, dim3(512), lds_bytes, st, static_cast<const uint16_t*>(G),
                        static_cast<const uint16_t*>(S), partial, N, O, M, plan.Mp, plan.rows_per_split,
-                       plan.cyclic ? 1 : 0);
+                       plan.cyclic ? 1 : 0, pick_tau_mode(M));
     return hipGetLastError();
 }
 
@@ -1382,7 +1419,7 @@ hipError_t launch_ws64(const void* G, const void* S, float* partial, int64_t N, 
     dim3 grid(static_cast<unsigned>(ceil_div(O, 128)), static_cast<unsigned>(plan.splits), 1);
     hipLaunchKernelGGL((wgrad_partial_ws64_kernel<GT>), grid, dim3(512), lds_bytes, st, static_cast<const uint16_t*>(G),
                        static_cast<const uint16_t*>(S), partial, N, O, M, plan.Mp, plan.rows_per_split,
-                       plan.cyclic ? 1 : 0);
+                       plan.cyclic ? 1 : 0, pick_tau_mode(M));
     return hipGetLastError();
 }
 
