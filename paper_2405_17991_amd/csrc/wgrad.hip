@@ -16,7 +16,6 @@
 #include "kernels.h"
 
 #include <atomic>
-#include <type_traits>
 #ifdef VELORA_TUNING
 #include <cstdlib>
 #endif
@@ -1119,7 +1118,6 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
 // would wait for the stores).  Needs dv >= 16, d <= 2048, at most 8 * NS8 splits, partials
 // below 2 GiB and fewer than 2^31 - 2^24 vectors.
 // ---------------------------------------------------------------------------
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int kSweepU = 8;
 constexpr int kSweepNL = 18;
 
@@ -1139,7 +1137,7 @@ __global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __
 
     // Everything below is straight-line code inside one loop whose only branches are uniform: with
     // divergent branches around the loads and stores the compiler's wait-count bookkeeping falls back
-    // to "wait for everything", which drains the store stream once per trip (35 against 31 us).
+    // to "wait for everything", which drains the store stream once per trip (35 against 29 us).
     // Threads without a table entry load from past the end of the descriptor (zeros, no memory
     // request) and write their sum to the dump slot; stores past the end of dW are dropped by the
     // range check of a descriptor that is rebuilt for every trip.
@@ -1147,14 +1145,8 @@ __global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __
     const bool fetcher = t < static_cast<uint32_t>(U) * nl;
     const uint32_t fu = t / nl, fk = t - fu * nl;
     const uint32_t slot = fetcher ? t : static_cast<uint32_t>(U * NL);
-    // The partial loads and the waits for them are written out (inline assembly): the compiler's
-    // wait-count pass merges the loop's first and later iterations and then waits for the previous
-    // trip's stores as well (vmcnt(13) where 24 operations may stay in flight).  Loads and stores
-    // share one in-order counter on this chip, so "at most n younger operations outstanding" is the
-    // exact condition; operations the compiler does not know of only make its own waits stricter.
-    const uint64_t pa64 = reinterpret_cast<uint64_t>(partial);
-    const i32x4 pr_words = {static_cast<int>(pa64 & 0xFFFFFFFFu), static_cast<int>((pa64 >> 32) & 0xFFFFu),
-                            static_cast<int>(part_bytes), 0x00020000};   // base, stride 0, bytes, raw 32-bit data
+    const __amdgpu_buffer_rsrc_t pr =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(partial), 0, part_bytes, 0x00020000);
     auto fetch = [&](float (&px)[NS], uint32_t trip_base) {   // trip_base: the block's first vector in window 0 of that trip
         const uint32_t b = trip_base + fu * stride;             // the block's first vector in window fu
         const uint32_t L = b / dv + fk;
@@ -1163,22 +1155,7 @@ __global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __
         const uint32_t off = ok ? (o * Mp + g) * 4u : 0x80000000u;
 #pragma unroll
         for (int s = 0; s < NS; ++s)
-            asm volatile("buffer_load_dword %0, %1, %2, 0 offen"
-                         : "=v"(px[s])
-                         : "v"(off + s * split_stride_b), "s"(pr_words)
-                         : "memory");
-    };
-    // wait until at most `younger` vector-memory operations issued after px's loads are outstanding
-    auto landed = [&](float (&px)[NS], auto younger) {
-        constexpr int n = decltype(younger)::value;
-        static_assert(n >= 0 && n <= 63, "vmcnt has six bits");
-#pragma unroll
-        for (int s0 = 0; s0 < NS; s0 += 8)
-            asm volatile("s_waitcnt vmcnt(%8)"
-                         : "+v"(px[s0]), "+v"(px[s0 + 1]), "+v"(px[s0 + 2]), "+v"(px[s0 + 3]), "+v"(px[s0 + 4]),
-                           "+v"(px[s0 + 5]), "+v"(px[s0 + 6]), "+v"(px[s0 + 7])
-                         : "n"(n)
-                         : "memory");
+            px[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(pr, off + s * split_stride_b, 0, 0));
     };
     auto publish = [&](const float (&px)[NS], int half) {
         float sum = 0.f;
@@ -1243,37 +1220,29 @@ __global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __
         }
     };
 
-    // Loads run R trips ahead of the stores that use them, so that the wait in front of publish() is
-    // for loads that have had R - 1 whole trips of stores to come back; p[r] are the landing
-    // registers of trips r, r + R, ...  Behind the loads of trip k + 1 when they are waited for:
-    // in the steady state (R - 1) later fetches and R trips of stores (and of loads of the old
-    // values when accumulating); for the first trips, whose fetches were issued back to back, one
-    // trip of stores at least.  The smaller count serves for both (it only asks that stores three
-    // trips old have completed as well).
-    constexpr int R = NS8 == 1 ? 4 : 2;
-    constexpr int kPerTrip = ACC ? 2 * U : U;
-    using Wait0 = std::integral_constant<int, 0>;
-    using WaitN = std::integral_constant<int, (R - 1) * NS + kPerTrip>;
+    // Loads run two trips ahead of the stores that use them, into two alternating register sets, so
+    // that the wait in front of publish() is for loads that have had a whole trip of stores to come
+    // back.  Everything is compiler-visible straight-line code: its wait counts come out as "at most
+    // the stores and loads issued since" (vmcnt(16..24)), not as "everything".
     const uint32_t tstep = U * stride;
     uint32_t base = piece * 256u;               // the block's first vector in window 0 of the current trip
-    float p[R][NS];
-    fetch(p[0], base);
-    landed(p[0], Wait0{});
-    publish(p[0], 0);
+    float pa[NS], pb[NS];
+    fetch(pa, base);
+    publish(pa, 0);
     lds_barrier();
-#pragma unroll
-    for (int r = 1; r < R; ++r) fetch(p[r], base + r * tstep);
+    fetch(pa, base + tstep);
     while (base < n_vec) {
-#pragma unroll
-        for (int r = 0; r < R; ++r) {           // trip k with k % R == r; R is even, so its table half is r & 1
-            if (base >= n_vec) break;
-            fetch(p[r], base + R * tstep);
-            store_trip(base, r & 1);
-            landed(p[(r + 1) % R], WaitN{});
-            publish(p[(r + 1) % R], (r + 1) & 1);
-            lds_barrier();
-            base += tstep;
-        }
+        fetch(pb, base + 2 * tstep);
+        store_trip(base, 0);
+        publish(pa, 1);
+        lds_barrier();
+        base += tstep;
+        if (base >= n_vec) break;
+        fetch(pa, base + 2 * tstep);
+        store_trip(base, 1);
+        publish(pb, 0);
+        lds_barrier();
+        base += tstep;
     }
 }
 
@@ -1764,9 +1733,10 @@ hipError_t expand_best(const float* partial, int splits, int64_t t_stride, const
     // sixteen split strides stay below 2^30 bytes: the offsets of the splits a kernel asks for beyond
     // the last real one then land past the end of the descriptor (zeros) without wrapping around
     // Rows of 32 KB and more: measured against the row-by-row kernel on whole calls, alternating in one
-    // process, the sweep is level or ahead on every such layer shape (-0.4 us on 4096 x 11008 with M = 43,
-    // -2.1 us with M = 64, -8.9 us on 5120 x 13824 with M = 216); with shorter rows the many small blocks
-    // of the row kernel interleave as well or better (+1..2 us for the sweep on the 5120-wide layers).
+    // process, the sweep is ahead on every such layer shape (-2.4 us on 4096 x 11008 with M = 43,
+    // -3.6 us with M = 64, -4.4 us on 5120 x 13824 with M = 54, -7.4 us with M = 216); with shorter rows
+    // the many small blocks of the row kernel interleave as well (-1.8 .. +0.9 us for the sweep on the
+    // 4096- and 5120-wide layers, no trend).
     const int sweep_mode = env_int("VELORA_WGRAD_SWEEP", 1);   // measurement builds: 0 never, 2 whenever it fits
     const bool long_rows = D * (dw_bf16 ? 2 : 4) >= 32768;
     const bool fits = static_cast<double>(O) * static_cast<double>(D) / 4.0 < lim &&
