@@ -42,7 +42,7 @@ def _stale(target: str, deps: List[str]) -> bool:
 # spill inside them would add scratch loads and stores to that count, which makes every wait cover more
 # than it needs and serialises the load streams, so the build fails if the compiler reports any spill or
 # scratch use for them.
-NO_SPILL = {"linear.hip": "linear_mfma_kernel"}
+NO_SPILL = {"linear.hip": "linear_mfma_kernel", "wgrad.hip": "wgrad_partial_ws"}
 
 
 def _check_no_spill(src: str, remarks: str) -> None:
