@@ -54,7 +54,7 @@ def _parse():
                     help="only the streaming probes and the step's two entry points on the headline workload "
                          "(no warm-cache leg, no other records, no shape sweep): under rocprofv3 every launch of "
                          "a hot-path kernel then has the headline shape and cold buffers")
-    ap.add_argument("--shape-steps", type=int, default=50)
+    ap.add_argument("--shape-steps", type=int, default=100)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (a kernel of known traffic, "
                          "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -142,16 +142,34 @@ def _time_steps(torch, ring, steps, warmup, with_events, rotate=True):
     return dt, c, w
 
 
+def _settle(torch, ring, ms=30.0):
+    """Steps of the ring's own workload until `ms` of them have run: the same protection against the chip's
+    power-management transient as the headline's 100 warm-up steps (a fixed count would be 3 ms of a small
+    layer and 20 ms of a large one)."""
+    t0 = time.perf_counter()
+    i = 0
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(20):
+            ring.step(i)
+            i += 1
+        torch.cuda.synchronize()
+
+
 def _event_samples_us(torch, fn, launches):
     """Per-launch microseconds of fn(i), one sample per event pair around EVENT_BATCH launches."""
-    for i in range(3):
-        fn(i)
+    # at least 20 ms of the same launches first (see _settle)
+    t0, k = time.perf_counter(), 0
+    while k < 3 or (time.perf_counter() - t0) * 1e3 < 20.0:
+        for _ in range(5):
+            fn(k)
+            k += 1
+        torch.cuda.synchronize()
     n_batches = max(1, launches // EVENT_BATCH)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_batches)]
     for b in range(n_batches):
         ev[b][0].record()
         for i in range(EVENT_BATCH):
-            fn(3 + b * EVENT_BATCH + i)
+            fn(k + b * EVENT_BATCH + i)
         ev[b][1].record()
     torch.cuda.synchronize()
     return [e[0].elapsed_time(e[1]) / EVENT_BATCH * 1e3 for e in ev]
@@ -691,6 +709,7 @@ def main():
             Xs, Gs = _device_inputs(torch, s, dev)
             vs = vl.velora_init_v(Xs, s.M, allow_degenerate=True)
             r = Ring(vl, torch, s, Xs, Gs, vs, dw_dtype)
+            _settle(torch, r)
             _, cs, wsmp = _time_steps(torch, r, args.shape_steps, 40, with_events=True)
             cst, wst = _stats(cs), _stats(wsmp)
             rec = _shape_record(s, cst["mean"], wst["mean"], dw_b, r.ws_bytes)
