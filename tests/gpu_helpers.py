@@ -9,7 +9,8 @@ import workloads as wl
 # Tolerances (the benchmark spec): float32 path 1e-5 relative (Frobenius, and max error
 # against the largest magnitude); bf16 inputs with float32 accumulation 2e-2
 # relative Frobenius.  The secondary bounds below are what the arithmetic should
-# really achieve (derivation in the design document) and are asserted as well.
+# really achieve (one rounding to bf16 on store; exact bf16 products accumulated
+# in float32 over N terms, error about sqrt(N) * 2^-24) and are asserted as well.
 TOL_F32 = 1e-5
 TOL_BF16 = 2e-2
 TOL_BF16_STORE = 4e-3        # one RNE rounding to bf16: rms relative error 2^-9/sqrt(3) ~ 1.1e-3

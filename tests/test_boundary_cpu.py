@@ -230,6 +230,42 @@ def test_update_v_argument_errors(vl):
     assert c(P, P, 64, 16, 4, vl.F32, P, None, 0.5, P, None, need, None) == 5
 
 
+def test_weight_grad_static_argument_errors(vl):
+    # the same host-side checks as velora_weight_grad, and a plan that needs more than the static array is
+    # refused before any device call (so this runs without a GPU)
+    from paper_2405_17991_amd.binding import raw
+    w = raw.velora_weight_grad_static
+    N, O, D, M = 64, 32, 16, 4
+    ok = (P, P, P, N, O, D, M, vl.BF16, P, vl.F32, 0, None)
+
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return w(*a)
+
+    assert call(a0=None) == 1 and call(a1=None) == 1 and call(a2=None) == 1 and call(a8=None) == 1
+    assert call(a7=5) == 3 and call(a9=5) == 3
+    assert call(a3=0) == 2 and call(a4=0) == 2 and call(a6=3) == 2
+    assert call(a0=P + 1) == 4 and call(a8=P + 2) == 4
+    # 2^20 output features x 1024 groups: 4 GiB of partial sums per token range
+    big = vl.velora_workspace_bytes(vl.OP_WEIGHT_GRAD, 1024, 1024 * 8, 1 << 20, 1024, vl.BF16)
+    assert big > vl.STATIC_SCRATCH_BYTES
+    assert w(P, P, P, 1024, 1 << 20, 1024 * 8, 1024, vl.BF16, P, vl.F32, 0, None) == 5
+
+
+def test_bandwidth_probe_argument_errors(vl):
+    from paper_2405_17991_amd.binding import raw
+    b = raw.velora_bandwidth_probe
+    assert b(3, P, P, 1024, P, None) == 2 and b(-1, P, P, 1024, P, None) == 2
+    assert b(0, P, None, 0, P, None) == 2 and b(0, P, None, 1000, P, None) == 2      # bytes: positive multiple of 16
+    assert b(0, None, None, 1024, P, None) == 1 and b(0, P, None, 1024, None, None) == 1
+    assert b(1, None, None, 1024, None, None) == 1 and b(2, P, None, 1024, None, None) == 1
+    assert b(2, None, P, 1024, None, None) == 1
+    assert b(0, P + 8, None, 1024, P, None) == 4 and b(1, None, P + 4, 1024, None, None) == 4
+    assert b(0, P, None, 1024, P + 2, None) == 4
+
+
 def test_workspace_query(vl):
     q = vl.velora_workspace_bytes
     assert q(vl.OP_COMPRESS, 128, 64, 0, 4, vl.BF16) == 0

@@ -439,3 +439,22 @@ def test_shape_error_reaches_python(vl):
     with pytest.raises(vl.VeloraError) as ei:
         vl.velora_compress(X, v, 13)                        # 13824 / 1024 is not an integer
     assert ei.value.status == 2
+
+
+@pytest.mark.parametrize("nbytes", [16, 4096 + 16, (3 << 20) + 48, 64 << 20])
+def test_bandwidth_probe_kernels_move_what_they_claim(vl, nbytes):
+    # the streaming probes that bench.py's measured ceilings come from: copy is bit-exact and touches nothing
+    # past the end, write leaves zeros, read leaves its source alone
+    torch = _torch()
+    g = torch.Generator(device="cuda").manual_seed(nbytes % 9973)
+    src = torch.randint(0, 256, (nbytes + 64,), dtype=torch.uint8, device="cuda", generator=g)
+    keep = src.clone()
+    dst = torch.full((nbytes + 64,), 0xAB, dtype=torch.uint8, device="cuda")
+    vl.velora_bandwidth_probe("copy", src=src[:nbytes], dst=dst[:nbytes])
+    assert torch.equal(dst[:nbytes], src[:nbytes]) and bool((dst[nbytes:] == 0xAB).all())
+    vl.velora_bandwidth_probe("write", dst=dst[:nbytes])
+    assert int(dst[:nbytes].count_nonzero()) == 0 and bool((dst[nbytes:] == 0xAB).all())
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+    vl.velora_bandwidth_probe("read", src=src[:nbytes], sink=sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, keep)
