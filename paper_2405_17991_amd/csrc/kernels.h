@@ -69,8 +69,9 @@ hipError_t launch_compress_update(const void* X, const float* v_in, void* S, flo
 
 // ---- wgrad.hip ----
 // Workspace layout: float partial[splits][O][Mp] (Mp = M rounded up to 4),
-// then, for bf16 inputs with more than three 16-group tiles (M > 48), S re-laid
-// out as MFMA fragments (ceil(N/32) steps x tiles_packed tiles x 1 KiB).
+// then, for bf16 inputs with more than three 16-group tiles (M > 48), room for S
+// re-laid out as MFMA fragments (ceil(N/32) steps x tiles_packed tiles x 1 KiB);
+// the kernels for four to six tiles use it only when they cannot read S in place.
 struct WgradPlan {
     int splits;        // number of token ranges (split-K)
     int64_t rows_per_split;

@@ -12,6 +12,18 @@
 //            bf16 MFMA, and writes the partials to the workspace;
 //   kernel 2 sums the partials in a fixed order (deterministic, no float
 //            atomics), multiplies by v and streams dW out with 16-byte stores.
+//
+// Kernels in this file, by the number of 16-group tiles ceil(M / 16) a block covers:
+//   wgrad_partial_mfma_kernel      1 tile; 5-6 tiles when the blocks need several rounds; 8-byte G loads;
+//                                  S that is not 16-byte aligned or has an odd element count
+//   wgrad_partial_ws_kernel        2-3 tiles: loader waves + computing waves, 128-token chunks through LDS
+//   wgrad_partial_ws64_kernel      4 tiles, and 5-6 when every block is resident at once: 64-token chunks
+//   wgrad_partial_shared_g_kernel  8, 12, 16 tiles (M up to 256; larger M in chunks of 256)
+//   wgrad_partial_simple_kernel    float32 inputs and whatever the MFMA kernels cannot take
+//   wgrad_pack_s_kernel            S as ready-made MFMA fragments, for the kernels that read S that way
+//   wgrad_expand_kernel            dW rows below 32 KB: one block per row
+//   wgrad_expand_sweep_kernel      dW rows of 32 KB and more: one sweep of the whole grid over dW
+//   wgrad_reduce_kernel            dense T[O, M] for the factored hand-off
 #include "common.h"
 #include "kernels.h"
 
