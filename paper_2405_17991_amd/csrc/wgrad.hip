@@ -565,6 +565,15 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws_kernel(const uint16_t* _
     f32x4 (*red)[TP][kWave] = reinterpret_cast<f32x4 (*)[TP][kWave]>(lds);
     float* out = partial + static_cast<int64_t>(split) * O * Mp;
     constexpr int H = (TP + 1) / 2;
+#if VELORA_SKIP & 8
+    // measurement builds only: the partial tile stored without the cross-wave sum (wrong values, same stores)
+    if (mw == 0 || mw == 2) {
+#pragma unroll
+        for (int i = 0; i < TP; ++i)
+            if ((mw == 0) == (i < H)) store_tile<CW>(out, acc[i / CW][i % CW], o0, jj, q, i % CW, (i / CW) * 16, O, Mp);
+    }
+    return;
+#endif
     if (mw == 1 || mw == 3) {
 #pragma unroll
         for (int i = 0; i < TP; ++i) red[mw >> 1][i][lane] = acc[i / CW][i % CW];
