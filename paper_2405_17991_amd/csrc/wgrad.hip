@@ -1243,8 +1243,8 @@ __global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __
 
     // Loads run two trips ahead of the stores that use them, into two alternating register sets, so
     // that the wait in front of publish() is for loads that have had a whole trip of stores to come
-    // back.  Everything is compiler-visible straight-line code: its wait counts come out as "at most
-    // the stores and loads issued since" (vmcnt(16..24)), not as "everything".
+    // back.  Everything is compiler-visible straight-line code, so its wait counts come out as counts
+    // (vmcnt(7..13) behind this trip's stores and the other set's loads), not as "wait for everything".
     const uint32_t tstep = U * stride;
     uint32_t base = piece * 256u;               // the block's first vector in window 0 of the current trip
     float pa[NS], pb[NS];
