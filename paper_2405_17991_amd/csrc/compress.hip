@@ -82,6 +82,59 @@ __global__ __launch_bounds__(256) void compress_vec_kernel(const typename E::vec
     }
 }
 
+// bf16 sub-tokens whose size is a multiple of 4 but not of 8 (d = 172: the 11008-wide layer at 64
+// sub-tokens per token) start on a 16-byte boundary only every second time, but a PAIR of them is
+// d / 4 whole 16-byte vectors.  One wave slot takes a pair: lane p loads vector p of the pair and keeps
+// two slices of v, one for the elements that belong to the first sub-token and one for the second
+// (the vector in the middle straddles both), so the loads are the 16-byte ones of the kernel above
+// and only the arithmetic doubles.  With 8-byte loads (one sub-token of 43 vectors per wave slot) the
+// layer ran at 0.68 of the HBM peak, as a pair of 43 16-byte vectors at the 0.74 of d = 344.
+// Needs an even number of sub-tokens, X 16-byte aligned, 33 <= d / 4 <= 64.
+template <int U>
+__global__ __launch_bounds__(256) void compress_pair_kernel(const uint4* __restrict__ X, const float* __restrict__ v,
+                                                           uint16_t* __restrict__ S, int64_t n_pairs, int vpp, int d) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / kWave;
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * blockDim.x / kWave;
+    const int64_t n_chunks = ceil_div(n_pairs, static_cast<int64_t>(U));
+    float va[8], vb[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int idx = lane * 8 + e;
+        va[e] = idx < d ? v[idx] : 0.f;
+        vb[e] = (idx >= d && idx < 2 * d) ? v[idx - d] : 0.f;
+    }
+    for (int64_t chunk = wave; chunk < n_chunks; chunk += n_waves) {
+        const int64_t k0 = chunk * U;
+        uint4 q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            q[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (k0 + u < n_pairs && lane < vpp) q[u] = load_stream16(&X[(k0 + u) * vpp + lane]);
+        }
+        float sa[U], sb[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float f[8];
+            Bf16Elem::unpack(q[u], f);
+            float a = 0.f, b = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                a = fmaf(f[e], va[e], a);
+                b = fmaf(f[e], vb[e], b);
+            }
+            sa[u] = group_sum<kWave>(a);
+            sb[u] = group_sum<kWave>(b);
+        }
+        // lane r < 2U stores result r of the wave's 2U consecutive sub-tokens
+        float val = sa[0];
+#pragma unroll
+        for (int r = 1; r < 2 * U; ++r)
+            if (lane == r) val = (r & 1) ? sb[r / 2] : sa[r / 2];
+        if (lane < 2 * U && k0 + lane / 2 < n_pairs) Bf16Elem::store(S, 2 * k0 + lane, val);
+    }
+}
+
 // Generic compress: any d, element-aligned pointers.  P lanes (power of two,
 // chosen by the host) share a sub-token and stride over its elements.
 template <typename E>
@@ -274,6 +327,14 @@ hipError_t compress_any(const void* X, const float* v, void* S, int64_t n_sub, i
     }
     if constexpr (std::is_same<E, Bf16Elem>::value) {
         // a multiple of 4 but not of 8 (the 11008-wide layer at 64 sub-tokens per token: d = 172): 8-byte vectors
+        if (vec_ok && d % 8 == 4 && d / 4 >= 33 && d / 4 <= 64 && n_sub % 2 == 0) {
+            constexpr int U = 8;
+            const int64_t n_pairs = n_sub / 2;
+            const int grid = grid_for(ceil_div(n_pairs, static_cast<int64_t>(U)), kBlock / kWave, cfg.max_blocks);
+            hipLaunchKernelGGL((compress_pair_kernel<U>), dim3(grid), dim3(kBlock), 0, st, static_cast<const uint4*>(X), v,
+                               static_cast<uint16_t*>(S), n_pairs, static_cast<int>(d / 4), static_cast<int>(d));
+            return hipGetLastError();
+        }
         if (d % 4 == 0 && (reinterpret_cast<uintptr_t>(X) & 7) == 0) {
             bool handled = false;
             hipError_t e = dispatch_compress_vec<Bf16Half>(static_cast<int>(d / 4), X, v, S, n_sub, cfg, st, &handled);

@@ -42,6 +42,11 @@ COMPRESS_CASES = [
     # bf16 sub-token sizes that are a multiple of 4 but not of 8: 8-byte vectors
     (97, 2 * 172, 172, wl.BF16), (150, 11008, 172, wl.BF16), (203, 5 * 4, 4, wl.BF16), (131, 3 * 20, 20, wl.BF16),
     (45, 2 * 1028, 1028, wl.BF16), (64, 11008, 1376, wl.BF16), (64, 11008, 688, wl.BF16),
+    # ... of 132 to 256 elements are taken in pairs (a pair is d / 4 whole 16-byte vectors): the smallest
+    # and the largest such d, a number of pairs that is not a multiple of the eight a wave takes, one pair,
+    # and an odd number of sub-tokens (which stays with the 8-byte kernel)
+    (5, 10 * 132, 132, wl.BF16), (7, 10 * 252, 252, wl.BF16), (37, 6 * 172, 172, wl.BF16), (1, 2 * 172, 172, wl.BF16),
+    (3, 3 * 172, 172, wl.BF16), (9, 2 * 260, 260, wl.BF16),
     # generic kernel: d not a power of two times the vector width, d = 1, d = D
     (50, 60, 12, wl.BF16), (50, 63, 7, wl.F32), (31, 33, 1, wl.BF16), (17, 100, 100, wl.F32),
     (11, 3000, 3000, wl.BF16), (1, 8, 8, wl.BF16), (1, 1, 1, wl.F32),
