@@ -17,6 +17,7 @@
 //   wgrad_partial_mfma_kernel      1 tile; 5-6 tiles when the blocks need several rounds; 8-byte G loads;
 //                                  S that is not 16-byte aligned or has an odd element count
 //   wgrad_partial_ws_kernel        2-3 tiles: loader waves + computing waves, 128-token chunks through LDS
+//   wgrad_partial_ws256_kernel     2-3 tiles on more than 8192 output features: the same on 256-feature tiles
 //   wgrad_partial_ws64_kernel      4 tiles, and 5-6 when every block is resident at once: 64-token chunks
 //   wgrad_partial_shared_g_kernel  8, 12, 16 tiles (M up to 256; larger M in chunks of 256)
 //   wgrad_partial_simple_kernel    float32 inputs and whatever the MFMA kernels cannot take
@@ -775,6 +776,179 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t*
 }
 
 // ---------------------------------------------------------------------------
+// Kernel 1, loader waves on a 256-feature tile (two or three group tiles).
+//
+// The same division of labour as wgrad_partial_ws64_kernel, with twice the features per block: a chunk
+// is 64 tokens x 256 features of G (32 KB) plus those tokens' rows of S, and each of the four computing
+// waves takes one 32-token step of it and one 128-feature half (eight column tiles, as in the 128-wide
+// kernel).  S is fetched once per 256 output features instead of once per 128: with 43 sub-tokens per
+// token that takes the S share of a block's cache-line requests from 27 % to 16 %, and the partial
+// kernels are bound by the number of requests a compute unit can keep in flight.  The price is twice the
+// token ranges for the same number of blocks (twice the partial sums written here and read back by the
+// expansion), which is why this pays at two and three tiles and not beyond.
+// grid = (o tiles of 256, splits); 512 threads; 3 slots x (32 KB + 4 or 8 KB) of dynamic LDS.
+// ---------------------------------------------------------------------------
+constexpr int kWs256GBytes = kWs64Rows * 512;
+constexpr size_t ws256_kernel_lds_bytes(int gt) { return static_cast<size_t>(kWsSlots) * (kWs256GBytes + ws64_s_kb4(gt) * 4096); }
+
+template <int GT>
+__global__ __launch_bounds__(512) void wgrad_partial_ws256_kernel(const uint16_t* __restrict__ G,
+                                                                 const uint16_t* __restrict__ S,
+                                                                 float* __restrict__ partial, int64_t N, int64_t O,
+                                                                 int64_t M, int64_t Mp, int64_t rows_per_split,
+                                                                 int cyclic, int tau_mode) {
+    constexpr int OT = 256, CH = 8;                       // CH: column tiles per computing wave
+    constexpr int NS = ws64_s_kb4(GT);                    // S loads per loader wave and chunk
+    constexpr int kSlotBytes = kWs256GBytes + NS * 4096;
+    constexpr int kLoadsPerChunk = 8 + NS;
+    static_assert(static_cast<size_t>(2) * GT * CH * kWave * sizeof(f32x4) <= ws256_kernel_lds_bytes(GT),
+                  "the cross-wave sum reuses the ring");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const bool loader = w < 4;
+    const int mw = w - 4;
+    const int step = mw & 1, half = (mw >> 1) & 1;
+    const int q = lane >> 4;
+    const int jj = lane & 15;
+    const int64_t o0 = static_cast<int64_t>(blockIdx.x) * OT;
+    const int split = blockIdx.y;
+    const int splits = gridDim.y;
+    // the planner's ranges are multiples of 128 tokens; here a chunk is 64, two per 128
+    int64_t row0, span_rows;
+    int n_chunks;
+    uint32_t pair_stride;                                 // rows from one 128-token pair of chunks to the next
+    if (cyclic) {
+        const int64_t total_pairs = ceil_div(N, 128);
+        row0 = static_cast<int64_t>(split) * 128;
+        span_rows = N - row0;
+        n_chunks = 2 * static_cast<int>((total_pairs - split + splits - 1) / splits);
+        pair_stride = static_cast<uint32_t>(splits) * 128u;
+    } else {
+        row0 = static_cast<int64_t>(split) * rows_per_split;
+        span_rows = N - row0 < rows_per_split ? N - row0 : rows_per_split;
+        n_chunks = 2 * static_cast<int>(ceil_div(span_rows, 128));
+        pair_stride = 128u;
+    }
+    if (span_rows <= 0) { n_chunks = 0; span_rows = 0; }
+    auto chunk_row = [&](int i) -> uint32_t { return static_cast<uint32_t>(i >> 1) * pair_stride + static_cast<uint32_t>(i & 1) * 64u; };
+    constexpr uint32_t kLaneOut = 0x7FFFFFFFu, kStepOut = 0x80000000u;
+    const uint32_t row_bytes = static_cast<uint32_t>(O) * 2u;
+    const uint32_t s_row_bytes = static_cast<uint32_t>(M) * 2u;
+
+    // loader wave w, instruction r: rows 16 w + 2 r + (lane / 32) of the chunk, 16 bytes at (lane % 32) * 16 of
+    // the 512-byte row piece; LDS-direct loads land lane after lane, i.e. as [row][512 bytes]
+    const int lrow = lane >> 5, lcol = lane & 31;
+    const bool col_ok = o0 + lcol * 8 < O;
+    const uint32_t voff_g0 =
+        col_ok ? static_cast<uint32_t>(16 * (w & 3) + lrow) * row_bytes + static_cast<uint32_t>(lcol * 16) : kLaneOut;
+    const uint32_t voff_gstep = col_ok ? 2u * row_bytes : 0u;
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(G) + (row0 * O + o0) * 2), 0,
+        static_cast<int>(static_cast<uint32_t>(span_rows) * row_bytes - (span_rows > 0 ? static_cast<uint32_t>(o0 * 2) : 0u)),
+        0x00020000);
+    const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(S) + row0 * M * 2), 0,
+        static_cast<int>(static_cast<uint32_t>(span_rows) * s_row_bytes), 0x00020000);
+    auto issue_chunk = [&](int i) {
+        char* slot = lds + (i % kWsSlots) * kSlotBytes;
+        const bool real = i < n_chunks;
+        const uint32_t g_off = real ? chunk_row(i) * row_bytes : kStepOut;
+        const uint32_t s_off = real ? chunk_row(i) * s_row_bytes : kStepOut;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(g_rsrc, (lds_void_ptr)(slot + (16 * (w & 3) + 2 * r) * 512), 16,
+                                                     voff_g0 + r * voff_gstep + g_off, 0, 0, kStreamAux);
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+            const uint32_t kb = static_cast<uint32_t>((w & 3) + 4 * t);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(s_rsrc, (lds_void_ptr)(slot + kWs256GBytes + kb * 1024), 16,
+                                                     kb * 1024u + static_cast<uint32_t>(lane) * 16u + s_off, 0, 0, 0);
+        }
+    };
+
+    f32x4 acc[GT][CH];
+#pragma unroll
+    for (int a = 0; a < GT; ++a)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int g_lds[8], s_lds[8];                               // token_of_slot: which token sits in K slot (q, e)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int tok = 32 * step + token_of_slot(tau_mode, q, e);
+        g_lds[e] = tok * 512 + jj * 32 + half * 16;
+        s_lds[e] = kWs256GBytes + (tok * static_cast<int>(M) + jj) * 2;
+    }
+    const bool last_tile_ok = (GT - 1) * 16 + jj < M;
+
+    // the two role loops and their barriers: as in wgrad_partial_ws_kernel
+    if (loader) {
+        issue_chunk(0);
+        issue_chunk(1);
+        for (int i = 0; i < n_chunks; ++i) {
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (kLoadsPerChunk & 15) | ((kLoadsPerChunk >> 4) << 14));
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue_chunk(i + 2);
+        }
+    } else {
+        for (int i = 0; i < n_chunks; ++i) {
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const int slot_off = (i % kWsSlots) * kSlotBytes;
+            RawRow<4> rows[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const uint4 x = *reinterpret_cast<const uint4*>(lds + slot_off + g_lds[r]);
+                rows[r].w[0] = x.x; rows[r].w[1] = x.y; rows[r].w[2] = x.z; rows[r].w[3] = x.w;
+            }
+            bf16x8 gf[CH];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) gf[c] = column_fragment(rows, c);
+#pragma unroll
+            for (int a = 0; a < GT; ++a) {
+                uint32_t sv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sv[e] = *reinterpret_cast<const uint16_t*>(lds + slot_off + s_lds[e] + a * 32);
+                uint4 f = make_uint4(__builtin_amdgcn_perm(sv[1], sv[0], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[3], sv[2], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[5], sv[4], 0x05040100u),
+                                     __builtin_amdgcn_perm(sv[7], sv[6], 0x05040100u));
+                if (a == GT - 1 && !last_tile_ok) f = make_uint4(0u, 0u, 0u, 0u);
+                const bf16x8 sf = __builtin_bit_cast(bf16x8, f);
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
+            }
+        }
+    }
+    if (loader) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+
+    // step 0 + step 1 for each half of the features; the step-0 waves store.  Lane jj's column tile c of
+    // half h is feature o0 + 16 jj + 8 h + c (the 32-byte piece a lane reads holds sixteen features).
+    constexpr int NT = GT * CH;
+    f32x4 (*red)[NT][kWave] = reinterpret_cast<f32x4 (*)[NT][kWave]>(lds);
+    float* out = partial + static_cast<int64_t>(split) * O * Mp;
+    if (!loader && step == 1) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) red[half][i][lane] = acc[i / CH][i % CH];
+    }
+    __syncthreads();
+    if (!loader && step == 0) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const int a = i / CH, c = i % CH;
+            const f32x4 t = acc[a][c] + red[half][i][lane];
+            store_tile<16>(out, t, o0, jj, q, half * CH + c, a * 16, O, Mp);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Kernel 1, MFMA path for many group tiles (8, 12 or 16 per block).
 //
 // With that many tiles a wave cannot hold accumulators for all of them, so the
@@ -1327,6 +1501,21 @@ Tiling tiling_for(int64_t M) {
 // issue slots than the packing pre-pass does time) or the packed fragment array.
 bool direct_s(const Tiling& t) { return !t.shared && t.gt <= 3; }
 
+// Two and three group tiles on many output features: blocks of 256 features (wgrad_partial_ws256_kernel).
+// Halving the S fetches costs twice the token ranges, i.e. twice the partial sums written and read back.
+// Measured on whole calls, N = 16384: O = 11008, M = 32: 92.6 against 99.8 us; O = 13824, M = 20: 119.8
+// against 128.5 us; but O = 4096, M = 43: 58.9 against 58.1 us and O = 5120, M = 20: 52.8 against 51.4 us
+// (the partial kernel gains 1.3 us, the expansion of 16 ranges instead of 8 loses 1.6).  Hence only
+// where 128-feature tiles alone outnumber a quarter of the compute units, so that the narrow layout has
+// at most three ranges and needs several rounds of blocks.  The planner counts blocks accordingly; a
+// call that cannot take the wide kernel (alignment) runs the 128-feature kernels on the same ranges.
+// (measurement builds: VELORA_WGRAD_WIDE=0 never, 2 for every two- and three-tile call)
+bool wide_tiles(const Tiling& t, int64_t O, int num_cus) {
+    const int mode = env_int("VELORA_WGRAD_WIDE", 1);
+    if (t.shared || (t.gt != 2 && t.gt != 3) || mode == 0) return false;
+    return mode == 2 || ceil_div(O, 128) * 4 > num_cus;
+}
+
 MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, int s_align, const WgradPlan& plan) {
     MfmaChoice ch{0, 0, 4, 0, false, s_align >= 16};
     const Tiling tl = tiling_for(M);
@@ -1413,6 +1602,27 @@ hipError_t launch_ws64(const void* G, const void* S, float* partial, int64_t N, 
     return hipGetLastError();
 }
 
+template <int GT>
+hipError_t launch_ws256(const void* G, const void* S, float* partial, int64_t N, int64_t O, int64_t M,
+                        const WgradPlan& plan, hipStream_t st) {
+    static std::atomic<bool> allowed[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const size_t lds_bytes = ws256_kernel_lds_bytes(GT);
+    if (dev < 0 || dev >= 64 || !allowed[dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_ws256_kernel<GT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) allowed[dev].store(true, std::memory_order_release);
+    }
+    dim3 grid(static_cast<unsigned>(ceil_div(O, 256)), static_cast<unsigned>(plan.splits), 1);
+    hipLaunchKernelGGL((wgrad_partial_ws256_kernel<GT>), grid, dim3(512), lds_bytes, st, static_cast<const uint16_t*>(G),
+                       static_cast<const uint16_t*>(S), partial, N, O, M, plan.Mp, plan.rows_per_split,
+                       plan.cyclic ? 1 : 0, pick_tau_mode(M));
+    return hipGetLastError();
+}
+
 #define VELORA_MFMA_CASE(CW, GT, NST, DIRECT) \
     if (ch.cw == CW && ch.gt == GT)           \
         return launch_mfma<CW, GT, NST, DIRECT>(G, s_operand, partial, N, O, M, plan, ch.chunks, st);
@@ -1448,6 +1658,10 @@ hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_oper
     if (ch.cw == 8 && ch.gt <= 3 && (ch.gt >= 2 || ws_mode == 2) && ch.s_align16 && plan.tiles_packed == 0 &&
         (N * M) % 2 == 0 && ws_mode != 0) {
         if (ch.gt == 1) return launch_ws<1>(G, s_operand, partial, N, O, M, plan, st);
+        if (wide_tiles(tiling_for(M), O, plan.num_cus)) {
+            if (ch.gt == 2) return launch_ws256<2>(G, s_operand, partial, N, O, M, plan, st);
+            return launch_ws256<3>(G, s_operand, partial, N, O, M, plan, st);
+        }
         if (ch.gt == 2) return launch_ws<2>(G, s_operand, partial, N, O, M, plan, st);
         return launch_ws<3>(G, s_operand, partial, N, O, M, plan, st);
     }
@@ -1564,7 +1778,7 @@ WgradPlan plan_wgrad_uncached(int64_t N, int64_t O, int64_t D, int64_t M, bool i
     Tiling tl{1, 4, false, 1};
     if (is_bf16) tl = tiling_for(M);
     const int gt = tl.gt;
-    const int64_t o_tiles = ceil_div(O, 128) * tl.chunks;
+    const int64_t o_tiles = (is_bf16 && wide_tiles(tl, O, cfg.num_cus) ? ceil_div(O, 256) : ceil_div(O, 128)) * tl.chunks;
     // Each split writes a partial tile that the second kernel reads back.
     const double per_split = static_cast<double>(O) * p.Mp * 8.0;
     const int64_t min_rows = is_bf16 ? 256 : 32;   // the plain-FMA kernel is latency-bound per token

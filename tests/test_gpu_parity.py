@@ -257,6 +257,12 @@ WGRAD_CASES = [
     (385, 128, 752, 16, wl.BF16),                # M = 47, N * M odd
     (40000, 128, 272, 16, wl.BF16),              # M = 17: 313 chunks, more than two per split
     (33000, 256, 1376, 32, wl.BF16),             # M = 43, ragged last chunk
+    # two and three tiles on more than 8192 output features run on 256-feature blocks: output widths around
+    # that tile, one that is not a multiple of 8 (per-wave kernel on the same token ranges), and a long
+    # token axis (tens of chunks per block)
+    (300, 8456, 1376, 32, wl.BF16), (1000, 8448, 640, 32, wl.BF16), (200, 8440, 1024, 32, wl.BF16),   # M = 43, 20, 32
+    (310, 8260, 768, 32, wl.BF16),               # M = 24, O % 8 != 0
+    (8000, 8200, 544, 32, wl.BF16),              # M = 17
     # four group tiles: the loader-wave kernel with 64-token chunks and the features split over two waves
     (63, 128, 1568, 32, wl.BF16), (64, 72, 2048, 32, wl.BF16), (65, 264, 2016, 32, wl.BF16),   # M = 49, 64, 63
     (1000, 136, 416, 8, wl.BF16),                # M = 52
