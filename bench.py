@@ -346,6 +346,30 @@ def _linear_record(vl, torch, sh, v, dev, launches):
     return rec
 
 
+def _dense_form_record(vl, torch, sh, v, dev, launches):
+    """The backward of paper Listing 1 as printed, for comparison with the factored weight gradient (not part
+    of `value`): Xhat = reconstruct(S, v) materialised by velora_reconstruct, then the dense product
+    dW = G^T Xhat in the vendor GEMM (bf16 in, bf16 out).  `gemm_only_us` is what any kernel that builds the
+    tiles of Xhat on the fly instead would still have to spend at the vendor GEMM's rate on this shape: d times
+    the flops of the factored form."""
+    launches = max(5, min(launches, 20))
+    G = (torch.randn((sh.N, sh.O), device=dev) * 0.05).to(torch.bfloat16)
+    S = torch.randn((sh.N, sh.M), device=dev).to(torch.bfloat16)
+    Xhat = torch.empty((sh.N, sh.D), device=dev, dtype=torch.bfloat16)
+    dWd = torch.empty((sh.O, sh.D), device=dev, dtype=torch.bfloat16)
+    Gt = G.t()
+    vl.velora_reconstruct(S, v, sh.D, Xhat=Xhat)
+    gemm = _event_avg_us(torch, lambda i: torch.matmul(Gt, Xhat, out=dWd), launches)
+    both = _event_avg_us(torch, lambda i: (vl.velora_reconstruct(S, v, sh.D, Xhat=Xhat),
+                                           torch.matmul(Gt, Xhat, out=dWd)), launches)
+    flops = sh.wgrad_flops_dense()
+    return {"what": "velora_reconstruct + vendor GEMM G^T Xhat (bf16 out)", "reconstruct_plus_gemm_us": round(both, 1),
+            "gemm_only_us": round(gemm, 1), "gemm_TFLOPs": round(flops / gemm * 1e-6, 1),
+            "gemm_frac_mfma": round(flops / gemm * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "gemm_time_at_mfma_peak_us": round(flops / MFMA_BF16_PEAK_TFLOPS * 1e-6, 1),
+            "materialised_MB": round(sh.N * sh.D * 2 / 1e6, 1)}
+
+
 def _mlp_block_record(torch, dev):
     """A whole LLaMA-7B-like gated MLP block (hidden 4096, intermediate 11008, 16384 tokens, bf16), forward +
     backward through autograd: the plain block against the same block with VeLoRA on its three projections
@@ -694,6 +718,8 @@ def main():
         out["rmsnorm_compress"] = _rmsnorm_record(vl, torch, wl, dev, args.steps)
         torch.cuda.empty_cache()
         out["linear_compress"] = _linear_record(vl, torch, sh, v, dev, args.steps)
+        torch.cuda.empty_cache()
+        out["weight_grad"]["dense_form"] = _dense_form_record(vl, torch, sh, v, dev, args.steps)
         torch.cuda.empty_cache()
         out["mlp_block"] = _mlp_block_record(torch, dev)
     torch.cuda.empty_cache()
