@@ -17,7 +17,7 @@
 //   wgrad_partial_mfma_kernel      1 tile; 5-6 tiles when the blocks need several rounds; 8-byte G loads;
 //                                  S that is not 16-byte aligned or has an odd element count
 //   wgrad_partial_ws_kernel        2-3 tiles: loader waves + computing waves, 128-token chunks through LDS
-//   wgrad_partial_ws256_kernel     2-3 tiles on more than 8192 output features: the same on 256-feature tiles
+//   wgrad_partial_ws256_kernel     1-3 tiles on more than 8192 output features: the same on 256-feature tiles
 //   wgrad_partial_ws64_kernel      4 tiles, and 5-6 when every block is resident at once: 64-token chunks
 //   wgrad_partial_shared_g_kernel  8, 12, 16 tiles (M up to 256; larger M in chunks of 256)
 //   wgrad_partial_simple_kernel    float32 inputs and whatever the MFMA kernels cannot take
@@ -776,7 +776,7 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t*
 }
 
 // ---------------------------------------------------------------------------
-// Kernel 1, loader waves on a 256-feature tile (two or three group tiles).
+// Kernel 1, loader waves on a 256-feature tile (one to three group tiles).
 //
 // The same division of labour as wgrad_partial_ws64_kernel, with twice the features per block: a chunk
 // is 64 tokens x 256 features of G (32 KB) plus those tokens' rows of S, and each of the four computing
@@ -785,7 +785,7 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t*
 // token that takes the S share of a block's cache-line requests from 27 % to 16 %, and the partial
 // kernels are bound by the number of requests a compute unit can keep in flight.  The price is twice the
 // token ranges for the same number of blocks (twice the partial sums written here and read back by the
-// expansion), which is why this pays at two and three tiles and not beyond.
+// expansion), which is why this pays only on wide outputs, where the 128-feature layout has few ranges.
 // grid = (o tiles of 256, splits); 512 threads; 3 slots x (32 KB + 4 or 8 KB) of dynamic LDS.
 // ---------------------------------------------------------------------------
 constexpr int kWs256GBytes = kWs64Rows * 512;
@@ -1501,18 +1501,19 @@ Tiling tiling_for(int64_t M) {
 // issue slots than the packing pre-pass does time) or the packed fragment array.
 bool direct_s(const Tiling& t) { return !t.shared && t.gt <= 3; }
 
-// Two and three group tiles on many output features: blocks of 256 features (wgrad_partial_ws256_kernel).
+// Up to three group tiles on many output features: blocks of 256 features (wgrad_partial_ws256_kernel).
 // Halving the S fetches costs twice the token ranges, i.e. twice the partial sums written and read back.
 // Measured on whole calls, N = 16384: O = 11008, M = 32: 92.6 against 99.8 us; O = 13824, M = 20: 119.8
-// against 128.5 us; but O = 4096, M = 43: 58.9 against 58.1 us and O = 5120, M = 20: 52.8 against 51.4 us
-// (the partial kernel gains 1.3 us, the expansion of 16 ranges instead of 8 loses 1.6).  Hence only
-// where 128-feature tiles alone outnumber a quarter of the compute units, so that the narrow layout has
-// at most three ranges and needs several rounds of blocks.  The planner counts blocks accordingly; a
-// call that cannot take the wide kernel (alignment) runs the 128-feature kernels on the same ranges.
-// (measurement builds: VELORA_WGRAD_WIDE=0 never, 2 for every two- and three-tile call)
+// against 128.5 us; O = 11008, M = 16: 89.6 against 93.5 us; but O = 4096, M = 43: 58.9 against 58.1 us,
+// O = 5120, M = 20: 52.8 against 51.4 us (the partial kernel gains 1.3 us, the expansion of 16 ranges
+// instead of 8 loses 1.6) and O = 2048, M = 6, N = 65536: 55.9 against 49.4 us.  Hence only where
+// 128-feature tiles alone outnumber a quarter of the compute units, so that the narrow layout has at
+// most three ranges and needs several rounds of blocks.  The planner counts blocks accordingly; a call
+// that cannot take the wide kernel (alignment) runs the 128-feature kernels on the same ranges.
+// (measurement builds: VELORA_WGRAD_WIDE=0 never, 2 for every call with up to three tiles)
 bool wide_tiles(const Tiling& t, int64_t O, int num_cus) {
     const int mode = env_int("VELORA_WGRAD_WIDE", 1);
-    if (t.shared || (t.gt != 2 && t.gt != 3) || mode == 0) return false;
+    if (t.shared || t.gt > 3 || mode == 0) return false;
     return mode == 2 || ceil_div(O, 128) * 4 > num_cus;
 }
 
@@ -1655,13 +1656,15 @@ hipError_t dispatch_mfma(const MfmaChoice& ch, const void* G, const void* s_oper
     // M = 16) and stays; with two or three the split is worth 2-6 us (29.0 against 30.8 us on O = 4096,
     // M = 43; 78.5 against 84.4 us on O = 13824, M = 20).
     const int ws_mode = env_int("VELORA_WGRAD_WS", 1);   // measurement builds: 0 never, 2 also for one tile
-    if (ch.cw == 8 && ch.gt <= 3 && (ch.gt >= 2 || ws_mode == 2) && ch.s_align16 && plan.tiles_packed == 0 &&
+    const bool wide = wide_tiles(tiling_for(M), O, plan.num_cus);
+    if (ch.cw == 8 && ch.gt <= 3 && (ch.gt >= 2 || ws_mode == 2 || wide) && ch.s_align16 && plan.tiles_packed == 0 &&
         (N * M) % 2 == 0 && ws_mode != 0) {
-        if (ch.gt == 1) return launch_ws<1>(G, s_operand, partial, N, O, M, plan, st);
-        if (wide_tiles(tiling_for(M), O, plan.num_cus)) {
+        if (wide) {
+            if (ch.gt == 1) return launch_ws256<1>(G, s_operand, partial, N, O, M, plan, st);
             if (ch.gt == 2) return launch_ws256<2>(G, s_operand, partial, N, O, M, plan, st);
             return launch_ws256<3>(G, s_operand, partial, N, O, M, plan, st);
         }
+        if (ch.gt == 1) return launch_ws<1>(G, s_operand, partial, N, O, M, plan, st);
         if (ch.gt == 2) return launch_ws<2>(G, s_operand, partial, N, O, M, plan, st);
         return launch_ws<3>(G, s_operand, partial, N, O, M, plan, st);
     }
