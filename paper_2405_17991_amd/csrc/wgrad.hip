@@ -17,7 +17,7 @@
 //   wgrad_partial_mfma_kernel      1 tile; 5-6 tiles when the blocks need several rounds; 8-byte G loads;
 //                                  S that is not 16-byte aligned or has an odd element count
 //   wgrad_partial_ws_kernel        2-3 tiles: loader waves + computing waves, 128-token chunks through LDS
-//   wgrad_partial_ws256_kernel     1-3 tiles on more than 8192 output features: the same on 256-feature tiles
+//   wgrad_partial_ws256_kernel     1-5 tiles on more than 8192 output features: the same on 256-feature tiles
 //   wgrad_partial_ws64_kernel      4 tiles, and 5-6 when every block is resident at once: 64-token chunks
 //   wgrad_partial_shared_g_kernel  8, 12, 16 tiles (M up to 256; larger M in chunks of 256)
 //   wgrad_partial_simple_kernel    float32 inputs and whatever the MFMA kernels cannot take
@@ -407,7 +407,7 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 // pair dq = 8, 1, 2 or 4 tokens apart; the host picks the one whose distance is nearest to 64 bytes
 // mod 128 (measured at M = 80, O = 5120: 37.5 us with dq = 8, 35.4 us with dq = 2).  A power-of-two
 // M >= 64 collides under every map.
-__device__ __forceinline__ int token_of_slot(int mode, int q, int e) {
+__host__ __device__ constexpr int token_of_slot(int mode, int q, int e) {
     switch (mode) {
         case 1: return q + 4 * e;
         case 2: return 2 * (q & 1) + (q >> 1) + 4 * e;
@@ -415,6 +415,20 @@ __device__ __forceinline__ int token_of_slot(int mode, int q, int e) {
         default: return 8 * q + e;
     }
 }
+// Every map has the form token(q, 0) + (e & 1) * s1 + (e >> 1) * s2 with s1, s2 the same for all lanes, so a
+// kernel short of registers can keep one per-lane base and eight wave-uniform offsets instead of eight
+// per-lane addresses.
+constexpr bool token_maps_are_affine() {
+    for (int mode = 0; mode < 4; ++mode) {
+        const int s1 = token_of_slot(mode, 0, 1) - token_of_slot(mode, 0, 0);
+        const int s2 = token_of_slot(mode, 0, 2) - token_of_slot(mode, 0, 0);
+        for (int q = 0; q < 4; ++q)
+            for (int e = 0; e < 8; ++e)
+                if (token_of_slot(mode, q, e) != token_of_slot(mode, q, 0) + (e & 1) * s1 + (e >> 1) * s2) return false;
+    }
+    return true;
+}
+static_assert(token_maps_are_affine(), "token_of_slot: base per lane + uniform offsets");
 
 template <int GT>
 __global__ __launch_bounds__(512) void wgrad_partial_ws_kernel(const uint16_t* __restrict__ G,
@@ -776,7 +790,7 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t*
 }
 
 // ---------------------------------------------------------------------------
-// Kernel 1, loader waves on a 256-feature tile (one to three group tiles).
+// Kernel 1, loader waves on a 256-feature tile (one to five group tiles).
 //
 // The same division of labour as wgrad_partial_ws64_kernel, with twice the features per block: a chunk
 // is 64 tokens x 256 features of G (32 KB) plus those tokens' rows of S, and each of the four computing
@@ -786,7 +800,7 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws64_kernel(const uint16_t*
 // kernels are bound by the number of requests a compute unit can keep in flight.  The price is twice the
 // token ranges for the same number of blocks (twice the partial sums written here and read back by the
 // expansion), which is why this pays only on wide outputs, where the 128-feature layout has few ranges.
-// grid = (o tiles of 256, splits); 512 threads; 3 slots x (32 KB + 4 or 8 KB) of dynamic LDS.
+// grid = (o tiles of 256, splits); 512 threads; 3 slots x (32 KB + 4, 8 or 12 KB) of dynamic LDS.
 // ---------------------------------------------------------------------------
 constexpr int kWs256GBytes = kWs64Rows * 512;
 constexpr size_t ws256_kernel_lds_bytes(int gt) { return static_cast<size_t>(kWsSlots) * (kWs256GBytes + ws64_s_kb4(gt) * 4096); }
@@ -798,6 +812,7 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws256_kernel(const uint16_t
                                                                  int64_t M, int64_t Mp, int64_t rows_per_split,
                                                                  int cyclic, int tau_mode) {
     constexpr int OT = 256, CH = 8;                       // CH: column tiles per computing wave
+    constexpr bool kTwoBatches = GT >= 5;
     constexpr int NS = ws64_s_kb4(GT);                    // S loads per loader wave and chunk
     constexpr int kSlotBytes = kWs256GBytes + NS * 4096;
     constexpr int kLoadsPerChunk = 8 + NS;
@@ -873,12 +888,20 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws256_kernel(const uint16_t
     for (int a = 0; a < GT; ++a)
 #pragma unroll
         for (int c = 0; c < CH; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    int g_lds[8], s_lds[8];                               // token_of_slot: which token sits in K slot (q, e)
+    // token_of_slot: which token sits in K slot (q, e).  One per-lane base each for G and S plus eight
+    // wave-uniform offsets (scalar registers): eight per-lane addresses each would not fit beside the
+    // accumulators of five tiles.
+    const int tok_s1 = token_of_slot(tau_mode, 0, 1) - token_of_slot(tau_mode, 0, 0);
+    const int tok_s2 = token_of_slot(tau_mode, 0, 2) - token_of_slot(tau_mode, 0, 0);
+    const int tok0 = 32 * step + token_of_slot(tau_mode, q, 0);
+    const int g_lds0 = tok0 * 512 + jj * 32 + half * 16;
+    const int s_lds0 = kWs256GBytes + (tok0 * static_cast<int>(M) + jj) * 2;
+    int g_lds[8], s_lds[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const int tok = 32 * step + token_of_slot(tau_mode, q, e);
-        g_lds[e] = tok * 512 + jj * 32 + half * 16;
-        s_lds[e] = kWs256GBytes + (tok * static_cast<int>(M) + jj) * 2;
+        const int dt = __builtin_amdgcn_readfirstlane((e & 1) * tok_s1 + (e >> 1) * tok_s2);
+        g_lds[e] = dt * 512;
+        s_lds[e] = dt * static_cast<int>(M) * 2;
     }
     const bool last_tile_ok = (GT - 1) * 16 + jj < M;
 
@@ -899,29 +922,56 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws256_kernel(const uint16_t
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             const int slot_off = (i % kWsSlots) * kSlotBytes;
-            RawRow<4> rows[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const uint4 x = *reinterpret_cast<const uint4*>(lds + slot_off + g_lds[r]);
-                rows[r].w[0] = x.x; rows[r].w[1] = x.y; rows[r].w[2] = x.z; rows[r].w[3] = x.w;
-            }
-            bf16x8 gf[CH];
-#pragma unroll
-            for (int c = 0; c < CH; ++c) gf[c] = column_fragment(rows, c);
-#pragma unroll
-            for (int a = 0; a < GT; ++a) {
+            const char* g_base = lds + (slot_off + g_lds0);
+            const char* s_base = lds + (slot_off + s_lds0);
+            auto s_fragment = [&](int a) -> bf16x8 {
                 uint32_t sv[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) sv[e] = *reinterpret_cast<const uint16_t*>(lds + slot_off + s_lds[e] + a * 32);
+                for (int e = 0; e < 8; ++e) sv[e] = *reinterpret_cast<const uint16_t*>(s_base + s_lds[e] + a * 32);
                 uint4 f = make_uint4(__builtin_amdgcn_perm(sv[1], sv[0], 0x05040100u),
                                      __builtin_amdgcn_perm(sv[3], sv[2], 0x05040100u),
                                      __builtin_amdgcn_perm(sv[5], sv[4], 0x05040100u),
                                      __builtin_amdgcn_perm(sv[7], sv[6], 0x05040100u));
                 if (a == GT - 1 && !last_tile_ok) f = make_uint4(0u, 0u, 0u, 0u);
-                const bf16x8 sf = __builtin_bit_cast(bf16x8, f);
+                return __builtin_bit_cast(bf16x8, f);
+            };
+            if constexpr (!kTwoBatches) {
+                RawRow<4> rows[8];
 #pragma unroll
-                for (int c = 0; c < CH; ++c)
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
+                for (int r = 0; r < 8; ++r) {
+                    const uint4 x = *reinterpret_cast<const uint4*>(g_base + g_lds[r]);
+                    rows[r].w[0] = x.x; rows[r].w[1] = x.y; rows[r].w[2] = x.z; rows[r].w[3] = x.w;
+                }
+                bf16x8 gf[CH];
+#pragma unroll
+                for (int c = 0; c < CH; ++c) gf[c] = column_fragment(rows, c);
+#pragma unroll
+                for (int a = 0; a < GT; ++a) {
+                    const bf16x8 sf = s_fragment(a);
+#pragma unroll
+                    for (int c = 0; c < CH; ++c)
+                        acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][c], 0, 0, 0);
+                }
+            } else {
+                // five tiles: 160 accumulator registers leave no room for eight G fragments and their rows at
+                // once (two waves per SIMD, 256 registers each), so the S fragments are formed first and the
+                // wave's eight column tiles go through in two batches of four
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) {
+                    uint2 rows[8];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) rows[r] = *reinterpret_cast<const uint2*>(g_base + g_lds[r] + cb * 8);
+                    bf16x8 gf[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) gf[c] = column_fragment4(rows, c);
+#pragma unroll
+                    for (int a = 0; a < GT; ++a) {
+                        const bf16x8 sf = s_fragment(a);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            acc[a][cb * 4 + c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, gf[c], acc[a][cb * 4 + c], 0, 0, 0);
+                    }
+                }
             }
         }
     }
@@ -933,17 +983,22 @@ __global__ __launch_bounds__(512) void wgrad_partial_ws256_kernel(const uint16_t
     constexpr int NT = GT * CH;
     f32x4 (*red)[NT][kWave] = reinterpret_cast<f32x4 (*)[NT][kWave]>(lds);
     float* out = partial + static_cast<int64_t>(split) * O * Mp;
+    // The lane's index once more, from the hardware and behind the loop: carried across the loop, it and
+    // what is derived from it are the registers that five tiles' accumulators leave no room for.
+    int lane_e;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_e));
+    const int q_e = lane_e >> 4, jj_e = lane_e & 15;
     if (!loader && step == 1) {
 #pragma unroll
-        for (int i = 0; i < NT; ++i) red[half][i][lane] = acc[i / CH][i % CH];
+        for (int i = 0; i < NT; ++i) red[half][i][lane_e] = acc[i / CH][i % CH];
     }
     __syncthreads();
     if (!loader && step == 0) {
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
             const int a = i / CH, c = i % CH;
-            const f32x4 t = acc[a][c] + red[half][i][lane];
-            store_tile<16>(out, t, o0, jj, q, half * CH + c, a * 16, O, Mp);
+            const f32x4 t = acc[a][c] + red[half][i][lane_e];
+            store_tile<16>(out, t, o0, jj_e, q_e, half * CH + c, a * 16, O, Mp);
         }
     }
 }
@@ -1501,19 +1556,21 @@ Tiling tiling_for(int64_t M) {
 // issue slots than the packing pre-pass does time) or the packed fragment array.
 bool direct_s(const Tiling& t) { return !t.shared && t.gt <= 3; }
 
-// Up to three group tiles on many output features: blocks of 256 features (wgrad_partial_ws256_kernel).
+// Up to five group tiles on many output features: blocks of 256 features (wgrad_partial_ws256_kernel).
 // Halving the S fetches costs twice the token ranges, i.e. twice the partial sums written and read back.
 // Measured on whole calls, N = 16384: O = 11008, M = 32: 92.6 against 99.8 us; O = 13824, M = 20: 119.8
-// against 128.5 us; O = 11008, M = 16: 89.6 against 93.5 us; but O = 4096, M = 43: 58.9 against 58.1 us,
-// O = 5120, M = 20: 52.8 against 51.4 us (the partial kernel gains 1.3 us, the expansion of 16 ranges
-// instead of 8 loses 1.6) and O = 2048, M = 6, N = 65536: 55.9 against 49.4 us.  Hence only where
-// 128-feature tiles alone outnumber a quarter of the compute units, so that the narrow layout has at
-// most three ranges and needs several rounds of blocks.  The planner counts blocks accordingly; a call
-// that cannot take the wide kernel (alignment) runs the 128-feature kernels on the same ranges.
-// (measurement builds: VELORA_WGRAD_WIDE=0 never, 2 for every call with up to three tiles)
+// against 128.5 us; O = 11008, M = 16: 89.6 against 93.5 us; O = 11008, M = 64: 94.1 against 101.5 us;
+// O = 13824, M = 80: 124.8 against 133.4 us; but O = 4096, M = 43: 58.9 against 58.1 us, O = 5120,
+// M = 20: 52.8 against 51.4 us (the partial kernel gains 1.3 us, the expansion of 16 ranges instead of 8
+// loses 1.6), O = 5120, M = 54: 81.5 against 79.1 us, O = 5120, M = 80: 65.0 against 57.9 us and O = 2048,
+// M = 6, N = 65536: 55.9 against 49.4 us.  Hence only where 128-feature tiles alone outnumber a quarter of
+// the compute units, so that the narrow layout has at most three ranges and needs several rounds of
+// blocks.  The planner counts blocks accordingly; a call that cannot take the wide kernel (alignment) runs
+// the 128-feature kernels on the same ranges.
+// (measurement builds: VELORA_WGRAD_WIDE=0 never, 2 for every call with up to five tiles)
 bool wide_tiles(const Tiling& t, int64_t O, int num_cus) {
     const int mode = env_int("VELORA_WGRAD_WIDE", 1);
-    if (t.shared || t.gt > 3 || mode == 0) return false;
+    if (t.shared || t.gt > 5 || t.chunks != 1 || mode == 0) return false;
     return mode == 2 || ceil_div(O, 128) * 4 > num_cus;
 }
 
@@ -1867,6 +1924,12 @@ hipError_t launch_partials(const void* G, const void* S, int64_t N, int64_t O, i
         // (O = 13824, M = 80: 147 against 144 us), so those stay with the per-wave kernel.
         // (measurement builds: VELORA_WGRAD_WS=0 never, 2 for every launch with four to six tiles)
         const int ws_mode = env_int("VELORA_WGRAD_WS", 1);
+        if (ch.cw == 8 && !ch.shared && (ch.gt == 4 || ch.gt == 5) && ch.chunks == 1 && ch.s_align16 && (N * M) % 2 == 0 &&
+            ws_mode != 0 && wide_tiles(tiling_for(M), O, plan.num_cus)) {
+            if (!(phases & 2)) return hipSuccess;
+            if (ch.gt == 4) return launch_ws256<4>(G, S, partial, N, O, M, plan, st);
+            return launch_ws256<5>(G, S, partial, N, O, M, plan, st);
+        }
         const bool one_round = ceil_div(O, 128) * plan.splits <= plan.num_cus;
         const int ws64_max_gt = ws_mode == 2 || one_round ? 6 : 4;
         if (ch.cw == 8 && !ch.shared && ch.gt >= 4 && ch.gt <= ws64_max_gt && ch.chunks == 1 && ch.s_align16 &&

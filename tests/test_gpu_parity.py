@@ -257,10 +257,12 @@ WGRAD_CASES = [
     (385, 128, 752, 16, wl.BF16),                # M = 47, N * M odd
     (40000, 128, 272, 16, wl.BF16),              # M = 17: 313 chunks, more than two per split
     (33000, 256, 1376, 32, wl.BF16),             # M = 43, ragged last chunk
-    # up to three tiles on more than 8192 output features run on 256-feature blocks: output widths around
+    # up to five tiles on more than 8192 output features run on 256-feature blocks: output widths around
     # that tile, one that is not a multiple of 8 (per-wave kernel on the same token ranges), and a long
     # token axis (tens of chunks per block)
     (300, 8456, 512, 32, wl.BF16), (500, 8200, 320, 64, wl.BF16), (257, 8260, 256, 32, wl.BF16),   # M = 16, 5, 8
+    (700, 8456, 1696, 32, wl.BF16), (600, 8200, 2560, 32, wl.BF16), (300, 8260, 2048, 32, wl.BF16),   # M = 53, 80, 64
+    (450, 8448, 2080, 32, wl.BF16),              # M = 65
     (300, 8456, 1376, 32, wl.BF16), (1000, 8448, 640, 32, wl.BF16), (200, 8440, 1024, 32, wl.BF16),   # M = 43, 20, 32
     (310, 8260, 768, 32, wl.BF16),               # M = 24, O % 8 != 0
     (8000, 8200, 544, 32, wl.BF16),              # M = 17

@@ -143,6 +143,7 @@ def test_gemm_loop_has_the_memory_instructions_its_wait_assumes(linear_asm):
 @pytest.mark.parametrize("kernel,loads", [
     ("wgrad_partial_ws_kernelILi1E", 9), ("wgrad_partial_ws_kernelILi2E", 10), ("wgrad_partial_ws_kernelILi3E", 11),
     ("wgrad_partial_ws256_kernelILi1E", 9), ("wgrad_partial_ws256_kernelILi2E", 9), ("wgrad_partial_ws256_kernelILi3E", 10),
+    ("wgrad_partial_ws256_kernelILi4E", 10), ("wgrad_partial_ws256_kernelILi5E", 11),
     ("wgrad_partial_ws64_kernelILi4E", 6), ("wgrad_partial_ws64_kernelILi5E", 7), ("wgrad_partial_ws64_kernelILi6E", 7),
 ])
 def test_loader_wave_loop_waits_for_all_but_one_chunk(wgrad_asm, kernel, loads):
