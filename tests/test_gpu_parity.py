@@ -263,6 +263,7 @@ WGRAD_CASES = [
     (300, 8456, 512, 32, wl.BF16), (500, 8200, 320, 64, wl.BF16), (257, 8260, 256, 32, wl.BF16),   # M = 16, 5, 8
     (700, 8456, 1696, 32, wl.BF16), (600, 8200, 2560, 32, wl.BF16), (300, 8260, 2048, 32, wl.BF16),   # M = 53, 80, 64
     (450, 8448, 2080, 32, wl.BF16),              # M = 65
+    (1, 8448, 512, 32, wl.BF16), (65, 8200, 96, 32, wl.BF16),   # one token; M = 3 and one token past a chunk
     (300, 8456, 1376, 32, wl.BF16), (1000, 8448, 640, 32, wl.BF16), (200, 8440, 1024, 32, wl.BF16),   # M = 43, 20, 32
     (310, 8260, 768, 32, wl.BF16),               # M = 24, O % 8 != 0
     (8000, 8200, 544, 32, wl.BF16),              # M = 17
