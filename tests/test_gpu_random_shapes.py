@@ -64,6 +64,33 @@ def test_random_shape(vl, N, O, D, d, dtype):
         assert (np.abs(to_host_f64(Xhat) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-30).all()
 
 
+def _wide_output_shapes(n, seed):
+    # more than 8192 output features: the weight gradient's 256-feature tiles for up to 80 sub-tokens per
+    # token, the 128-feature kernels on the same plan beyond that or when O is not a multiple of 8
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([8, 16, 32, 64]))
+        M = int(rng.integers(1, min(100, 2048 // d) + 1))
+        N = int(rng.integers(1, 1000))
+        O = 8192 + int(rng.integers(1, 160)) * int(rng.choice([8, 8, 8, 4, 1]))
+        out.append((N, O, M * d, d))
+    return out
+
+
+@pytest.mark.parametrize("N,O,D,d", _wide_output_shapes(16, 77))
+def test_random_shape_wide_output_weight_grad(vl, N, O, D, d):
+    M = D // d
+    seed = N * 7919 + O * 104729 + D
+    G = wl.random_tensor(N, O, wl.BF16, seed=seed, stream=7, sigma=0.05)
+    S = wl.random_tensor(N, M, wl.BF16, seed=seed, stream=8)
+    v = wl.random_unit_v(d, seed=seed)
+    dW = vl.velora_weight_grad(to_dev(G, wl.BF16), to_dev(S, wl.BF16), to_dev(v, wl.F32), D)
+    want = oracle.weight_grad_bruteforce(G, S, v, D)
+    got = to_host_f64(dW)
+    assert rel_fro(got, want) <= TOL_F32_FROM_BF16 and rel_max(got, want) <= TOL_F32_FROM_BF16
+
+
 def _gemm_shapes(n, seed):
     # multiples that reach the MFMA kernel (D % 64 == 0 and O % 4 == 0 forward, O % 64 == 0 and D % 8 == 0
     # backward) mixed with ones that do not
