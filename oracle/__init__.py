@@ -49,6 +49,8 @@ def _load():
     L.velora_oracle_round_bf16.restype = ctypes.c_uint16
     L.velora_oracle_widen_bf16.argtypes = [ctypes.c_uint16]
     L.velora_oracle_widen_bf16.restype = ctypes.c_double
+    L.velora_oracle_store_array.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_void_p]
+    L.velora_oracle_store_array.restype = None
     L.velora_oracle_init_v.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci]
     L.velora_oracle_init_v.restype = ci
     L.velora_oracle_update_v.argtypes = [vp, ci, i64, i64, i64, vp, ctypes.c_double, vp, vp, ci]
@@ -224,12 +226,12 @@ def linear(X: np.ndarray, W: np.ndarray, threads: int = 0) -> np.ndarray:
 
 
 def _store(x: np.ndarray, dt: int) -> np.ndarray:
-    """float64 -> storage dtype: float32, or bfloat16 bits by round-to-nearest-even of the float32 value."""
-    f = x.astype(np.float32)
-    if dt != DT_BF16:
-        return f
-    b = f.view(np.uint32)
-    return ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+    """float64 -> storage dtype in ONE rounding to nearest even (float32, or bfloat16 bits by the same
+    routine as round_bf16): the stored value of Listing 1's `out` and `grad_input` in the training dtype."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = np.empty(x.shape, dtype=np.uint16 if dt == DT_BF16 else np.float32)
+    _load().velora_oracle_store_array(_p(x), dt, x.size, _p(out))
+    return out
 
 
 def linear_compress(X: np.ndarray, W: np.ndarray, v: np.ndarray, M: int,

@@ -107,6 +107,11 @@ extern "C" {
 uint16_t velora_oracle_round_bf16(double x) { return round_to_bf16(x); }
 double velora_oracle_widen_bf16(uint16_t b) { return widen_bf16(b); }
 
+// out[i] = x[i] stored as dt (float32 by the cast, bfloat16 by round_to_bf16): one rounding from float64.
+void velora_oracle_store_array(const double* x, int dt, int64_t n, void* out) {
+    for (int64_t i = 0; i < n; ++i) store(out, dt, i, x[i]);
+}
+
 // Sec. 3.2: v = average of all N*M sub-tokens of the first batch; Sec. 3.1:
 // unit length.  mean_out (may be null) receives the un-normalised average.
 // Returns 0, or 6 when the average is zero or not finite, in which case

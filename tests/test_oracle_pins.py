@@ -82,6 +82,24 @@ class TestBf16Format:
         got = np.array([oracle.round_bf16(float(x)) for x in a], dtype=np.uint16)
         assert (got == want).all()
 
+    def test_array_store_rounds_once(self):
+        """The store of Y and dX in the training dtype is one rounding from float64: a value just above a
+        bfloat16 tie, by less than float32 resolves, must go up (through float32 first it would land on the
+        tie and go to even), and the array routine agrees with the scalar one element by element."""
+        one = 0x3F80
+        x = np.array([1.0 + 2.0 ** -8 + 2.0 ** -30, 1.0 + 2.0 ** -8, -(1.0 + 3 * 2.0 ** -8 - 2.0 ** -40), 0.0, 1e40,
+                      2.0 ** -134, 3.0e-39], dtype=np.float64)
+        got = oracle._store(x, oracle.DT_BF16)
+        assert got.dtype == np.uint16
+        assert got[0] == one + 1 and got[1] == one and got[2] == (0x8000 | (one + 1)) and got[4] == 0x7F80
+        assert (got == np.array([oracle.round_bf16(float(t)) for t in x], dtype=np.uint16)).all()
+        r = np.random.default_rng(9).standard_normal((37, 53)) * 1e-3
+        got2 = oracle._store(r, oracle.DT_BF16)
+        assert got2.shape == r.shape
+        assert (got2.ravel() == np.array([oracle.round_bf16(float(t)) for t in r.ravel()], dtype=np.uint16)).all()
+        f = oracle._store(r, oracle.DT_F32)
+        assert f.dtype == np.float32 and (f == r.astype(np.float32)).all()
+
 
 # ------------------------------------------------------------------ worked example
 class TestWorkedExample:
