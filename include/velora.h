@@ -29,6 +29,13 @@
  *     launched and the outputs are untouched.  No C++ exception crosses the
  *     boundary.  The library keeps no state between calls; concurrent calls on
  *     different streams with disjoint outputs/workspaces are safe.
+ *   - Apart from velora_init_v, no call allocates, synchronises or clears
+ *     memory, so a sequence of calls can be recorded into a HIP graph.  Some
+ *     kernels use more than 64 KB of LDS and raise their limit
+ *     (hipFuncSetAttribute) at their first launch on a device: run the
+ *     sequence once eagerly before capturing it.  What the library remembers
+ *     between calls (those per-device flags, the last launch plans per
+ *     thread) never changes a result.
  *   - Pointers must be aligned to their element size (VELORA_ERR_ALIGN
  *     otherwise).  16-byte aligned pointers with d a multiple of 8 (bf16) or 4
  *     (f32) take the vectorised kernels; anything else takes slower generic
