@@ -17,7 +17,8 @@
 //   wgrad_partial_mfma_kernel      1 tile; 5-6 tiles when the blocks need several rounds; 8-byte G loads;
 //                                  S that is not 16-byte aligned or has an odd element count
 //   wgrad_partial_ws_kernel        2-3 tiles: loader waves + computing waves, 128-token chunks through LDS
-//   wgrad_partial_ws256_kernel     1-5 tiles on more than 8192 output features: the same on 256-feature tiles
+//   wgrad_partial_ws256_kernel     1-3 tiles on more than 5376, 4-5 tiles on more than 8192 output features: the same
+//                                  on 256-feature tiles
 //   wgrad_partial_ws64_kernel      4 tiles, and 5-6 when every block is resident at once: 64-token chunks
 //   wgrad_partial_shared_g_kernel  8, 12, 16 tiles (M up to 256; larger M in chunks of 256)
 //   wgrad_partial_simple_kernel    float32 inputs and whatever the MFMA kernels cannot take
@@ -1567,21 +1568,26 @@ Tiling tiling_for(int64_t M) {
 bool direct_s(const Tiling& t) { return !t.shared && t.gt <= 3; }
 
 // Up to five group tiles on many output features: blocks of 256 features (wgrad_partial_ws256_kernel).
-// Halving the S fetches costs twice the token ranges, i.e. twice the partial sums written and read back.
-// Measured on whole calls, N = 16384: O = 11008, M = 32: 92.6 against 99.8 us; O = 13824, M = 20: 119.8
-// against 128.5 us; O = 11008, M = 16: 89.6 against 93.5 us; O = 11008, M = 64: 94.1 against 101.5 us;
-// O = 13824, M = 80: 124.8 against 133.4 us; but O = 4096, M = 43: 58.9 against 58.1 us, O = 5120,
-// M = 20: 52.8 against 51.4 us (the partial kernel gains 1.3 us, the expansion of 16 ranges instead of 8
-// loses 1.6), O = 5120, M = 54: 81.5 against 79.1 us, O = 5120, M = 80: 65.0 against 57.9 us and O = 2048,
-// M = 6, N = 65536: 55.9 against 49.4 us.  Hence only where 128-feature tiles alone outnumber a quarter of
-// the compute units, so that the narrow layout has at most three ranges and needs several rounds of
-// blocks.  The planner counts blocks accordingly; a call that cannot take the wide kernel (alignment) runs
-// the 128-feature kernels on the same ranges.
+// Halving the S fetches costs twice the token ranges, i.e. twice the partial sums written and read back
+// (the more groups per token, the more bytes that is).  Measured on whole calls, N = 16384, narrow -> wide:
+//   one to three tiles:  O = 11008: M = 16 93.5 -> 89.6 us, M = 32 99.8 -> 92.6; O = 13824, M = 20: 128.5 ->
+//     119.8; O = 8192: M = 16 71.8 -> 69.6, M = 32 74.3 -> 71.2, M = 43 110.7 -> 106.6; O = 7168: M = 16 64.0 ->
+//     61.8, M = 32 66.5 -> 62.8; O = 6144: M = 16 54.4 -> 53.5, M = 32 57.3 -> 55.6, M = 43 83.9 -> 83.1;
+//     O = 5632: M = 16 52.5 -> 50.3, M = 32 54.4 -> 52.4, M = 43 79.4 -> 76.9; but O = 5120: M = 5 +1.5 us,
+//     M = 20 +1.4 us; O = 4096: M = 43 58.1 -> 58.9 (the partial kernel gains 1.3 us, the expansion of 16
+//     ranges instead of 8 loses 1.6); O = 2048, M = 6, N = 65536: 49.4 -> 55.9
+//   four and five tiles: O = 11008, M = 64: 101.5 -> 94.1; O = 13824, M = 80: 133.4 -> 124.8; but O = 8192:
+//     M = 64 75.2 -> 76.0, M = 80 81.7 -> 86.2; O = 6144: M = 64 59.5 -> 62.1, M = 80 66.7 -> 69.6; O = 5120:
+//     M = 54 79.1 -> 81.5, M = 80 57.9 -> 65.0
+// Hence: up to three tiles when 128-feature tiles alone outnumber a sixth of the compute units (the narrow
+// layout then has at most five ranges), four and five tiles when they outnumber a quarter (at most three
+// ranges and several rounds of blocks).  The planner counts blocks accordingly; a call that cannot take
+// the wide kernel (alignment) runs the 128-feature kernels on the same ranges.
 // (measurement builds: VELORA_WGRAD_WIDE=0 never, 2 for every call with up to five tiles)
 bool wide_tiles(const Tiling& t, int64_t O, int num_cus) {
     const int mode = env_int("VELORA_WGRAD_WIDE", 1);
     if (t.shared || t.gt > 5 || t.chunks != 1 || mode == 0) return false;
-    return mode == 2 || ceil_div(O, 128) * 4 > num_cus;
+    return mode == 2 || ceil_div(O, 128) * (t.gt <= 3 ? 6 : 4) > num_cus;
 }
 
 MfmaChoice choose_mfma(int64_t O, int64_t M, int g_align, int s_align, const WgradPlan& plan) {

@@ -257,13 +257,16 @@ WGRAD_CASES = [
     (385, 128, 752, 16, wl.BF16),                # M = 47, N * M odd
     (40000, 128, 272, 16, wl.BF16),              # M = 17: 313 chunks, more than two per split
     (33000, 256, 1376, 32, wl.BF16),             # M = 43, ragged last chunk
-    # up to five tiles on more than 8192 output features run on 256-feature blocks: output widths around
+    # up to five tiles on wide outputs (here: more than 8192 features) run on 256-feature blocks: output widths around
     # that tile, one that is not a multiple of 8 (per-wave kernel on the same token ranges), and a long
     # token axis (tens of chunks per block)
     (300, 8456, 512, 32, wl.BF16), (500, 8200, 320, 64, wl.BF16), (257, 8260, 256, 32, wl.BF16),   # M = 16, 5, 8
     (700, 8456, 1696, 32, wl.BF16), (600, 8200, 2560, 32, wl.BF16), (300, 8260, 2048, 32, wl.BF16),   # M = 53, 80, 64
     (450, 8448, 2080, 32, wl.BF16),              # M = 65
     (1, 8448, 512, 32, wl.BF16), (65, 8200, 96, 32, wl.BF16),   # one token; M = 3 and one token past a chunk
+    # (up to three tiles: from 5377 output features on)
+    (300, 5640, 1376, 32, wl.BF16), (500, 6152, 512, 32, wl.BF16), (200, 7176, 1024, 32, wl.BF16),   # M = 43, 16, 32
+    (400, 6144, 2048, 32, wl.BF16),              # M = 64 at this width: 128-feature tiles
     (300, 8456, 1376, 32, wl.BF16), (1000, 8448, 640, 32, wl.BF16), (200, 8440, 1024, 32, wl.BF16),   # M = 43, 20, 32
     (310, 8260, 768, 32, wl.BF16),               # M = 24, O % 8 != 0
     (8000, 8200, 544, 32, wl.BF16),              # M = 17
