@@ -23,8 +23,8 @@
 //   wgrad_partial_shared_g_kernel  8, 12, 16 tiles (M up to 256; larger M in chunks of 256)
 //   wgrad_partial_simple_kernel    float32 inputs and whatever the MFMA kernels cannot take
 //   wgrad_pack_s_kernel            S as ready-made MFMA fragments, for the kernels that read S that way
-//   wgrad_expand_kernel            dW rows below 32 KB (21 KB for bf16 output): one block per row
-//   wgrad_expand_sweep_kernel      longer dW rows: one sweep of the whole grid over dW
+//   wgrad_expand_kernel            float32 dW rows below 32 KB, and what the sweep cannot take: one block per row
+//   wgrad_expand_sweep_kernel      longer float32 rows and bf16 output: one sweep of the whole grid over dW
 //   wgrad_reduce_kernel            dense T[O, M] for the factored hand-off
 #include "common.h"
 #include "kernels.h"
@@ -2055,9 +2055,12 @@ hipError_t expand_best(const float* partial, int splits, int64_t t_stride, const
     // the many small blocks of the row kernel interleave as well (-1.8 .. +0.9 us for the sweep on the
     // 4096- and 5120-wide layers, no trend).
     const int sweep_mode = env_int("VELORA_WGRAD_SWEEP", 1);   // measurement builds: 0 never, 2 whenever it fits
-    // bf16 output: the sweep is already ahead at rows of 22 KB (4096 x 11008: 49.5 -> 45.0 us, 5120 x 13824:
-    // 61.7 -> 58.2 us at M = 54, 96.8 -> 93.3 us at M = 216) and level at 8 KB; float32 rows of 22-28 KB: no trend
-    const bool long_rows = D * (dw_bf16 ? 2 : 4) >= (dw_bf16 ? 21504 : 32768);
+    // bf16 output: the sweep is ahead at every row length it was measured on (whole calls, N = 16384:
+    // 4096 x 11008: 49.5 -> 45.0 us; 5120 x 13824: 61.7 -> 58.2 us at M = 54, 96.8 -> 93.3 us at M = 216;
+    // 4096 x 4096, M = 32: 37.1 -> 35.5; 5120 x 5120: 45.0 -> 43.0 at M = 20, 53.5 -> 50.1 at M = 80;
+    // 11008 x 4096, M = 32: 76.9 -> 75.0; 2048 x 768, N = 65536: 48.4 -> 47.3; level on 3072 x 768), so it
+    // runs whenever the shape fits it.  float32 rows of 22-28 KB: no trend.
+    const bool long_rows = dw_bf16 || D * 4 >= 32768;
     const bool fits = static_cast<double>(O) * static_cast<double>(D) / 4.0 < lim &&
                       static_cast<double>(O) * static_cast<double>(t_stride) <= 16777216.0 && splits <= 16 && d <= 2048 &&
                       (sweep_mode == 2 || (sweep_mode == 1 && long_rows));

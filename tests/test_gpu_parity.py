@@ -334,8 +334,9 @@ LONG_ROW_CASES = [
     (300, 8, 8192, 64, "f32"), (300, 5, 8256, 172, "f32"), (200, 3, 16384, 1024, "f32"),
     (2000, 300, 8192, 2048, "f32"), (700, 131, 11008, 344, "f32"), (8192, 2048, 8192, 256, "f32"),
     (300, 8, 16384, 128, "bf16"), (260, 12, 16512, 172, "bf16"), (1500, 260, 16384, 256, "bf16"),
-    # bf16 output takes the sweep from rows of 21 KB on
-    (400, 70, 11008, 256, "bf16"), (250, 33, 10752, 128, "bf16"), (300, 20, 13824, 64, "bf16"),
+    # bf16 output takes the sweep at every row length (sub-tokens of 128 elements and more)
+    (400, 70, 11008, 256, "bf16"), (250, 33, 10752, 128, "bf16"), (300, 20, 13824, 256, "bf16"),
+    (200, 40, 1024, 128, "bf16"), (129, 7, 768, 128, "bf16"), (90, 1, 256, 256, "bf16"), (500, 300, 4096, 1024, "bf16"),
 ]
 
 
