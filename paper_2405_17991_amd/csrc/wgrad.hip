@@ -1444,6 +1444,23 @@ __global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __
         const uint32_t span = left < U * stride ? left : U * stride;
         const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
             static_cast<unsigned char*>(dW) + static_cast<size_t>(base) * VB, 0, span * VB, 0x00020000);
+        // accumulate: this trip's old values first, all U loads in flight at once.  Loaded one by one in front
+        // of their stores they would each wait for the store before them (same descriptor, so the compiler
+        // keeps the order): eight memory round trips per trip, 123 against 69 us for the 4096 x 11008 float32
+        // array.  (Loading them a whole trip ahead into a second register set: 73 us.)
+        u32x4 oldv[ACC ? U : 1];
+        if constexpr (ACC) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t off = (u * stride + t) * VB;
+                if constexpr (!OUT_BF16 || VW == 8) {
+                    oldv[u] = __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0);
+                } else {
+                    const u32x2 o2 = __builtin_amdgcn_raw_buffer_load_b64(wr, off, 0, 0);
+                    oldv[u] = u32x4{o2.x, o2.y, 0u, 0u};
+                }
+            }
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t off = (u * stride + t) * VB;           // past `span` vectors: dropped (loads: zero)
@@ -1456,13 +1473,13 @@ __global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __
             const f32x4 va = *reinterpret_cast<const f32x4*>(vs + j * VW);
             if constexpr (!OUT_BF16) {
                 f32x4 r = {tg * va.x, tg * va.y, tg * va.z, tg * va.w};
-                if constexpr (ACC) r += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0));
+                if constexpr (ACC) r += __builtin_bit_cast(f32x4, oldv[u]);
                 __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, r), wr, off, 0, kStreamAux);
             } else if constexpr (VW == 8) {
                 const f32x4 vb = *reinterpret_cast<const f32x4*>(vs + j * VW + 4);
                 float r[8] = {tg * va.x, tg * va.y, tg * va.z, tg * va.w, tg * vb.x, tg * vb.y, tg * vb.z, tg * vb.w};
                 if constexpr (ACC) {
-                    const u32x4 old = __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0);
+                    const u32x4 old = oldv[u];
                     r[0] += bf16_lo(old.x); r[1] += bf16_hi(old.x); r[2] += bf16_lo(old.y); r[3] += bf16_hi(old.y);
                     r[4] += bf16_lo(old.z); r[5] += bf16_hi(old.z); r[6] += bf16_lo(old.w); r[7] += bf16_hi(old.w);
                 }
@@ -1472,7 +1489,7 @@ __global__ __launch_bounds__(256) void wgrad_expand_sweep_kernel(const float* __
             } else {
                 float r[4] = {tg * va.x, tg * va.y, tg * va.z, tg * va.w};
                 if constexpr (ACC) {
-                    const u32x2 old = __builtin_amdgcn_raw_buffer_load_b64(wr, off, 0, 0);
+                    const u32x4 old = oldv[u];
                     r[0] += bf16_lo(old.x); r[1] += bf16_hi(old.x); r[2] += bf16_lo(old.y); r[3] += bf16_hi(old.y);
                 }
                 __builtin_amdgcn_raw_buffer_store_b64(u32x2{pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3])}, wr, off, 0,
