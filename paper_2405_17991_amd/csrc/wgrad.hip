@@ -21,7 +21,8 @@
 //                                  on 256-feature tiles
 //   wgrad_partial_ws64_kernel      4 tiles, and 5-6 when every block is resident at once: 64-token chunks
 //   wgrad_partial_shared_g_kernel  8, 12, 16 tiles (M up to 256; larger M in chunks of 256)
-//   wgrad_partial_simple_kernel    float32 inputs and whatever the MFMA kernels cannot take
+//   wgrad_partial_f32_mfma_kernel  float32 inputs (O a multiple of 4, 16-byte aligned G)
+//   wgrad_partial_simple_kernel    whatever the MFMA kernels cannot take
 //   wgrad_pack_s_kernel            S as ready-made MFMA fragments, for the kernels that read S that way
 //   wgrad_expand_kernel            float32 dW rows below 32 KB, and what the sweep cannot take: one block per row
 //   wgrad_expand_sweep_kernel      longer float32 rows and bf16 output: one sweep of the whole grid over dW
@@ -1169,6 +1170,136 @@ __global__ __launch_bounds__(NW * 64) void wgrad_partial_shared_g_kernel(const u
 }
 
 // ---------------------------------------------------------------------------
+// Kernel 1, float32 inputs on the float32 matrix instruction.
+//
+// v_mfma_f32_16x16x4_f32: D[16x16] += A[16x4] * B[4x16]; lane l supplies A[l%16][l/16] and B[l/16][l%16], ONE
+// value each, so with the reduction index (the token) as the slow axis of both operands nothing has to be
+// transposed: lane (q, jj) of k step ks takes token 4 ks + q, the value S[token][16 a + jj] for group tile a
+// and eight consecutive features G[token][o0 + 8 jj .. + 7] (two 16-byte loads, 512 contiguous bytes per
+// token and wave), of which feature c feeds column tile c (the same strided column map as the bf16 kernels,
+// so the epilogue is theirs).  A block owns 128 features x one token range x GT group tiles; its four waves
+// take alternate 16-token steps with the next step's loads in flight, and are summed (w0 + w2) + (w1 + w3)
+// through LDS at the end.  The instruction runs at 1/16 of the bf16 rate: with 43 groups per token the
+// matrix pipes need about as long as HBM needs for G, which is still an order of magnitude less than the
+// plain-FMA kernel below needs (N = 16384, O = 4096, M = 43: 514 us).
+// Edges as in the bf16 kernels: range-checked descriptors return zeros past the token range, past O and
+// past M.  Needs O % 4 == 0, 16-byte aligned G, and byte offsets inside a token range below 2^31.
+// grid = (o tiles of 128, splits, chunks of GT group tiles)
+// ---------------------------------------------------------------------------
+constexpr int kF32Step = 16;                           // tokens per step and wave: four k steps of the instruction
+
+template <int GT>
+__global__ __launch_bounds__(256) void wgrad_partial_f32_mfma_kernel(const float* __restrict__ G,
+                                                                    const float* __restrict__ S,
+                                                                    float* __restrict__ partial, int64_t N, int64_t O,
+                                                                    int64_t M, int64_t Mp, int64_t rows_per_split) {
+    constexpr int CW = 8, NT = GT * CW;
+    __shared__ f32x4 red[2][NT][kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int q = lane >> 4;
+    const int jj = lane & 15;
+    const int64_t o0 = static_cast<int64_t>(blockIdx.x) * (16 * CW);
+    const int split = blockIdx.y;
+    const int64_t g0 = static_cast<int64_t>(blockIdx.z) * (16 * GT);
+    const int64_t kb = static_cast<int64_t>(split) * rows_per_split;
+    int64_t ke = kb + rows_per_split;
+    if (ke > N) ke = N;
+    const int rows = ke > kb ? static_cast<int>(ke - kb) : 0;
+    const int n_steps = (rows + kF32Step - 1) / kF32Step;
+
+    constexpr uint32_t kOut = 0x80000000u;             // an offset no descriptor here covers
+    const uint32_t row_bytes = static_cast<uint32_t>(O) * 4u;
+    const uint32_t s_row_bytes = static_cast<uint32_t>(M) * 4u;
+    const bool lo_ok = o0 + jj * CW < O, hi_ok = o0 + jj * CW + 4 < O;
+    const uint32_t g_lane = static_cast<uint32_t>(q) * row_bytes + static_cast<uint32_t>(jj * CW * 4);
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(G) + (kb * O + o0) * 4), 0,
+        rows > 0 ? static_cast<int>(static_cast<uint32_t>(rows) * row_bytes - static_cast<uint32_t>(o0 * 4)) : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(S) + kb * M * 4), 0,
+        static_cast<int>(static_cast<uint32_t>(rows) * s_row_bytes), 0x00020000);
+    uint32_t s_lane[GT];
+#pragma unroll
+    for (int a = 0; a < GT; ++a)
+        s_lane[a] = g0 + 16 * a + jj < M ? static_cast<uint32_t>(q) * s_row_bytes + static_cast<uint32_t>((g0 + 16 * a + jj) * 4)
+                                         : kOut;
+
+    struct Stage {
+        f32x4 glo[4], ghi[4];                          // [k step]: features 8 jj .. + 3 and + 4 .. + 7 of token 4 ks + q
+        float sv[4][GT];
+    };
+    auto load_step = [&](Stage& st, int t) {
+        // step t covers tokens 16 t .. 16 t + 15 of the range; past the last step: offsets nothing covers
+        const bool real = t < n_steps;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const uint32_t r = static_cast<uint32_t>(t * kF32Step + ks * 4);
+            const uint32_t goff = r * row_bytes + g_lane;
+            st.glo[ks] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(g_rsrc, real && lo_ok ? goff : kOut, 0, kStreamAux));
+            st.ghi[ks] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(g_rsrc, real && hi_ok ? goff + 16u : kOut, 0, kStreamAux));
+#pragma unroll
+            for (int a = 0; a < GT; ++a)
+                st.sv[ks][a] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                             s_rsrc, real && s_lane[a] != kOut ? r * s_row_bytes + s_lane[a] : kOut, 0, 0));
+        }
+    };
+
+    f32x4 acc[GT][CW];
+#pragma unroll
+    for (int a = 0; a < GT; ++a)
+#pragma unroll
+        for (int c = 0; c < CW; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](const Stage& st) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int a = 0; a < GT; ++a)
+#pragma unroll
+                for (int c = 0; c < CW; ++c) {
+                    const float b = c < 4 ? st.glo[ks][c] : st.ghi[ks][c - 4];
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.sv[ks][a], b, acc[a][c], 0, 0, 0);
+                }
+    };
+
+    // two register stages: the loads of this wave's next step are in flight while it works on the current one
+    Stage sa, sb;
+    load_step(sa, w);
+    for (int t = w; t < n_steps; t += 8) {
+        load_step(sb, t + 4);
+        compute(sa);
+        if (t + 4 >= n_steps) break;
+        load_step(sa, t + 8);
+        compute(sb);
+    }
+
+    // (w0 + w2) + (w1 + w3), a fixed order
+    if (w >= 2) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) red[w - 2][i][lane] = acc[i / CW][i % CW];
+    }
+    __syncthreads();
+    if (w < 2) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) acc[i / CW][i % CW] += red[w][i][lane];
+    }
+    __syncthreads();
+    if (w == 1) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) red[0][i][lane] = acc[i / CW][i % CW];
+    }
+    __syncthreads();
+    if (w == 0) {
+        float* out = partial + static_cast<int64_t>(split) * O * Mp;
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const f32x4 t = acc[i / CW][i % CW] + red[0][i][lane];
+            store_tile<CW>(out, t, o0, jj, q, i % CW, g0 + (i / CW) * 16, O, Mp);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Kernel 1, generic path: float32 inputs, or shapes/pointers the MFMA path
 // cannot take.  Plain FMA; thread (ol, gq) owns output feature o0+ol and the
 // groups g0 + gq + 4*i, i < 4.
@@ -1795,6 +1926,30 @@ hipError_t launch_simple(const void* G, const void* S, float* partial, int64_t N
     return hipGetLastError();
 }
 
+// float32 inputs on the float32 matrix instruction: up to three group tiles per block, more groups in
+// further blocks (which read G again)
+bool f32_mfma_ok(int64_t O, int64_t M, int g_align, const WgradPlan& plan) {
+    return O % 4 == 0 && g_align >= 16 &&
+           static_cast<double>(plan.rows_per_split + 32) * static_cast<double>(O) * 4.0 < 2147483648.0 &&
+           static_cast<double>(plan.rows_per_split + 32) * static_cast<double>(M) * 4.0 < 2147483648.0 &&
+           ceil_div(M, 48) <= 65535;
+}
+
+hipError_t launch_f32_mfma(const void* G, const void* S, float* partial, int64_t N, int64_t O, int64_t M,
+                           const WgradPlan& plan, hipStream_t st) {
+    const int gt = M <= 16 ? 1 : M <= 32 ? 2 : 3;
+    dim3 grid(static_cast<unsigned>(ceil_div(O, 128)), static_cast<unsigned>(plan.splits),
+              static_cast<unsigned>(ceil_div(M, 16 * gt)));
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, static_cast<const float*>(G), static_cast<const float*>(S),
+                           partial, N, O, M, plan.Mp, plan.rows_per_split);
+        return hipGetLastError();
+    };
+    if (gt == 1) return go(wgrad_partial_f32_mfma_kernel<1>);
+    if (gt == 2) return go(wgrad_partial_f32_mfma_kernel<2>);
+    return go(wgrad_partial_f32_mfma_kernel<3>);
+}
+
 template <bool OUT_BF16, bool VEC>
 hipError_t launch_expand(const float* partial, int splits, int64_t Mp, const float* v, void* dW, int64_t O, int64_t D,
                          int64_t M, bool accumulate, bool dw_align16, hipStream_t st) {
@@ -1988,6 +2143,10 @@ hipError_t launch_partials(const void* G, const void* S, int64_t N, int64_t O, i
             else done = true;
             if (e != hipSuccess) return e;
         }
+    }
+    if (!done && !is_bf16 && env_int("VELORA_WGRAD_FORCE_SIMPLE", 0) == 0 && f32_mfma_ok(O, M, g_align, plan)) {
+        if (!(phases & 2)) return hipSuccess;
+        return launch_f32_mfma(G, S, partial, N, O, M, plan, st);
     }
     if (!done) {
         e = is_bf16 ? launch_simple<Bf16Elem>(G, S, partial, N, O, M, plan, st)

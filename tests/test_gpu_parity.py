@@ -231,6 +231,13 @@ WGRAD_CASES = [
     # (N, O, D, d, dtype)
     (256, 64, 64, 16, wl.F32),                 # configuration 1
     (100, 50, 24, 3, wl.F32), (333, 70, 40, 40, wl.F32), (64, 9, 12, 1, wl.F32),
+    # float32 inputs with O % 4 == 0 take the float32 matrix instruction: one, two and three group tiles, more
+    # groups than one block covers (M = 100: three chunks), partial feature tiles, token counts around the
+    # 16-token steps and the four waves' turns
+    (515, 260, 2048, 128, wl.F32), (77, 520, 1024, 32, wl.F32), (300, 136, 1376, 32, wl.F32),    # M = 16, 32, 43
+    (200, 128, 3200, 32, wl.F32), (1000, 64, 96, 32, wl.F32), (33, 12, 64, 16, wl.F32),          # M = 100, 3, 4
+    (15, 4, 8, 8, wl.F32), (16, 132, 48, 1, wl.F32), (65, 8, 640, 2, wl.F32), (129, 36, 170, 10, wl.F32),   # M = 1, 48, 320, 17
+    (4096, 512, 1376, 32, wl.F32),
     # bf16 MFMA tilings: M = D/d picks (S columns per lane, sets); O picks the G tile
     (1000, 256, 768, 64, wl.BF16),             # M = 12
     (777, 384, 768, 128, wl.BF16),             # M = 6, ragged token tail
