@@ -47,6 +47,14 @@ COMPRESS_CASES = [
     # and an odd number of sub-tokens (which stays with the 8-byte kernel)
     (5, 10 * 132, 132, wl.BF16), (7, 10 * 252, 252, wl.BF16), (37, 6 * 172, 172, wl.BF16), (1, 2 * 172, 172, wl.BF16),
     (3, 3 * 172, 172, wl.BF16), (9, 2 * 260, 260, wl.BF16),
+    # sub-token sizes no vector kernel takes, in an X that is a whole number of 16-byte vectors: tiles of 256 or
+    # 64 sub-tokens through LDS (d = 43 and 86 are 256 and 128 sub-tokens per token on the 11008-wide layer,
+    # d = 54 and 27 on the 13824-wide one); partial last tiles, fewer sub-tokens than one tile, d = 1, 2, 3,
+    # the largest d of each tile size, float32
+    (300, 11008, 43, wl.BF16), (150, 11008, 86, wl.BF16), (96, 13824, 54, wl.BF16), (40, 13824, 27, wl.BF16),
+    (64, 24, 3, wl.BF16), (1000, 16, 2, wl.BF16), (8, 9, 9, wl.BF16), (16, 127, 127, wl.BF16), (8, 2 * 250, 250, wl.BF16),
+    (8, 495, 495, wl.BF16), (8, 497, 497, wl.BF16), (300, 1376 * 2, 43, wl.F32), (52, 300, 100, wl.F32), (4, 3 * 63, 63, wl.F32),
+    (4, 250, 250, wl.F32), (2048, 8, 1, wl.BF16),
     # generic kernel: d not a power of two times the vector width, d = 1, d = D
     (50, 60, 12, wl.BF16), (50, 63, 7, wl.F32), (31, 33, 1, wl.BF16), (17, 100, 100, wl.F32),
     (11, 3000, 3000, wl.BF16), (1, 8, 8, wl.BF16), (1, 1, 1, wl.F32),
@@ -72,11 +80,11 @@ def test_compress_matches_oracle(vl, N, D, d, dtype):
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
-@pytest.mark.parametrize("d", [8, 64, 256, 12, 24, 344, 1032, 172, 20])
+@pytest.mark.parametrize("d", [8, 64, 256, 12, 24, 344, 1032, 172, 20, 43, 86, 250])
 def test_compress_gather_is_bit_exact(vl, dtype, d):
     # v = e_j: compress degenerates to a gather, so the indexing (group) is
     # checked with no rounding at all.
-    N, M = 131, 5
+    N, M = (136 if d in (43, 86, 250) else 131), 5     # 136: X is a whole number of 16-byte vectors (LDS-tile kernel)
     D = M * d
     X = wl.random_tensor(N, D, dtype, seed=99)
     for j in (0, d // 2, d - 1):
