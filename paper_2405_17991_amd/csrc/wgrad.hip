@@ -1382,6 +1382,7 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
     // threads (one latency, not one per split) and then summed in split order
     int mchunk = kTChunk / (rows_per_block * splits);
     if (mchunk > kTChunk / 2 / rows_per_block) mchunk = kTChunk / 2 / rows_per_block;
+    if (mchunk >= 4) mchunk &= ~3;   // a chunk of groups then starts on a multiple of four columns whatever d is
     for (int64_t gc0 = 0; gc0 < M; gc0 += mchunk) {
         const int gcn = static_cast<int>((M - gc0) < mchunk ? (M - gc0) : mchunk);
         float* Pr = P + r * splits * mchunk;
@@ -1470,6 +1471,29 @@ __global__ __launch_bounds__(kExpandThreads) void wgrad_expand_kernel(const floa
                         r0 += old.x; r1 += old.y; r2 += old.z; r3 += old.w;
                     }
                     const f32x4 out4 = {r0, r1, r2, r3};
+                    __builtin_nontemporal_store(out4, reinterpret_cast<f32x4*>(q));
+                }
+            } else if (!OUT_BF16 && vec8 && (mchunk >= M || (mchunk & 3) == 0)) {
+                // float32 rows whose sub-token size is not a multiple of four (d = 43: 256 sub-tokens per token on
+                // an 11008-wide layer): still four columns per 16-byte store; a group boundary may fall inside
+                // the four (at most one, d >= 4), so every column looks up its own group and element of v
+                for (int64_t i = p; i < c_count / 4; i += tpr) {
+                    const int64_t cl = i * 4;
+                    int gl = static_cast<int>(cl / d);
+                    int j = static_cast<int>(cl - static_cast<int64_t>(gl) * d);
+                    float r[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        r[u] = Tr[gl] * v[j];
+                        if (++j == d) { j = 0; ++gl; }
+                    }
+                    const int64_t e = o * D + c_begin + cl;
+                    float4* q = reinterpret_cast<float4*>(static_cast<float*>(dW) + e);
+                    if (accumulate) {
+                        const float4 old = *q;
+                        r[0] += old.x; r[1] += old.y; r[2] += old.z; r[3] += old.w;
+                    }
+                    const f32x4 out4 = {r[0], r[1], r[2], r[3]};
                     __builtin_nontemporal_store(out4, reinterpret_cast<f32x4*>(q));
                 }
             } else {
@@ -1963,8 +1987,9 @@ hipError_t launch_expand(const float* partial, int splits, int64_t Mp, const flo
     // 256..1024 threads; short rows are grouped (power of two, <= 16 rows).
     // (measured: 4 stores per thread is at or near the best block shape for
     // every layer shape of the five configurations)
-    const bool vec8 = OUT_BF16 && VEC && d % 8 == 0 && dw_align16;
-    const int64_t per_row = ceil_div(D, vec8 ? 8 : 4);
+    const bool any4 = !OUT_BF16 && !VEC && d >= 4 && D % 4 == 0 && dw_align16;   // see the kernel's third branch
+    const bool vec8 = (OUT_BF16 && VEC && d % 8 == 0 && dw_align16) || any4;
+    const int64_t per_row = ceil_div(D, OUT_BF16 && vec8 ? 8 : 4);
     const int spt = 4;
     int64_t threads = ceil_div(ceil_div(per_row, spt), 64) * 64;
     if (threads > kExpandThreads) threads = kExpandThreads;
@@ -2164,7 +2189,7 @@ hipError_t expand_any(const float* partial, int splits, int64_t Mp, const float*
                    : launch_expand<true, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, false, st);
     }
     return vec ? launch_expand<false, true>(partial, splits, Mp, v, dW, O, D, M, accumulate, true, st)
-               : launch_expand<false, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, false, st);
+               : launch_expand<false, false>(partial, splits, Mp, v, dW, O, D, M, accumulate, dw_align >= 16, st);
 }
 
 }  // namespace

@@ -262,6 +262,12 @@ WGRAD_CASES = [
     (130, 32, 40, 1, wl.BF16),                 # d = 1: dW = G^T S
     (90, 48, 512, 512, wl.BF16),               # M = 1: rank-one gradient
     (1, 16, 64, 16, wl.BF16), (31, 8, 16, 8, wl.BF16),
+    # sub-token sizes that are not a multiple of four, float32 dW: four columns per store across group boundaries
+    # (D % 4 == 0, d >= 4), several chunks of groups per row (M = 300 with many token ranges), and the scalar
+    # rest (D % 4 != 0, d < 4)
+    (300, 72, 11008, 43, wl.BF16), (200, 64, 86 * 16, 86, wl.BF16), (150, 40, 54 * 8, 54, wl.BF16),
+    (120, 20, 36, 9, wl.BF16), (4000, 8, 1500, 5, wl.BF16), (90, 36, 35, 5, wl.BF16), (70, 12, 24, 3, wl.BF16),
+    (257, 24, 43 * 12, 43, wl.F32),
     # two and three group tiles take the kernel whose loader waves stage G and S in LDS: token counts around
     # its 128-token chunks (127, 128, 129, one short of and one past several chunks per split), output widths
     # around its 128-feature tiles, group counts at both ends of each tile count, an odd N * M (falls back to
@@ -314,7 +320,7 @@ def test_weight_grad_matches_bruteforce_oracle(vl, N, O, D, d, dtype):
         assert rel_max(got, want) <= TOL_F32_FROM_BF16
 
 
-@pytest.mark.parametrize("N,O,D,d", [(515, 136, 2048, 128), (300, 64, 1728, 8), (150, 30, 64, 16)])
+@pytest.mark.parametrize("N,O,D,d", [(515, 136, 2048, 128), (300, 64, 1728, 8), (150, 30, 64, 16), (200, 24, 43 * 8, 43)])
 def test_weight_grad_bf16_output_and_accumulate(vl, N, O, D, d):
     torch = _torch()
     M = D // d
