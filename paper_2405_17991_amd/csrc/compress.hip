@@ -327,6 +327,45 @@ __global__ __launch_bounds__(256) void reconstruct_generic_kernel(const typename
     }
 }
 
+// Reconstruct for sub-token sizes whose 16-byte vectors straddle sub-tokens (d not a multiple of the vector
+// width), Xhat 16-byte aligned and a whole number of vectors: a thread still writes whole vectors; it finds
+// the sub-token and the position of its vector's first element by one division and steps through the
+// boundaries inside the vector.  v sits in LDS.  16384 x 11008 bf16 at d = 43: 186 us with the element-wise
+// kernel above.
+template <typename E>
+__global__ __launch_bounds__(256) void reconstruct_straddle_kernel(const typename E::type* __restrict__ S,
+                                                                  const float* __restrict__ v, uint4* __restrict__ Xhat,
+                                                                  int64_t n_vec, int64_t n_sub, int d) {
+    constexpr int kV = E::kPerVec;
+    extern __shared__ float vs_lds[];
+    for (int j = threadIdx.x; j < d; j += blockDim.x) vs_lds[j] = v[j];
+    __syncthreads();
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
+        const int64_t e = i * kV;
+        int64_t k = e / d;
+        int j = static_cast<int>(e - k * d);
+        float s = E::load(S, k);
+        float r[kV];
+#pragma unroll
+        for (int u = 0; u < kV; ++u) {
+            r[u] = s * vs_lds[j];
+            if (++j == d) {
+                j = 0;
+                ++k;
+                if (k < n_sub) s = E::load(S, k);
+            }
+        }
+        u32x4_store out;
+        if constexpr (kV == 8) {
+            out = u32x4_store{pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]), pack_bf16x2(r[4], r[5]), pack_bf16x2(r[6], r[7])};
+        } else {
+            out = u32x4_store{__float_as_uint(r[0]), __float_as_uint(r[1]), __float_as_uint(r[2]), __float_as_uint(r[3])};
+        }
+        __builtin_nontemporal_store(out, reinterpret_cast<u32x4_store*>(&Xhat[i]));
+    }
+}
+
 // ---------------------------------------------------------------------------
 // host-side dispatch
 // ---------------------------------------------------------------------------
@@ -448,6 +487,12 @@ hipError_t reconstruct_any(const void* S, const float* v, void* Xhat, int64_t n_
         hipLaunchKernelGGL((reconstruct_vec_kernel<E, 8>), dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
                            static_cast<const typename E::type*>(S), v, static_cast<uint4*>(Xhat), n_sub,
                            static_cast<int>(vps));
+    } else if (vec_ok && n_elem % E::kPerVec == 0 && d <= 8192) {
+        const int64_t n_vec = n_elem / E::kPerVec;
+        const int grid = grid_for(ceil_div(n_vec, kBlock * 4), 1, cfg.num_cus * 8);
+        hipLaunchKernelGGL((reconstruct_straddle_kernel<E>), dim3(grid), dim3(kBlock), static_cast<size_t>(d) * 4, st,
+                           static_cast<const typename E::type*>(S), v, static_cast<uint4*>(Xhat), n_vec, n_sub,
+                           static_cast<int>(d));
     } else {
         const int grid = grid_for(ceil_div(n_elem, kBlock), 1, cfg.max_blocks * 4);
         hipLaunchKernelGGL((reconstruct_generic_kernel<E>), dim3(grid), dim3(kBlock), 0, st,

@@ -114,6 +114,9 @@ def test_compress_unaligned_views_take_generic_path(vl):
 @pytest.mark.parametrize("N,D,d,dtype", [
     (256, 64, 16, wl.F32), (33, 96, 32, wl.BF16), (100, 768, 64, wl.BF16), (7, 60, 12, wl.BF16),
     (9, 63, 7, wl.F32), (5, 33, 1, wl.F32), (3, 2048, 1024, wl.BF16),
+    # vectors that straddle sub-tokens (d not a multiple of the vector width, Xhat a whole number of vectors)
+    (300, 11008, 43, wl.BF16), (150, 13824, 54, wl.BF16), (64, 24, 3, wl.BF16), (8, 9, 9, wl.BF16), (2048, 8, 1, wl.BF16),
+    (300, 2752, 43, wl.F32), (4, 63, 7, wl.F32), (16, 20, 2, wl.F32), (40, 12000, 6000, wl.BF16),
 ])
 def test_reconstruct_matches_oracle(vl, N, D, d, dtype):
     M = D // d
