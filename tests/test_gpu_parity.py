@@ -150,6 +150,9 @@ def test_projection_is_idempotent_on_gpu(vl):
     (77, 63, 7, wl.F32), (40, 33, 1, wl.F32), (3, 3000, 3000, wl.BF16),
     (700, 72, 24, wl.BF16), (333, 3 * 344, 344, wl.BF16), (210, 2 * 344, 344, wl.F32), (90, 2 * 1032, 1032, wl.BF16),
     (64, 2040, 2040, wl.BF16),
+    # sub-token sizes the vector kernel cannot take, X a whole number of 16-byte vectors: column sums from LDS tiles
+    (300, 11008, 43, wl.BF16), (150, 11008, 86, wl.BF16), (96, 13824, 54, wl.BF16), (64, 24, 3, wl.BF16),
+    (8, 2 * 250, 250, wl.BF16), (300, 2752, 43, wl.F32), (52, 300, 100, wl.F32), (2048, 8, 1, wl.BF16), (5000, 86, 43, wl.BF16),
 ])
 def test_init_v_matches_oracle(vl, N, D, d, dtype):
     M = D // d
